@@ -1,0 +1,195 @@
+/*
+ * edgc.h -- C ABI of the MI355X (gfx950) implementation of EDGC's per-step
+ * data-parallel hot path (EDGC: Entropy-driven Dynamic Gradient Compression,
+ * arXiv 2511.10333):
+ *
+ *   1. down-sampled gradient-entropy estimation   (GDS, Sec. IV-B; Eq. (1))
+ *   2. entropy window -> compression rank         (CQM, Theorem 3 with g of
+ *      Theorem 1 / Lemma 1; warm-up Sec. IV-D-2; Algorithm 1, Constraint 2)
+ *   3. rank-r low-rank compress / decompress with an error-feedback residual
+ *      (Sec. II-B, Sec. III-B, Sec. VII; PowerSGD-style subspace iteration)
+ *
+ * Conventions
+ *   - Every function returns an edgc_status (0 = OK, < 0 = error).  No C++
+ *     exception crosses this boundary.
+ *   - "device" pointers are HIP device memory on the context's GPU, owned by
+ *     the caller; "host" pointers are ordinary process memory.  The library
+ *     allocates device memory only in edgc_create (scratch) and frees it in
+ *     edgc_destroy.  Hot calls never allocate, never free and never
+ *     synchronise the stream; they only enqueue work on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - Matrices are row-major.  A gradient G is m x n with leading dimension
+ *     ld (elements); the residual is dense m x n fp32; factors P (m x r) and
+ *     Q (n x r) are fp32 with leading dimensions ldp, ldq >= r.
+ *   - One context serves one stream at a time: calls that share a context
+ *     share its scratch, so overlapping calls on the same context race.
+ *   - Argument errors are reported before anything is launched.
+ */
+#ifndef EDGC_H
+#define EDGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { EDGC_F32 = 0, EDGC_BF16 = 1 } edgc_dtype;
+
+typedef enum {
+    EDGC_OK         =  0,
+    EDGC_EINVAL     = -1,   /* bad argument (null / misaligned pointer, size out of range)  */
+    EDGC_ENOMEM     = -2,   /* allocation failed in edgc_create                            */
+    EDGC_EHIP       = -3,   /* a HIP call failed; see edgc_last_error                      */
+    EDGC_ENOTIMPL   = -4,
+    EDGC_ENONFINITE = -5    /* empty sample, or no finite value in it                      */
+} edgc_status;
+
+typedef struct edgc_ctx edgc_ctx;   /* opaque; owns only scratch memory */
+
+/* Creates a context on GPU `hip_device` with scratch sized for histograms of
+ * up to max_bins bins and matrices of up to max_rows x max_cols at rank
+ * <= max_rank (max_rank <= 128).  *out is NULL on failure. */
+int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, uint32_t max_rank,
+                uint64_t max_rows, uint64_t max_cols);
+int edgc_destroy(edgc_ctx* ctx);
+/* Message of the last failing call on this context (context-owned string). */
+const char* edgc_last_error(const edgc_ctx* ctx);
+
+/* ------------------------------------------------------------------------
+ * 1. Gradient entropy of a down-sampled buffer (GDS, Sec. IV-B: "selects a
+ *    data subset ... based on a gradient sampling rate beta"; entropy as in
+ *    Definition 1 / Eq. (1), estimated with an equal-width histogram).
+ *
+ *    Sample: element i of the flat buffer is taken iff
+ *        ((i / chunk) mod stride) == slot,  slot = mix64(seed, step) mod stride,
+ *    stride = 1/beta; mix64(s, c) is the splitmix64 output function applied to
+ *    s + 0x9E3779B97F4A7C15 * (c + 1).
+ *    Bins: B equal-width bins over [lo, hi] = range of the finite sample (or
+ *    the caller's range); index = trunc((x - lo) * (B / (hi - lo))) computed in
+ *    fp32 with separately rounded subtract / divide / multiply, clamped to
+ *    [0, B-1]; hi == lo puts everything in bin 0.  NaN/Inf are skipped and
+ *    counted.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    double   H_bits;        /* -sum p_i log2 p_i over the B bins                          */
+    double   h_diff_nats;   /* H_bits*ln2 + ln((hi-lo)/B): histogram estimate of Eq. (1); */
+                            /* this is what Theorem 3 consumes; -inf when hi == lo        */
+    float    lo, hi;
+    uint64_t n_sampled;     /* elements selected by the predicate                         */
+    uint64_t n_nonfinite;   /* of those, skipped as NaN/Inf                               */
+    int32_t  status;        /* EDGC_OK, or EDGC_ENONFINITE when no finite sample existed  */
+    int32_t  _pad;
+} edgc_entropy_result;
+
+/* grad: device, n_elems of dtype.  range_lo_hi_or_null: host float[2] or NULL.
+ * out: host; written by an asynchronous device-to-host copy on `hip_stream`,
+ * valid once the stream has been synchronised (pinned memory keeps the call
+ * fully asynchronous).  counts_out_or_null: device, `bins` uint64 counters.
+ * Errors: EDGC_EINVAL for null ctx/grad/out, stride == 0, chunk == 0,
+ * bins == 0 or > max_bins, lo > hi; EDGC_ENONFINITE when the predicate selects
+ * no element (known on the host).  A sample with no finite value is reported
+ * in out->status. */
+int edgc_entropy_estimate(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint64_t n_elems,
+                          uint64_t stride, uint32_t chunk, uint64_t seed, uint64_t step,
+                          uint32_t bins, const float* range_lo_hi_or_null,
+                          edgc_entropy_result* out, uint64_t* counts_out_or_null,
+                          void* hip_stream);
+
+/* Writes the sampled element indices, ascending, to idx_out (device, capacity
+ * `cap` entries) and their number to *n_out (host, known without the GPU).
+ * Same predicate as edgc_entropy_estimate. */
+int edgc_sample_indices(edgc_ctx* ctx, uint64_t n_elems, uint64_t stride, uint32_t chunk,
+                        uint64_t seed, uint64_t step, uint64_t* idx_out, uint64_t cap,
+                        uint64_t* n_out, void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * 2. Window of entropies -> rank.  Pure host code, deterministic, no GPU.
+ *    H_mean = mean of the window (Sec. IV-D-3).  The first call stores it as
+ *    the reference H_ref and returns rank 0.  Later calls evaluate Theorem 3
+ *        r_new = g^{-1}( exp(H_ref - H_mean) * g(r_ref) ),
+ *    g(r; m, n) = sqrt(sum of the min(m,n)-r smallest mid-point quantiles of
+ *    the Marchenko-Pastur law of Lemma 1) (Theorem 1), g^{-1}(t) = smallest r
+ *    with g(r) <= t.  Warm-up (Sec. IV-D-2): rank 0 until r_new < r_max and
+ *    iters_seen >= min_warmup_frac * total_iters; compression then starts from
+ *    r_prev = r_ref.  Algorithm 1: move r_prev towards r_new by at most
+ *    step_limit (Constraint 2), clamp to [r_min, r_max], emit the smallest
+ *    allowed rank >= r_prev (or r_prev itself when no set is given), and
+ *    T_com = eta * rank.  Entropies are the h_diff_nats values above.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    uint32_t m, n;              /* reference matrix shape for g(r; m, n)                  */
+    uint32_t r_min, r_max;      /* rank bounds, 1 <= r_min <= r_max <= min(m, n)          */
+    uint32_t step_limit;        /* s of Constraint 2 (paper: 8)                           */
+    const uint32_t* allowed;    /* host, ascending, or NULL                               */
+    uint32_t n_allowed;
+    double   eta;               /* T_com(r) = eta * r (Sec. IV-D-1); 0 => T_com = 0       */
+    uint64_t total_iters;
+    double   min_warmup_frac;   /* paper: 0.10                                            */
+    uint32_t r_ref;             /* r0 of Theorem 3; 0 => r_max (the paper's choice)       */
+} edgc_rank_params;
+
+typedef struct {                /* caller-owned plain data; zero-initialise before use    */
+    int32_t  have_ref;
+    int32_t  compressing;
+    double   H_ref;
+    double   r_prev;            /* un-snapped state of Algorithm 1                        */
+    uint64_t iters_seen;
+} edgc_rank_state;
+
+typedef struct {
+    uint32_t rank;              /* 0 => warm-up: send uncompressed                        */
+    uint32_t _pad;
+    double   r_unclamped;       /* r_new before step limit and clamp                      */
+    double   H_mean;
+    double   T_com;
+} edgc_rank_decision;
+
+/* Errors: EDGC_EINVAL for null pointers, k == 0, inconsistent bounds or a
+ * non-ascending allowed set; EDGC_ENONFINITE for a NaN/Inf entropy. */
+int edgc_select_rank(edgc_rank_state* state, const double* H_window, uint32_t k,
+                     uint64_t iters_in_window, const edgc_rank_params* params,
+                     edgc_rank_decision* out);
+
+/* ------------------------------------------------------------------------
+ * 3. Rank-r compressor with error feedback (Sec. II-B: power iteration and
+ *    orthogonalisation give the low-rank factors; Sec. III-B / VII: error
+ *    feedback).  One call of edgc_compress does, power_iters times,
+ *        D = G + E_old (first iteration only; D replaces E_old in `residual`)
+ *        P = D Q;  P <- orthonormal columns (QR Q-factor, positive diagonal R)
+ *        Q = D^T P
+ *    and edgc_decompress does  M^ = P Q^T -> grad_out,  E_new = D - M^ in
+ *    `residual`.  With EDGC_BF16 the gradient and grad_out are bf16, the
+ *    contraction operands are rounded to bf16 (nearest-even) and accumulated
+ *    in fp32, and E_new = D - widen(bf16(M^)).  With EDGC_F32 operands are
+ *    split into two bf16 planes (three MFMAs per product, ~2^-17 relative).
+ * ------------------------------------------------------------------------ */
+
+/* Fills columns [col_begin, col_end) of Q (device, n x ldq fp32) with seeded
+ * N(0,1): element (j, c) is a pure function of (seed, j, c) -- Box-Muller on
+ * two 53-bit uniforms from mix64(seed, 2k), mix64(seed, 2k+1), k = j*2^32 + c. */
+int edgc_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t col_begin,
+                uint32_t col_end, uint64_t seed, void* hip_stream);
+
+/* grad: device m x n (ld) of dtype.  residual: device m x n fp32, in: E_old
+ * (ignored when residual_is_zero != 0), out: D.  Q: device n x r (ldq), in:
+ * warm start, out: D^T P.  P: device m x r (ldp), out: orthonormal columns.
+ * Errors: EDGC_EINVAL for null pointers, r == 0, r > min(m, n), r > max_rank,
+ * m > max_rows, n > max_cols, ld < n, ldp/ldq < r, power_iters == 0, or P/Q
+ * not 16-byte aligned with ldp/ldq multiples of 4.
+ * A column of P that is numerically dependent on the previous ones (pivot of
+ * the scaled Gram matrix below 1e-11) is set to zero. */
+int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
+                  uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
+                  float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, void* hip_stream);
+
+/* residual: in D, out E_new.  grad_out: device m x n (ld) of dtype; may alias
+ * the gradient passed to edgc_compress. */
+int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                    uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
+                    edgc_dtype dtype, uint64_t ld, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EDGC_H */

@@ -1,0 +1,268 @@
+"""ctypes binding with the same names as the C ABI (``include/edgc.h``).
+
+Argument marshalling only: every step of the path runs inside the library's
+kernels.  There is no fallback: if ``libedgc.so`` is missing or fails to load,
+importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+F32, BF16 = 0, 1
+OK, EINVAL, ENOMEM, EHIP, ENOTIMPL, ENONFINITE = 0, -1, -2, -3, -4, -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libedgc.so")
+
+
+class EdgcError(RuntimeError):
+    def __init__(self, code: int, what: str, detail: str = ""):
+        super().__init__(f"{what}: edgc status {code}" + (f" ({detail})" if detail else ""))
+        self.code = code
+
+
+class _EntropyResult(C.Structure):
+    _fields_ = [("H_bits", C.c_double), ("h_diff_nats", C.c_double), ("lo", C.c_float),
+                ("hi", C.c_float), ("n_sampled", C.c_uint64), ("n_nonfinite", C.c_uint64),
+                ("status", C.c_int32), ("_pad", C.c_int32)]
+
+
+class _RankParams(C.Structure):
+    _fields_ = [("m", C.c_uint32), ("n", C.c_uint32), ("r_min", C.c_uint32), ("r_max", C.c_uint32),
+                ("step_limit", C.c_uint32), ("allowed", C.POINTER(C.c_uint32)),
+                ("n_allowed", C.c_uint32), ("eta", C.c_double), ("total_iters", C.c_uint64),
+                ("min_warmup_frac", C.c_double), ("r_ref", C.c_uint32)]
+
+
+class _RankState(C.Structure):
+    _fields_ = [("have_ref", C.c_int32), ("compressing", C.c_int32), ("H_ref", C.c_double),
+                ("r_prev", C.c_double), ("iters_seen", C.c_uint64)]
+
+
+class _RankDecision(C.Structure):
+    _fields_ = [("rank", C.c_uint32), ("_pad", C.c_uint32), ("r_unclamped", C.c_double),
+                ("H_mean", C.c_double), ("T_com", C.c_double)]
+
+
+ENTROPY_RESULT_BYTES = C.sizeof(_EntropyResult)
+
+_lib: Optional[C.CDLL] = None
+
+
+def load_library() -> C.CDLL:
+    """Loads the in-tree ``libedgc.so``; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    L = C.CDLL(path)
+    u64, u32, vp, i32 = C.c_uint64, C.c_uint32, C.c_void_p, C.c_int
+    L.edgc_create.restype = i32
+    L.edgc_create.argtypes = [C.POINTER(vp), i32, u32, u32, u64, u64]
+    L.edgc_destroy.restype = i32
+    L.edgc_destroy.argtypes = [vp]
+    L.edgc_last_error.restype = C.c_char_p
+    L.edgc_last_error.argtypes = [vp]
+    L.edgc_entropy_estimate.restype = i32
+    L.edgc_entropy_estimate.argtypes = [vp, vp, i32, u64, u64, u32, u64, u64, u32, vp, vp, vp, vp]
+    L.edgc_sample_indices.restype = i32
+    L.edgc_sample_indices.argtypes = [vp, u64, u64, u32, u64, u64, vp, u64, C.POINTER(u64), vp]
+    L.edgc_select_rank.restype = i32
+    L.edgc_select_rank.argtypes = [C.POINTER(_RankState), vp, u32, u64, C.POINTER(_RankParams),
+                                   C.POINTER(_RankDecision)]
+    L.edgc_init_q.restype = i32
+    L.edgc_init_q.argtypes = [vp, vp, u32, u32, u32, u32, u64, vp]
+    L.edgc_compress.restype = i32
+    L.edgc_compress.argtypes = [vp, vp, i32, u32, u32, u64, vp, i32, vp, u32, vp, u32, u32, u32, vp]
+    L.edgc_decompress.restype = i32
+    L.edgc_decompress.argtypes = [vp, vp, u32, vp, u32, u32, u32, u32, vp, vp, i32, u64, vp]
+    _lib = L
+    return L
+
+
+@dataclass
+class EntropyResult:
+    H_bits: float
+    h_diff_nats: float
+    lo: float
+    hi: float
+    n_sampled: int
+    n_nonfinite: int
+    status: int
+
+    @staticmethod
+    def from_buffer(buf) -> "EntropyResult":
+        """Decode the raw result struct (e.g. a pinned uint8 tensor's bytes)."""
+        r = _EntropyResult.from_buffer_copy(bytes(buf))
+        return EntropyResult(r.H_bits, r.h_diff_nats, r.lo, r.hi, int(r.n_sampled),
+                             int(r.n_nonfinite), int(r.status))
+
+
+@dataclass
+class RankParams:
+    m: int
+    n: int
+    r_min: int
+    r_max: int
+    step_limit: int = 8
+    allowed: Optional[Sequence[int]] = None
+    eta: float = 0.0
+    total_iters: int = 0
+    min_warmup_frac: float = 0.10
+    r_ref: int = 0
+
+
+@dataclass
+class RankState:
+    have_ref: int = 0
+    compressing: int = 0
+    H_ref: float = 0.0
+    r_prev: float = 0.0
+    iters_seen: int = 0
+
+
+@dataclass
+class RankDecision:
+    rank: int
+    r_unclamped: float
+    H_mean: float
+    T_com: float
+
+
+def select_rank(state: RankState, H_window: Sequence[float], iters_in_window: int,
+                prm: RankParams) -> RankDecision:
+    """edgc_select_rank: host-only; mutates ``state``."""
+    L = load_library()
+    H = (C.c_double * max(len(H_window), 1))(*[float(h) for h in H_window])
+    p = _RankParams(prm.m, prm.n, prm.r_min, prm.r_max, prm.step_limit, None, 0, prm.eta,
+                    prm.total_iters, prm.min_warmup_frac, prm.r_ref)
+    keep = None
+    if prm.allowed:
+        keep = (C.c_uint32 * len(prm.allowed))(*prm.allowed)
+        p.allowed = C.cast(keep, C.POINTER(C.c_uint32))
+        p.n_allowed = len(prm.allowed)
+    st = _RankState(state.have_ref, state.compressing, state.H_ref, state.r_prev, state.iters_seen)
+    dec = _RankDecision()
+    rc = L.edgc_select_rank(C.byref(st), C.cast(H, C.c_void_p), len(H_window), iters_in_window,
+                            C.byref(p), C.byref(dec))
+    if rc != OK:
+        raise EdgcError(rc, "edgc_select_rank")
+    state.have_ref, state.compressing = st.have_ref, st.compressing
+    state.H_ref, state.r_prev, state.iters_seen = st.H_ref, st.r_prev, int(st.iters_seen)
+    return RankDecision(int(dec.rank), dec.r_unclamped, dec.H_mean, dec.T_com)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("gradient tensors must be float32 or bfloat16")
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+class Context:
+    """Owns an ``edgc_ctx``.  Methods take torch CUDA tensors (device memory only) and
+    enqueue on ``stream`` (default: torch's current stream); nothing synchronises."""
+
+    def __init__(self, device: int = 0, max_bins: int = 65536, max_rank: int = 128,
+                 max_rows: int = 20480, max_cols: int = 20480):
+        self._L = load_library()
+        h = C.c_void_p()
+        rc = self._L.edgc_create(C.byref(h), device, max_bins, max_rank, max_rows, max_cols)
+        if rc != OK:
+            raise EdgcError(rc, "edgc_create")
+        self._h = h
+        self.device = device
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self._L.edgc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int, what: str) -> None:
+        if rc != OK:
+            msg = self._L.edgc_last_error(self._h)
+            raise EdgcError(rc, what, msg.decode() if msg else "")
+
+    # -- entropy -----------------------------------------------------------
+    def entropy_estimate_async(self, grad, stride: int, chunk: int, seed: int, step: int, bins: int,
+                               out_pinned, value_range=None, counts_out=None, stream=None) -> None:
+        """edgc_entropy_estimate.  ``out_pinned``: pinned uint8 CPU tensor of
+        ENTROPY_RESULT_BYTES bytes, valid after the stream is synchronised."""
+        rng = None
+        if value_range is not None:
+            rng = (C.c_float * 2)(float(value_range[0]), float(value_range[1]))
+        rc = self._L.edgc_entropy_estimate(
+            self._h, grad.data_ptr(), _dtype_code(grad), grad.numel(), stride, chunk, seed, step, bins,
+            C.cast(rng, C.c_void_p) if rng is not None else None, out_pinned.data_ptr(),
+            counts_out.data_ptr() if counts_out is not None else None, _stream_handle(stream))
+        self._check(rc, "edgc_entropy_estimate")
+
+    def entropy_estimate(self, grad, stride: int, chunk: int, seed: int, step: int, bins: int,
+                         value_range=None, counts_out=None, stream=None) -> EntropyResult:
+        """Blocking convenience wrapper: runs the estimate and synchronises the stream."""
+        import torch
+        out = torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True)
+        self.entropy_estimate_async(grad, stride, chunk, seed, step, bins, out, value_range,
+                                    counts_out, stream)
+        (stream if stream is not None else torch.cuda.current_stream()).synchronize()
+        return EntropyResult.from_buffer(out.numpy().tobytes())
+
+    def sample_indices(self, n_elems: int, stride: int, chunk: int, seed: int, step: int,
+                       idx_out=None, stream=None) -> int:
+        """edgc_sample_indices.  Returns the sample size; fills ``idx_out`` (int64 CUDA tensor)."""
+        n = C.c_uint64(0)
+        rc = self._L.edgc_sample_indices(
+            self._h, n_elems, stride, chunk, seed, step,
+            idx_out.data_ptr() if idx_out is not None else None,
+            idx_out.numel() if idx_out is not None else 0, C.byref(n), _stream_handle(stream))
+        self._check(rc, "edgc_sample_indices")
+        return int(n.value)
+
+    # -- compressor --------------------------------------------------------
+    def init_q(self, Q, col_begin: int, col_end: int, seed: int, stream=None) -> None:
+        assert Q.dim() == 2 and Q.is_contiguous()
+        rc = self._L.edgc_init_q(self._h, Q.data_ptr(), Q.shape[0], Q.shape[1], col_begin, col_end,
+                                 seed, _stream_handle(stream))
+        self._check(rc, "edgc_init_q")
+
+    def compress(self, grad, residual, residual_is_zero: bool, Q, P, r: int, power_iters: int = 1,
+                 stream=None) -> None:
+        """edgc_compress.  grad (m, n) fp32/bf16 (row stride = grad.stride(0)); residual (m, n)
+        fp32 contiguous; Q (n, ldq) and P (m, ldp) fp32 contiguous with ldq, ldp >= r."""
+        m, n = grad.shape
+        rc = self._L.edgc_compress(
+            self._h, grad.data_ptr(), _dtype_code(grad), m, n, grad.stride(0), residual.data_ptr(),
+            1 if residual_is_zero else 0, Q.data_ptr(), Q.shape[1], P.data_ptr(), P.shape[1], r,
+            power_iters, _stream_handle(stream))
+        self._check(rc, "edgc_compress")
+
+    def decompress(self, P, Q, r: int, residual, grad_out, stream=None) -> None:
+        """edgc_decompress.  residual (m, n) holds D on entry and E_new on return."""
+        m, n = grad_out.shape
+        rc = self._L.edgc_decompress(
+            self._h, P.data_ptr(), P.shape[1], Q.data_ptr(), Q.shape[1], m, n, r, residual.data_ptr(),
+            grad_out.data_ptr(), _dtype_code(grad_out), grad_out.stride(0), _stream_handle(stream))
+        self._check(rc, "edgc_decompress")

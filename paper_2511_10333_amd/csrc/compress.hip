@@ -1,0 +1,1013 @@
+// Rank-r low-rank compressor with error feedback on gfx950 (Sec. II-B: power
+// iteration + orthogonalisation; Sec. III-B / VII: error feedback).
+//
+//   k_pass_p        D = G + E_old (written back), P_partial = D Q    (split over columns)
+//   k_reduce_gram   P = sum of partials; per-block Gram P^T P in fp64
+//   k_gram_sum      Gram = sum of the per-block Grams (only when there are many)
+//   k_chol          scaled Cholesky of the Gram in fp64, inverse factor R^-1
+//   k_apply         P^ = P R^-1 (fp64), plus a transposed bf16 operand copy of P^
+//   k_pass_q        Q_partial = D^T P^                                (split over rows)
+//   k_reduce_q      Q = sum of partials
+//   k_decompress    M^ = P^ Q^T -> grad_out, E_new = D - M^
+//
+// All contractions run on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.
+// bf16 gradients use one bf16 plane per operand (operands rounded to nearest
+// even); fp32 gradients use two planes x = hi + lo (hi = bf16(x), lo =
+// bf16(x - hi)) and three MFMAs per product (hi*hi, hi*lo, lo*hi), which keeps
+// ~17 bits per operand.  The passes are HBM-bound (2r/(b+8), r/2 and r/6 flop
+// per byte), so the matrix is streamed exactly once per pass with 16-byte
+// accesses and everything else (factors, partials) stays in L2 / LDS.
+//
+// MFMA 32x32x16 operand layout (64 lanes): lane l supplies A[i = l%32][k = 8*(l/32) .. +8]
+// and B[k = 8*(l/32) .. +8][j = l%32]; accumulator register v of lane l holds
+// D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].
+#include "edgc_internal.h"
+
+#include <algorithm>
+#include <math.h>
+
+namespace edgc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kLdsRow = 144;   // 128 B of operand data + 16 B pad: conflict-free 16-byte reads
+
+__device__ __forceinline__ float bf16_bits_widen(uint32_t h) { return __uint_as_float(h << 16); }
+
+// x -> planes: p[0] = bf16(x); with two planes p[1] = bf16(x - p[0])
+template <int NP>
+__device__ __forceinline__ void to_planes(float x, __bf16 (&p)[NP])
+{
+    p[0] = static_cast<__bf16>(x);
+    if constexpr (NP == 2) p[1] = static_cast<__bf16>(x - static_cast<float>(p[0]));
+}
+
+template <int NP>
+__device__ __forceinline__ f32x16 mma(const bf16x8 (&a)[NP], const bf16x8 (&b)[NP], f32x16 acc)
+{
+    if constexpr (NP == 2) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[1], acc, 0, 0, 0);
+    }
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], acc, 0, 0, 0);
+}
+
+// blockIdx -> logical tile so that the blocks resident on one XCD (dispatch is
+// round-robin over 8 XCDs) work on neighbouring tiles and share factor slices in L2.
+__device__ __forceinline__ uint32_t xcd_swizzle(uint32_t bid, uint32_t total)
+{
+    return (total % 8u == 0u) ? (bid % 8u) * (total / 8u) + bid / 8u : bid;
+}
+
+// ---------------------------------------------------------------------------
+// seeded N(0,1) start of Q
+// ---------------------------------------------------------------------------
+__global__ void k_init_q(float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1, uint64_t seed)
+{
+    const uint32_t w = c1 - c0;
+    const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (t >= static_cast<uint64_t>(n) * w) return;
+    const uint32_t j = static_cast<uint32_t>(t / w), c = c0 + static_cast<uint32_t>(t % w);
+    const uint64_t k = (static_cast<uint64_t>(j) << 32) | c;
+    const uint64_t z1 = mix64(seed, 2ull * k), z2 = mix64(seed, 2ull * k + 1ull);
+    const double u1 = (static_cast<double>(z1 >> 11) + 0.5) * (1.0 / 9007199254740992.0);
+    const double u2 = static_cast<double>(z2 >> 11) * (1.0 / 9007199254740992.0);
+    Q[static_cast<size_t>(j) * ldq + c] =
+        static_cast<float>(sqrt(-2.0 * log(u1)) * cos(6.28318530717958647692 * u2));
+}
+
+// ---------------------------------------------------------------------------
+// P-pass:  D = G + E_old,  P_partial[s] = D[:, k-range s] * Q[k-range s, :]
+// Block: 4 waves x 32 rows = 128 rows; k-step BK = 64 (one plane) or 32 (two planes).
+// ---------------------------------------------------------------------------
+template <int NP> struct GradElem { using type = float; };
+template <> struct GradElem<1> { using type = uint16_t; };
+
+template <int NP, bool VECOK>
+__device__ __forceinline__ void load_grad4(const typename GradElem<NP>::type* __restrict__ G,
+                                           uint64_t ldg, uint32_t row, uint32_t col, uint32_t m,
+                                           uint32_t col_end, float (&v)[4])
+{
+    v[0] = v[1] = v[2] = v[3] = 0.0f;
+    if (G == nullptr || row >= m || col >= col_end) return;   // null gradient: D is re-read as it stands
+    const auto* p = G + static_cast<uint64_t>(row) * ldg + col;
+    if (VECOK && col + 4 <= col_end) {
+        if constexpr (NP == 2) {
+            const float4 q = *reinterpret_cast<const float4*>(p);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+            const uint2 q = *reinterpret_cast<const uint2*>(p);
+            v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+            v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < col_end) {
+                if constexpr (NP == 2) v[e] = p[e];
+                else v[e] = bf16_bits_widen(p[e]);
+            }
+    }
+}
+
+template <bool VECOK>
+__device__ __forceinline__ void load_f32x4(const float* __restrict__ base, uint64_t ld, uint32_t row,
+                                           uint32_t col, uint32_t rows, uint32_t col_end, float (&v)[4])
+{
+    v[0] = v[1] = v[2] = v[3] = 0.0f;
+    if (row >= rows || col >= col_end) return;
+    const float* p = base + static_cast<uint64_t>(row) * ld + col;
+    if (VECOK && col + 4 <= col_end) {
+        const float4 q = *reinterpret_cast<const float4*>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (col + e < col_end) v[e] = p[e];
+    }
+}
+
+template <bool VECOK>
+__device__ __forceinline__ void store_f32x4(float* __restrict__ base, uint64_t ld, uint32_t row,
+                                            uint32_t col, uint32_t rows, uint32_t col_end,
+                                            const float (&v)[4])
+{
+    if (row >= rows || col >= col_end) return;
+    float* p = base + static_cast<uint64_t>(row) * ld + col;
+    if (VECOK && col + 4 <= col_end) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (col + e < col_end) p[e] = v[e];
+    }
+}
+
+template <int NP, int RT, bool VECOK>
+__global__ __launch_bounds__(256) void k_pass_p(
+    const typename GradElem<NP>::type* __restrict__ G, uint64_t ldg, float* __restrict__ E, int e_zero,
+    const float* __restrict__ Q, uint32_t ldq, float* __restrict__ part, uint32_t m, uint32_t n,
+    uint32_t r, uint32_t kper, uint32_t RB, uint32_t S)
+{
+    constexpr int BK  = (NP == 1) ? 64 : 32;       // k elements per step
+    constexpr int TPR = BK / 4;                    // threads per tile row
+    constexpr int RPP = 256 / TPR;                 // rows per load pass
+    constexpr int PA  = 128 / RPP;                 // load passes for the 128-row tile
+    constexpr int RP  = RT * 32;                   // padded rank
+    constexpr int NQB = (BK / 4) * (RP / 4);       // 4x4 micro-blocks of the Q tile
+    constexpr int PQ  = (NQB + 255) / 256;
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds[(128 + RP) * kLdsRow];
+    unsigned char* ldsA = lds;
+    unsigned char* ldsB = lds + 128 * kLdsRow;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t lid = xcd_swizzle(blockIdx.x, RB * S);
+    const uint32_t s = lid / RB, rb = lid % RB;
+    const uint32_t row0 = rb * 128;
+    const uint32_t k_begin = s * kper;
+    const uint32_t k_end = min(n, k_begin + kper);
+
+    const int a_row = tid / TPR, a_col = (tid % TPR) * 4;
+
+    float d[PA][4];
+    float qv[PQ][4][4];
+
+    auto fetch = [&](uint32_t k0) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            const uint32_t row = row0 + p * RPP + a_row, col = k0 + a_col;
+            float g[4], e[4] = {0.f, 0.f, 0.f, 0.f};
+            load_grad4<NP, VECOK>(G, ldg, row, col, m, k_end, g);
+            if (!e_zero) load_f32x4<VECOK>(E, n, row, col, m, k_end, e);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) d[p][x] = g[x] + e[x];
+        }
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int bi = tid + p * 256;
+            const int kb4 = bi / (RP / 4), cb4 = bi % (RP / 4);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                qv[p][kk][0] = qv[p][kk][1] = qv[p][kk][2] = qv[p][kk][3] = 0.0f;
+                const uint32_t k = k0 + kb4 * 4 + kk;
+                if (bi < NQB && k < k_end && static_cast<uint32_t>(cb4 * 4) < ldq) {
+                    const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<uint64_t>(k) * ldq + cb4 * 4);
+                    qv[p][kk][0] = q.x; qv[p][kk][1] = q.y; qv[p][kk][2] = q.z; qv[p][kk][3] = q.w;
+                }
+            }
+        }
+    };
+
+    f32x16 acc[RT];
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;
+
+    if (k_begin < k_end) fetch(k_begin);
+    for (uint32_t k0 = k_begin; k0 < k_end; k0 += BK) {
+        __syncthreads();                         // previous step's LDS reads are done
+        // D back to the residual buffer, operands into LDS
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            const uint32_t row = row0 + p * RPP + a_row, col = k0 + a_col;
+            store_f32x4<VECOK>(E, n, row, col, m, k_end, d[p]);
+            __bf16 pl[4][NP];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) to_planes<NP>(d[p][x], pl[x]);
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+                bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
+                *reinterpret_cast<bf16x4*>(ldsA + (p * RPP + a_row) * kLdsRow + q * (BK * 2) + a_col * 2) = w;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int bi = tid + p * 256;
+            if (bi < NQB) {
+                const int kb4 = bi / (RP / 4), cb4 = bi % (RP / 4);
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const bool live = static_cast<uint32_t>(cb4 * 4 + cc) < r;
+                    __bf16 pl[4][NP];
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) to_planes<NP>(live ? qv[p][kk][cc] : 0.0f, pl[kk]);
+#pragma unroll
+                    for (int q = 0; q < NP; ++q) {
+                        bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
+                        *reinterpret_cast<bf16x4*>(ldsB + (cb4 * 4 + cc) * kLdsRow + q * (BK * 2) + kb4 * 8) = w;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (k0 + BK < k_end) fetch(k0 + BK);     // next tile's loads fly during the MFMAs
+
+        const unsigned char* pa = ldsA + (wave * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
+        const unsigned char* pb = ldsB + (lane & 31) * kLdsRow + (lane >> 5) * 16;
+#pragma unroll
+        for (int kb = 0; kb < BK / 16; ++kb) {
+            bf16x8 a[NP];
+#pragma unroll
+            for (int q = 0; q < NP; ++q) a[q] = *reinterpret_cast<const bf16x8*>(pa + q * (BK * 2) + kb * 32);
+#pragma unroll
+            for (int ct = 0; ct < RT; ++ct) {
+                bf16x8 b[NP];
+#pragma unroll
+                for (int q = 0; q < NP; ++q)
+                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * kLdsRow + q * (BK * 2) + kb * 32);
+                acc[ct] = mma<NP>(a, b, acc[ct]);
+            }
+        }
+    }
+
+    // partial P of this k-range: part[s][row][c], c over the padded rank
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = row0 + wave * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            if (row < m)
+                part[(static_cast<size_t>(s) * m + row) * RP + ct * 32 + (lane & 31)] = acc[ct][v];
+        }
+}
+
+// ---------------------------------------------------------------------------
+// P = sum_s partial[s];  per-block Gram (64 rows) in fp64
+// ---------------------------------------------------------------------------
+template <int TA>
+__global__ __launch_bounds__(256) void k_reduce_gram(const float* __restrict__ part, uint32_t S,
+                                                     uint32_t m, uint32_t RP, uint32_t r,
+                                                     float* __restrict__ P, uint32_t ldp,
+                                                     double* __restrict__ gram_part)
+{
+    constexpr int CW = 16 * TA;
+    __shared__ float Ps[64][CW + 1];
+    const int tid = threadIdx.x;
+    const uint32_t row0 = blockIdx.x * 64;
+    for (int idx = tid; idx < 64 * CW; idx += 256) {
+        const int i = idx / CW, c = idx % CW;
+        const uint32_t row = row0 + i;
+        float v = 0.0f;
+        if (row < m && static_cast<uint32_t>(c) < r) {
+            for (uint32_t s = 0; s < S; ++s) v += part[(static_cast<size_t>(s) * m + row) * RP + c];
+            P[static_cast<size_t>(row) * ldp + c] = v;
+        }
+        Ps[i][c] = v;
+    }
+    __syncthreads();
+    const int ta = tid / 16, tb = tid % 16;
+    double acc[TA][TA];
+#pragma unroll
+    for (int x = 0; x < TA; ++x)
+#pragma unroll
+        for (int y = 0; y < TA; ++y) acc[x][y] = 0.0;
+#pragma unroll 2
+    for (int i = 0; i < 64; ++i) {
+        double a[TA], b[TA];
+#pragma unroll
+        for (int x = 0; x < TA; ++x) { a[x] = Ps[i][ta + 16 * x]; b[x] = Ps[i][tb + 16 * x]; }
+#pragma unroll
+        for (int x = 0; x < TA; ++x)
+#pragma unroll
+            for (int y = 0; y < TA; ++y) acc[x][y] = fma(a[x], b[y], acc[x][y]);
+    }
+    double* out = gram_part + static_cast<size_t>(blockIdx.x) * r * r;
+#pragma unroll
+    for (int x = 0; x < TA; ++x)
+#pragma unroll
+        for (int y = 0; y < TA; ++y) {
+            const uint32_t a = ta + 16 * x, b = tb + 16 * y;
+            if (a < r && b < r) out[a * r + b] = acc[x][y];
+        }
+}
+
+__global__ void k_gram_sum(const double* __restrict__ gram_part, uint32_t nb, uint32_t rr,
+                           double* __restrict__ gram)
+{
+    const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= rr) return;
+    double s = 0.0;
+    for (uint32_t b = 0; b < nb; ++b) s += gram_part[static_cast<size_t>(b) * rr + e];
+    gram[e] = s;
+}
+
+// ---------------------------------------------------------------------------
+// Scaled Cholesky of the Gram matrix and the inverse factor, one block, fp64.
+//   W = P^T P,  D = diag(W)^-1/2,  C = D W D = L L^T,  R = L^T D^-1,  R^-1 = D L^-T
+// A pivot of C below kPivotEps marks a column that is numerically dependent on
+// the previous ones: its P^ column becomes zero and it is left out of later
+// projections.
+// ---------------------------------------------------------------------------
+constexpr double kPivotEps = 1e-11;
+
+__global__ __launch_bounds__(1024) void k_chol(const double* __restrict__ gram_in, uint32_t nb,
+                                               uint32_t r, double* __restrict__ rinv)
+{
+    extern __shared__ double sm[];
+    const uint32_t ld = r + 1;
+    double* L = sm;                    // [r][r+1]
+    double* dsc = sm + static_cast<size_t>(r) * ld;   // [r] column scales
+    double* tmp = dsc + r;             // [r]
+    int* dead = reinterpret_cast<int*>(tmp + r);       // [r]
+    const int tid = threadIdx.x;
+    const uint32_t rr = r * r;
+
+    for (uint32_t e = tid; e < rr; e += 1024) {
+        double s = 0.0;
+        for (uint32_t b = 0; b < nb; ++b) s += gram_in[static_cast<size_t>(b) * rr + e];
+        L[(e / r) * ld + (e % r)] = s;
+    }
+    __syncthreads();
+    for (uint32_t j = tid; j < r; j += 1024) {
+        const double w = L[j * ld + j];
+        dsc[j] = (w > 0.0) ? 1.0 / sqrt(w) : 0.0;
+        dead[j] = 0;
+    }
+    __syncthreads();
+    for (uint32_t e = tid; e < rr; e += 1024) {
+        const uint32_t a = e / r, b = e % r;
+        L[a * ld + b] *= dsc[a] * dsc[b];
+    }
+    __syncthreads();
+
+    // left-looking Cholesky: 8 lanes per row share the dot product over k < j
+    const uint32_t row = tid >> 3, sub = tid & 7;
+    for (uint32_t j = 0; j < r; ++j) {
+        double v = 0.0;
+        if (row >= j && row < r) {
+            for (uint32_t k = sub; k < j; k += 8) v = fma(L[row * ld + k], L[j * ld + k], v);
+        }
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        v += __shfl_xor(v, 4, 64);
+        if (row >= j && row < r && sub == 0) tmp[row] = L[row * ld + j] - v;
+        __syncthreads();
+        const double piv = tmp[j];
+        if (row >= j && row < r && sub == 0) {
+            if (piv > kPivotEps) {
+                const double ljj = sqrt(piv);
+                L[row * ld + j] = (row == j) ? ljj : tmp[row] / ljj;
+            } else {
+                L[row * ld + j] = (row == j) ? 1.0 : 0.0;
+                if (row == j) dead[j] = 1;
+            }
+        }
+        __syncthreads();
+    }
+
+    // X = L^-1 column by column (8 lanes per column, x_k kept in registers of lane k % 8),
+    // then row k of R^-1:  rinv[k][c] = d_k * X[c][k]  for c >= k
+    const uint32_t col = tid >> 3;
+    if (col < r) {
+        double xr[16];                       // X[k][col] for k = 8*t + sub
+#pragma unroll
+        for (int t = 0; t < 16; ++t) xr[t] = 0.0;
+        const bool col_dead = dead[col] != 0;
+        for (uint32_t i = col; i < r; ++i) {
+            double xi;
+            if (i == col) {
+                xi = 1.0 / L[col * ld + col];
+            } else {
+                double v = 0.0;
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {
+                    const uint32_t k = 8 * t + sub;
+                    if (k >= col && k < i) v = fma(L[i * ld + k], xr[t], v);
+                }
+                v += __shfl_xor(v, 1, 64);
+                v += __shfl_xor(v, 2, 64);
+                v += __shfl_xor(v, 4, 64);
+                xi = -v / L[i * ld + i];
+            }
+#pragma unroll
+            for (int t = 0; t < 16; ++t)
+                if (static_cast<uint32_t>(8 * t) + sub == i) xr[t] = xi;
+            if (sub == 0) {
+                const bool zero = col_dead || dead[i] != 0;
+                // entry (k = col, c = i) of R^-1
+                rinv[static_cast<size_t>(col) * r + i] = zero ? 0.0 : dsc[col] * xi;
+            }
+        }
+        // strictly lower part of R^-1 is zero
+        for (uint32_t c = sub; c < col; c += 8) rinv[static_cast<size_t>(col) * r + c] = 0.0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// P^ = P R^-1 in fp64 (64 rows per block), fp32 result in place, and the bf16
+// operand copy Pt[plane][c][i] (i contiguous, rows padded to a multiple of 64)
+// that the Q-pass reads as MFMA B-fragments.
+// ---------------------------------------------------------------------------
+template <int CW, int NP>
+__global__ __launch_bounds__(256) void k_apply(float* __restrict__ P, uint32_t ldp,
+                                               const double* __restrict__ rinv, uint32_t m,
+                                               uint32_t r, __bf16* __restrict__ pt, uint32_t m_pad,
+                                               uint32_t RP)
+{
+    constexpr int NR = 64 * CW / 256;      // rows per thread
+    constexpr int RS = 256 / CW;           // row stride between a thread's rows
+    __shared__ float Ps[64][CW + 1];
+    const int tid = threadIdx.x;
+    const uint32_t row0 = blockIdx.x * 64;
+    for (int idx = tid; idx < 64 * CW; idx += 256) {
+        const int i = idx / CW, c = idx % CW;
+        const uint32_t row = row0 + i;
+        Ps[i][c] = (row < m && static_cast<uint32_t>(c) < r) ? P[static_cast<size_t>(row) * ldp + c] : 0.0f;
+    }
+    __syncthreads();
+    const int c = tid % CW, ih = tid / CW;
+    double acc[NR];
+#pragma unroll
+    for (int x = 0; x < NR; ++x) acc[x] = 0.0;
+    // R^-1 is upper triangular: column c needs k <= c; the wave runs to its largest c
+    const uint32_t cmax = static_cast<uint32_t>(CW >= 64 ? (c | 63) : (CW - 1));
+    const uint32_t kend = min(r, cmax + 1);
+    for (uint32_t k = 0; k < kend; ++k) {
+        const double rk = (static_cast<uint32_t>(c) < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
+#pragma unroll
+        for (int x = 0; x < NR; ++x) acc[x] = fma(static_cast<double>(Ps[ih + RS * x][k]), rk, acc[x]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < NR; ++x) {
+        const int i = ih + RS * x;
+        const float v = static_cast<float>(acc[x]);
+        Ps[i][c] = v;
+        const uint32_t row = row0 + i;
+        if (row < m && static_cast<uint32_t>(c) < r) P[static_cast<size_t>(row) * ldp + c] = v;
+    }
+    __syncthreads();
+    // transposed operand copy: 8 consecutive rows of one column per 16-byte store
+    for (uint32_t idx = tid; idx < RP * 8; idx += 256) {
+        const uint32_t cc = idx / 8, q = idx % 8;
+        bf16x8 w[NP];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v = (cc < static_cast<uint32_t>(CW)) ? Ps[8 * q + e][cc] : 0.0f;
+            __bf16 pl[NP];
+            to_planes<NP>(v, pl);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) w[p][e] = pl[p];
+        }
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+            *reinterpret_cast<bf16x8*>(pt + (static_cast<size_t>(p) * RP + cc) * m_pad + row0 + 8 * q) = w[p];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Q-pass:  Q_partial[s] = D[row-range s, :]^T * P^[row-range s, :]
+// Block: 4 waves, all on the same 32*NT columns, each wave on its own 64-row
+// stages; lane (jl, g) loads rows 8g..8g+7 of a 16-row step at columns
+// NT*jl..NT*jl+NT-1, which are the A-fragments (M = column, K = row) as they
+// stand: no transposition of D.  The P^ operand comes from the transposed copy
+// through a wave-private LDS tile.  Waves are summed through LDS at the end.
+// ---------------------------------------------------------------------------
+template <int NT, bool VECOK>
+__device__ __forceinline__ void load_d_rows(const float* __restrict__ D, uint32_t n, uint32_t m,
+                                            uint32_t row_base, uint32_t col, float (&v)[8][NT])
+{
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const uint32_t row = row_base + q;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) v[q][t] = 0.0f;
+        if (row < m && col < n) {
+            const float* p = D + static_cast<uint64_t>(row) * n + col;
+            if (VECOK && col + NT <= n) {
+                if constexpr (NT == 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(p);
+                    v[q][0] = x.x; v[q][1] = x.y; v[q][2] = x.z; v[q][3] = x.w;
+                } else {
+                    const float2 x = *reinterpret_cast<const float2*>(p);
+                    v[q][0] = x.x; v[q][1] = x.y;
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) if (col + t < n) v[q][t] = p[t];
+            }
+        }
+    }
+}
+
+template <int NP, int RT, int NT, bool VECOK>
+__global__ __launch_bounds__(256) void k_pass_q(const float* __restrict__ D,
+                                                const __bf16* __restrict__ pt, uint32_t m_pad,
+                                                float* __restrict__ part, uint32_t m, uint32_t n,
+                                                uint32_t stages_per_split, uint32_t CB, uint32_t S)
+{
+    constexpr int RP = RT * 32;
+    constexpr int ROWB = NP * 128 + 16;              // LDS bytes per column c: 64 rows x NP planes + pad
+    constexpr int WAVE_LDS = RP * ROWB;
+    constexpr int W = 32 * NT;
+    extern __shared__ __attribute__((aligned(16))) unsigned char qlds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int jl = lane & 31, g = lane >> 5;
+    const uint32_t lid = xcd_swizzle(blockIdx.x, CB * S);
+    const uint32_t s = lid / CB, cb = lid % CB;
+    const uint32_t j0 = cb * W;
+    const uint32_t total_stages = m_pad / 64;
+    const uint32_t st_begin = s * stages_per_split;
+    const uint32_t st_end = min(total_stages, st_begin + stages_per_split);
+    unsigned char* my = qlds + wave * WAVE_LDS;
+
+    f32x16 acc[RT][NT];
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ct][t][v] = 0.0f;
+
+    const uint32_t col = j0 + NT * jl;
+    for (uint32_t st = st_begin + wave; st < st_end; st += 4) {
+        const uint32_t i0 = st * 64;
+        // P^ tile: RP columns x 64 rows x NP planes, 16-byte segments, 8 per (column, plane)
+        for (int idx = lane; idx < RP * NP * 8; idx += 64) {
+            const int seg = idx % 8, cp = idx / 8, c = cp % RP, p = cp / RP;
+            const bf16x8 w = *reinterpret_cast<const bf16x8*>(
+                pt + (static_cast<size_t>(p) * RP + c) * m_pad + i0 + seg * 8);
+            *reinterpret_cast<bf16x8*>(my + c * ROWB + p * 128 + seg * 16) = w;
+        }
+        float dv[2][8][NT];
+        load_d_rows<NT, VECOK>(D, n, m, i0 + 8 * g, col, dv[0]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u + 1 < 4) load_d_rows<NT, VECOK>(D, n, m, i0 + 16 * (u + 1) + 8 * g, col, dv[(u + 1) & 1]);
+            bf16x8 a[NT][NP];
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    __bf16 pl[NP];
+                    to_planes<NP>(dv[u & 1][q][t], pl);
+#pragma unroll
+                    for (int p = 0; p < NP; ++p) a[t][p][q] = pl[p];
+                }
+#pragma unroll
+            for (int ct = 0; ct < RT; ++ct) {
+                bf16x8 b[NP];
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+                    b[p] = *reinterpret_cast<const bf16x8*>(my + (ct * 32 + jl) * ROWB + p * 128 + u * 32 + g * 16);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[ct][t] = mma<NP>(a[t], b, acc[ct][t]);
+            }
+        }
+    }
+
+    // sum the four waves: 2,3 -> LDS, 0,1 add; 1 -> LDS, 0 adds
+    constexpr int NACC = RT * NT * 16;
+    float* red = reinterpret_cast<float*>(qlds);
+    __syncthreads();
+    if (wave >= 2) {
+#pragma unroll
+        for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    red[((wave - 2) * NACC + (ct * NT + t) * 16 + v) * 64 + lane] = acc[ct][t][v];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    acc[ct][t][v] += red[(wave * NACC + (ct * NT + t) * 16 + v) * 64 + lane];
+    }
+    __syncthreads();
+    if (wave == 1) {
+#pragma unroll
+        for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    red[((ct * NT + t) * 16 + v) * 64 + lane] = acc[ct][t][v];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    // accumulator (ct, t, v) of lane l: column j = j0 + NT*rho + t with rho = 8*(v/4) + 4*g + v%4,
+    // factor column c = ct*32 + jl  ->  part[s][j][c]
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float x = acc[ct][t][v] + red[((ct * NT + t) * 16 + v) * 64 + lane];
+                const uint32_t j = j0 + NT * (8 * (v / 4) + 4 * g + (v % 4)) + t;
+                if (j < n) part[(static_cast<size_t>(s) * n + j) * RP + ct * 32 + jl] = x;
+            }
+}
+
+__global__ void k_reduce_q(const float* __restrict__ part, uint32_t S, uint32_t n, uint32_t RP,
+                           uint32_t r, float* __restrict__ Q, uint32_t ldq)
+{
+    const uint64_t t = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (t >= static_cast<uint64_t>(n) * RP) return;
+    const uint32_t j = static_cast<uint32_t>(t / RP), c = static_cast<uint32_t>(t % RP);
+    if (c >= r) return;
+    float v = 0.0f;
+    for (uint32_t s = 0; s < S; ++s) v += part[(static_cast<size_t>(s) * n + j) * RP + c];
+    Q[static_cast<size_t>(j) * ldq + c] = v;
+}
+
+// ---------------------------------------------------------------------------
+// Decompress:  M^ = P^ Q^T -> grad_out,  E_new = D - M^ (as transmitted), in place.
+// Block: 4 waves x 32 rows; the wave's P^ rows stay in registers as A-fragments;
+// Q rows of a 64-column stage go through LDS, row 2*jl + ct of the stage at LDS
+// row ct*32 + jl so that every lane ends up with two adjacent columns.
+// ---------------------------------------------------------------------------
+template <int NP, int RT, bool VECOK>
+__global__ __launch_bounds__(256) void k_decompress(
+    const float* __restrict__ P, uint32_t ldp, const float* __restrict__ Q, uint32_t ldq, uint32_t m,
+    uint32_t n, uint32_t r, float* __restrict__ E, void* __restrict__ out_, int out_bf16, uint64_t ldo,
+    uint32_t stages_per_split, uint32_t RB, uint32_t JS)
+{
+    constexpr int KT = RT * 2;                        // 16-wide k blocks over the padded rank
+    constexpr int RP = RT * 32;
+    constexpr int ROWB = NP * RP * 2 + 16;            // LDS bytes per Q row
+    extern __shared__ __attribute__((aligned(16))) unsigned char dlds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int jl = lane & 31, g = lane >> 5;
+    const uint32_t lid = xcd_swizzle(blockIdx.x, RB * JS);
+    const uint32_t js = lid % JS, rb = lid / JS;
+    const uint32_t row0 = rb * 128 + wave * 32;
+
+    // A-fragments: row row0 + jl of P^, k = kb*16 + 8g .. +8
+    bf16x8 a[KT][NP];
+    {
+        const uint32_t row = row0 + jl;
+#pragma unroll
+        for (int kb = 0; kb < KT; ++kb) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t c = kb * 16 + 8 * g + e;
+                v[e] = (row < m && c < r) ? P[static_cast<size_t>(row) * ldp + c] : 0.0f;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                __bf16 pl[NP];
+                to_planes<NP>(v[e], pl);
+#pragma unroll
+                for (int p = 0; p < NP; ++p) a[kb][p][e] = pl[p];
+            }
+        }
+    }
+
+    const uint32_t total_stages = (n + 63) / 64;
+    const uint32_t st_begin = js * stages_per_split;
+    const uint32_t st_end = min(total_stages, st_begin + stages_per_split);
+    for (uint32_t st = st_begin; st < st_end; ++st) {
+        const uint32_t j0 = st * 64;
+        __syncthreads();
+        // stage Q rows j0 .. j0+63: 4 consecutive factor columns per thread
+        for (int idx = tid; idx < 64 * (RP / 4); idx += 256) {
+            const int jj = idx / (RP / 4), c4 = (idx % (RP / 4)) * 4;
+            const uint32_t j = j0 + jj;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (j < n && static_cast<uint32_t>(c4) < ldq) {
+                const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(j) * ldq + c4);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            }
+            __bf16 pl[4][NP];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) to_planes<NP>((static_cast<uint32_t>(c4 + e) < r) ? v[e] : 0.0f, pl[e]);
+            const int lrow = (jj & 1) * 32 + (jj >> 1);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                bf16x4 w = {pl[0][p], pl[1][p], pl[2][p], pl[3][p]};
+                *reinterpret_cast<bf16x4*>(dlds + lrow * ROWB + p * (RP * 2) + c4 * 2) = w;
+            }
+        }
+        __syncthreads();
+
+        // D for this lane's 16 rows x 2 adjacent columns, issued before the MFMAs
+        const uint32_t col = j0 + 2 * jl;
+        float dv[16][2];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
+            dv[v][0] = dv[v][1] = 0.0f;
+            if (row < m && col < n) {
+                const float* p = E + static_cast<size_t>(row) * n + col;
+                if (VECOK && col + 2 <= n) {
+                    const float2 x = *reinterpret_cast<const float2*>(p);
+                    dv[v][0] = x.x; dv[v][1] = x.y;
+                } else {
+                    dv[v][0] = p[0];
+                    if (col + 1 < n) dv[v][1] = p[1];
+                }
+            }
+        }
+
+        f32x16 acc[2];
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;
+#pragma unroll
+            for (int kb = 0; kb < KT; ++kb) {
+                bf16x8 b[NP];
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+                    b[p] = *reinterpret_cast<const bf16x8*>(dlds + (ct * 32 + jl) * ROWB + p * (RP * 2) + kb * 32 + g * 16);
+                acc[ct] = mma<NP>(a[kb], b, acc[ct]);
+            }
+        }
+
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
+            if (row >= m || col >= n) continue;
+            float w0 = acc[0][v], w1 = acc[1][v];
+            if (out_bf16) {
+                const __bf16 h0 = static_cast<__bf16>(w0), h1 = static_cast<__bf16>(w1);
+                w0 = static_cast<float>(h0); w1 = static_cast<float>(h1);
+                __bf16* o = static_cast<__bf16*>(out_) + static_cast<size_t>(row) * ldo + col;
+                if (VECOK && col + 2 <= n) {
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    bf16x2 hh = {h0, h1};
+                    *reinterpret_cast<bf16x2*>(o) = hh;
+                } else {
+                    o[0] = h0;
+                    if (col + 1 < n) o[1] = h1;
+                }
+            } else {
+                float* o = static_cast<float*>(out_) + static_cast<size_t>(row) * ldo + col;
+                if (VECOK && col + 2 <= n) *reinterpret_cast<float2*>(o) = make_float2(w0, w1);
+                else { o[0] = w0; if (col + 1 < n) o[1] = w1; }
+            }
+            float* e = E + static_cast<size_t>(row) * n + col;
+            const float e0 = dv[v][0] - w0, e1 = dv[v][1] - w1;
+            if (VECOK && col + 2 <= n) *reinterpret_cast<float2*>(e) = make_float2(e0, e1);
+            else { e[0] = e0; if (col + 1 < n) e[1] = e1; }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static inline uint32_t cdiv(uint64_t a, uint64_t b) { return static_cast<uint32_t>((a + b - 1) / b); }
+static inline int rank_tiles(uint32_t r) { return r <= 32 ? 1 : (r <= 64 ? 2 : 4); }
+
+// Split-K partials: the P-pass writes at most (target blocks) * 128 rows, the
+// Q-pass at most (target blocks) * 128 columns, each of the padded rank.
+size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_rank, int num_cu)
+{
+    const uint64_t RP = static_cast<uint64_t>(rank_tiles(max_rank)) * 32;
+    const uint64_t target = static_cast<uint64_t>(num_cu) * 4;
+    const uint64_t p_rows = std::max<uint64_t>(max_rows, 128 * target) + max_rows;
+    const uint64_t q_cols = std::max<uint64_t>(max_cols, 128 * target) + max_cols;
+    return static_cast<size_t>(std::max(p_rows, q_cols) * RP);
+}
+
+int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1,
+                  uint64_t seed, hipStream_t st)
+{
+    const uint64_t total = static_cast<uint64_t>(n) * (c1 - c0);
+    if (total == 0) return EDGC_OK;
+    k_init_q<<<cdiv(total, 256), 256, 0, st>>>(Q, n, ldq, c0, c1, seed);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+template <int NP, int RT>
+static int run_pass_p(edgc_ctx* ctx, const void* grad, uint64_t ld, float* residual, int e_zero,
+                      const float* Q, uint32_t ldq, uint32_t m, uint32_t n, uint32_t r,
+                      uint32_t* S_out, hipStream_t st)
+{
+    constexpr uint32_t BK = (NP == 1) ? 64 : 32;
+    using GT = typename GradElem<NP>::type;
+    const uint32_t RB = cdiv(m, 128), RP = RT * 32;
+    const uint32_t ksteps = cdiv(n, BK);
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 4;
+    uint32_t S = std::max(1u, std::min(ksteps, target / RB));
+    const uint64_t cap = ctx->s.part_elems / (static_cast<uint64_t>(m) * RP);
+    if (cap == 0) return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
+    S = static_cast<uint32_t>(std::min<uint64_t>(S, cap));
+    const uint32_t kper = cdiv(ksteps, S) * BK;
+    S = cdiv(n, kper);
+    const bool vec = (n % 4 == 0) && (ld % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(grad) % (4 * sizeof(GT)) == 0) &&
+                     (reinterpret_cast<uintptr_t>(residual) % 16 == 0);
+    const GT* G = static_cast<const GT*>(grad);
+    if (vec)
+        k_pass_p<NP, RT, true><<<RB * S, 256, 0, st>>>(G, ld, residual, e_zero, Q, ldq, ctx->s.part, m, n, r, kper, RB, S);
+    else
+        k_pass_p<NP, RT, false><<<RB * S, 256, 0, st>>>(G, ld, residual, e_zero, Q, ldq, ctx->s.part, m, n, r, kper, RB, S);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    *S_out = S;
+    return EDGC_OK;
+}
+
+template <int NP>
+static int run_orthonormalise(edgc_ctx* ctx, uint32_t S, uint32_t m, uint32_t r, float* P,
+                              uint32_t ldp, uint32_t m_pad, hipStream_t st)
+{
+    Scratch& s = ctx->s;
+    const uint32_t RP = rank_tiles(r) * 32;
+    const uint32_t NB = cdiv(m, 64);
+    const uint32_t ta = cdiv(r, 16);
+    switch (ta <= 1 ? 1 : ta <= 2 ? 2 : ta <= 4 ? 4 : 8) {
+    case 1: k_reduce_gram<1><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+    case 2: k_reduce_gram<2><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+    case 4: k_reduce_gram<4><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+    default: k_reduce_gram<8><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+    }
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    const uint32_t rr = r * r;
+    const double* gram_src = s.gram_part;
+    uint32_t nb = NB;
+    if (static_cast<uint64_t>(NB) * rr > 65536) {       // many partials: sum them on many CUs
+        k_gram_sum<<<cdiv(rr, 256), 256, 0, st>>>(s.gram_part, NB, rr, s.gram);
+        EDGC_HIP_TRY(ctx, hipGetLastError());
+        gram_src = s.gram;
+        nb = 1;
+    }
+    const size_t chol_lds = (static_cast<size_t>(r) * (r + 1) + 2 * r) * sizeof(double) + r * sizeof(int);
+    if (chol_lds > 64 * 1024)
+        EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chol),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              static_cast<int>(chol_lds)));
+    k_chol<<<1, 1024, chol_lds, st>>>(gram_src, nb, r, s.rinv);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    __bf16* pt = static_cast<__bf16*>(s.pt);
+    const uint32_t NBA = m_pad / 64;
+    if (r <= 16)      k_apply<16, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+    else if (r <= 32) k_apply<32, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+    else if (r <= 64) k_apply<64, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+    else              k_apply<128, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+template <int NP, int RT, int NT>
+static int run_pass_q(edgc_ctx* ctx, const float* D, uint32_t m, uint32_t n, uint32_t r, float* Q,
+                      uint32_t ldq, uint32_t m_pad, hipStream_t st)
+{
+    constexpr uint32_t RP = RT * 32, W = 32 * NT;
+    constexpr size_t stage_lds = static_cast<size_t>(4) * RP * (NP * 128 + 16);
+    constexpr size_t red_lds = static_cast<size_t>(2) * RT * NT * 16 * 64 * sizeof(float);
+    constexpr size_t lds = stage_lds > red_lds ? stage_lds : red_lds;
+    const uint32_t CB = cdiv(n, W);
+    const uint32_t stages = m_pad / 64;
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 4;
+    uint32_t S = std::max(1u, std::min(cdiv(stages, 4), target / CB));
+    const uint64_t cap = ctx->s.part_elems / (static_cast<uint64_t>(n) * RP);
+    if (cap == 0) return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
+    S = static_cast<uint32_t>(std::min<uint64_t>(S, cap));
+    const uint32_t sps = cdiv(stages, S);
+    S = cdiv(stages, sps);
+    const bool vec = (n % NT == 0) && (reinterpret_cast<uintptr_t>(D) % 16 == 0);
+    const __bf16* pt = static_cast<const __bf16*>(ctx->s.pt);
+    if (vec) {
+        auto kern = &k_pass_q<NP, RT, NT, true>;
+        if (lds > 64 * 1024)
+            EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S);
+    } else {
+        auto kern = &k_pass_q<NP, RT, NT, false>;
+        if (lds > 64 * 1024)
+            EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+        kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S);
+    }
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    k_reduce_q<<<cdiv(static_cast<uint64_t>(n) * RP, 256), 256, 0, st>>>(ctx->s.part, S, n, RP, r, Q, ldq);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+template <int NP, int RT>
+static int compress_impl(edgc_ctx* ctx, const void* grad, uint32_t m, uint32_t n, uint64_t ld,
+                         float* residual, int e_zero, float* Q, uint32_t ldq, float* P, uint32_t ldp,
+                         uint32_t r, uint32_t power_iters, hipStream_t st)
+{
+    const uint32_t m_pad = cdiv(m, 64) * 64;
+    // After the first P-pass the residual buffer holds D; later iterations re-read it
+    // with a null gradient (D + 0).
+    for (uint32_t it = 0; it < power_iters; ++it) {
+        uint32_t S = 1;
+        int rc = (it == 0) ? run_pass_p<NP, RT>(ctx, grad, ld, residual, e_zero, Q, ldq, m, n, r, &S, st)
+                           : run_pass_p<NP, RT>(ctx, nullptr, ld, residual, 0, Q, ldq, m, n, r, &S, st);
+        if (rc != EDGC_OK) return rc;
+        rc = run_orthonormalise<NP>(ctx, S, m, r, P, ldp, m_pad, st);
+        if (rc != EDGC_OK) return rc;
+        if constexpr (RT == 4) rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
+        else                   rc = run_pass_q<NP, RT, 4>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
+        if (rc != EDGC_OK) return rc;
+    }
+    return EDGC_OK;
+}
+
+int launch_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dt, uint32_t m, uint32_t n,
+                    uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
+                    float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, hipStream_t st)
+{
+    const int rt = rank_tiles(r);
+#define EDGC_DISPATCH(NP_)                                                                          \
+    switch (rt) {                                                                                   \
+    case 1: return compress_impl<NP_, 1>(ctx, grad, m, n, ld, residual, residual_is_zero, Q, ldq, P, ldp, r, power_iters, st); \
+    case 2: return compress_impl<NP_, 2>(ctx, grad, m, n, ld, residual, residual_is_zero, Q, ldq, P, ldp, r, power_iters, st); \
+    default: return compress_impl<NP_, 4>(ctx, grad, m, n, ld, residual, residual_is_zero, Q, ldq, P, ldp, r, power_iters, st); \
+    }
+    if (dt == EDGC_BF16) { EDGC_DISPATCH(1) }
+    EDGC_DISPATCH(2)
+#undef EDGC_DISPATCH
+}
+
+template <int NP, int RT>
+static int decompress_impl(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                           uint32_t m, uint32_t n, uint32_t r, float* residual, void* out, int out_bf16,
+                           uint64_t ld, hipStream_t st)
+{
+    constexpr uint32_t RP = RT * 32;
+    constexpr size_t lds = static_cast<size_t>(64) * (NP * RP * 2 + 16);
+    const uint32_t RB = cdiv(m, 128);
+    const uint32_t stages = cdiv(n, 64);
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 4;
+    uint32_t JS = std::max(1u, std::min(stages, target / RB));
+    const uint32_t sps = cdiv(stages, JS);
+    JS = cdiv(stages, sps);
+    const uint32_t esz = out_bf16 ? 2 : 4;
+    const bool vec = (n % 2 == 0) && (ld % 2 == 0) && (reinterpret_cast<uintptr_t>(residual) % 8 == 0) &&
+                     (reinterpret_cast<uintptr_t>(out) % (2 * esz) == 0);
+    if (vec)
+        k_decompress<NP, RT, true><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS);
+    else
+        k_decompress<NP, RT, false><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+int launch_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                      uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
+                      edgc_dtype dt, uint64_t ld, hipStream_t st)
+{
+    const int rt = rank_tiles(r);
+    const int bf = (dt == EDGC_BF16);
+#define EDGC_DISPATCH(NP_)                                                                          \
+    switch (rt) {                                                                                   \
+    case 1: return decompress_impl<NP_, 1>(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, bf, ld, st); \
+    case 2: return decompress_impl<NP_, 2>(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, bf, ld, st); \
+    default: return decompress_impl<NP_, 4>(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, bf, ld, st); \
+    }
+    if (bf) { EDGC_DISPATCH(1) }
+    EDGC_DISPATCH(2)
+#undef EDGC_DISPATCH
+}
+
+}  // namespace edgc

@@ -1,0 +1,196 @@
+// C-ABI entry points of libedgc (include/edgc.h): argument checks, context and
+// scratch management, and hand-off to the kernel launchers.  No computation here.
+#include "edgc_internal.h"
+
+#include <new>
+
+using namespace edgc;
+
+namespace {
+
+bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+template <typename T>
+hipError_t dev_alloc(T** p, size_t count)
+{
+    *p = nullptr;
+    return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T));
+}
+
+void free_scratch(Scratch& s)
+{
+    void* ptrs[] = {s.mm_part, s.done_counter, s.counts, s.nonfinite, s.range, s.result_dev,
+                    s.part, s.gram_part, s.gram, s.rinv, s.pt};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    s = Scratch{};
+}
+
+}  // namespace
+
+extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, uint32_t max_rank,
+                           uint64_t max_rows, uint64_t max_cols)
+{
+    if (!out) return EDGC_EINVAL;
+    *out = nullptr;
+    if (max_bins == 0 || max_bins > (1u << 24) || max_rank == 0 || max_rank > 128 || max_rows == 0 ||
+        max_cols == 0 || max_rows > 0x7fffffffull || max_cols > 0x7fffffffull)
+        return EDGC_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || hip_device < 0 || hip_device >= ndev) return EDGC_EHIP;
+    if (hipSetDevice(hip_device) != hipSuccess) return EDGC_EHIP;
+
+    edgc_ctx* ctx = new (std::nothrow) edgc_ctx();
+    if (!ctx) return EDGC_ENOMEM;
+    ctx->device = hip_device;
+    ctx->max_bins = max_bins;
+    ctx->max_rank = max_rank;
+    ctx->max_rows = max_rows;
+    ctx->max_cols = max_cols;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->num_cu = prop.multiProcessorCount;
+
+    Scratch& s = ctx->s;
+    const uint64_t rp = (max_rank <= 32) ? 32 : (max_rank <= 64 ? 64 : 128);
+    const uint64_t rows_pad = (max_rows + 63) / 64 * 64;
+    s.part_elems = compress_part_elems(max_rows, max_cols, max_rank, ctx->num_cu);
+    s.gram_part_elems = (rows_pad / 64) * static_cast<uint64_t>(max_rank) * max_rank;
+    s.pt_bytes = 2ull * rp * rows_pad * 2ull;
+    bool ok = true;
+    ok = ok && dev_alloc(&s.mm_part, 2 * kMaxReduceBlocks) == hipSuccess;
+    ok = ok && dev_alloc(&s.done_counter, 4) == hipSuccess;
+    ok = ok && dev_alloc(&s.counts, max_bins) == hipSuccess;
+    ok = ok && dev_alloc(&s.nonfinite, 1) == hipSuccess;
+    ok = ok && hipMalloc(&s.range, 64) == hipSuccess;
+    ok = ok && hipMalloc(&s.result_dev, sizeof(edgc_entropy_result)) == hipSuccess;
+    ok = ok && dev_alloc(&s.part, s.part_elems) == hipSuccess;
+    ok = ok && dev_alloc(&s.gram_part, s.gram_part_elems) == hipSuccess;
+    ok = ok && dev_alloc(&s.gram, static_cast<size_t>(max_rank) * max_rank) == hipSuccess;
+    ok = ok && dev_alloc(&s.rinv, static_cast<size_t>(max_rank) * max_rank) == hipSuccess;
+    ok = ok && hipMalloc(&s.pt, s.pt_bytes) == hipSuccess;
+    ok = ok && hipMemset(s.done_counter, 0, 4 * sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        free_scratch(s);
+        delete ctx;
+        return EDGC_ENOMEM;
+    }
+    *out = ctx;
+    return EDGC_OK;
+}
+
+extern "C" int edgc_destroy(edgc_ctx* ctx)
+{
+    if (!ctx) return EDGC_EINVAL;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    free_scratch(ctx->s);
+    delete ctx;
+    return EDGC_OK;
+}
+
+extern "C" const char* edgc_last_error(const edgc_ctx* ctx)
+{
+    return ctx ? ctx->last_error.c_str() : "null context";
+}
+
+static int check_sampler_args(edgc_ctx* ctx, uint64_t stride, uint32_t chunk)
+{
+    if (stride == 0 || chunk == 0) return fail(ctx, EDGC_EINVAL, "stride and chunk must be >= 1");
+    if (stride > (1ull << 40) || chunk > (1u << 20))
+        return fail(ctx, EDGC_EINVAL, "stride > 2^40 or chunk > 2^20");
+    return EDGC_OK;
+}
+
+extern "C" int edgc_entropy_estimate(edgc_ctx* ctx, const void* grad, edgc_dtype dtype,
+                                     uint64_t n_elems, uint64_t stride, uint32_t chunk, uint64_t seed,
+                                     uint64_t step, uint32_t bins, const float* range,
+                                     edgc_entropy_result* out, uint64_t* counts_out, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!grad || !out) return fail(ctx, EDGC_EINVAL, "null grad or out");
+    if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
+    if (int rc = check_sampler_args(ctx, stride, chunk)) return rc;
+    if (bins == 0 || bins > ctx->max_bins) return fail(ctx, EDGC_EINVAL, "bins == 0 or bins > max_bins");
+    if (range && !(range[0] <= range[1])) return fail(ctx, EDGC_EINVAL, "range needs lo <= hi");
+    if (!aligned_to(grad, dtype == EDGC_F32 ? 4 : 2)) return fail(ctx, EDGC_EINVAL, "grad misaligned");
+    if (counts_out && !aligned_to(counts_out, 8)) return fail(ctx, EDGC_EINVAL, "counts misaligned");
+    if (n_elems > (1ull << 44)) return fail(ctx, EDGC_EINVAL, "n_elems too large");
+    const SampleGeom g = make_geom(grad, dtype, n_elems, stride, chunk, seed, step);
+    if (g.n_sampled == 0) return fail(ctx, EDGC_ENONFINITE, "the sampling predicate selects no element");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return launch_entropy(ctx, grad, dtype, g, bins, range, out, counts_out,
+                          static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int edgc_sample_indices(edgc_ctx* ctx, uint64_t n_elems, uint64_t stride, uint32_t chunk,
+                                   uint64_t seed, uint64_t step, uint64_t* idx_out, uint64_t cap,
+                                   uint64_t* n_out, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!n_out) return fail(ctx, EDGC_EINVAL, "null n_out");
+    if (int rc = check_sampler_args(ctx, stride, chunk)) return rc;
+    // layout of the indices does not depend on dtype or alignment: use the scalar geometry
+    SampleGeom g = make_geom(reinterpret_cast<const void*>(uintptr_t{1}), EDGC_F32, n_elems, stride,
+                             chunk, seed, step);
+    *n_out = g.n_sampled;
+    if (!idx_out || cap == 0) return EDGC_OK;
+    if (!aligned_to(idx_out, 8)) return fail(ctx, EDGC_EINVAL, "idx_out misaligned");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return launch_sample_indices(ctx, g, idx_out, cap, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int edgc_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t col_begin,
+                           uint32_t col_end, uint64_t seed, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!Q || col_begin > col_end || col_end > ldq) return fail(ctx, EDGC_EINVAL, "bad Q columns");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return launch_init_q(ctx, Q, n, ldq, col_begin, col_end, seed, static_cast<hipStream_t>(hip_stream));
+}
+
+static int check_factor_args(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                             uint32_t m, uint32_t n, uint32_t r, uint64_t ld)
+{
+    if (!P || !Q) return fail(ctx, EDGC_EINVAL, "null P or Q");
+    if (m == 0 || n == 0) return fail(ctx, EDGC_EINVAL, "empty matrix");
+    if (m > ctx->max_rows || n > ctx->max_cols) return fail(ctx, EDGC_EINVAL, "matrix larger than the context");
+    if (r == 0 || r > m || r > n || r > ctx->max_rank) return fail(ctx, EDGC_EINVAL, "rank out of range");
+    if (ld < n || ldp < r || ldq < r) return fail(ctx, EDGC_EINVAL, "leading dimension too small");
+    if (ldp % 4 || ldq % 4 || !aligned_to(P, 16) || !aligned_to(Q, 16))
+        return fail(ctx, EDGC_EINVAL, "P and Q need 16-byte alignment and leading dimensions that are multiples of 4");
+    return EDGC_OK;
+}
+
+extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
+                             uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
+                             float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!grad || !residual) return fail(ctx, EDGC_EINVAL, "null grad or residual");
+    if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
+    if (int rc = check_factor_args(ctx, P, ldp, Q, ldq, m, n, r, ld)) return rc;
+    if (power_iters == 0) return fail(ctx, EDGC_EINVAL, "power_iters must be >= 1");
+    if (!aligned_to(grad, dtype == EDGC_F32 ? 4 : 2) || !aligned_to(residual, 4))
+        return fail(ctx, EDGC_EINVAL, "grad or residual misaligned");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return launch_compress(ctx, grad, dtype, m, n, ld, residual, residual_is_zero, Q, ldq, P, ldp, r,
+                           power_iters, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                               uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
+                               edgc_dtype dtype, uint64_t ld, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!residual || !grad_out) return fail(ctx, EDGC_EINVAL, "null residual or grad_out");
+    if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
+    if (int rc = check_factor_args(ctx, P, ldp, Q, ldq, m, n, r, ld)) return rc;
+    if (!aligned_to(grad_out, dtype == EDGC_F32 ? 4 : 2) || !aligned_to(residual, 4))
+        return fail(ctx, EDGC_EINVAL, "grad_out or residual misaligned");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return launch_decompress(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld,
+                             static_cast<hipStream_t>(hip_stream));
+}

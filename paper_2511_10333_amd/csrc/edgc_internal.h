@@ -1,0 +1,106 @@
+// Internal declarations shared by the HIP translation units of libedgc.
+// Nothing here is part of the public ABI (include/edgc.h is).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "edgc.h"
+
+namespace edgc {
+
+// Scratch owned by a context.  Sized once in edgc_create; hot calls only use it.
+struct Scratch {
+    // entropy
+    float*              mm_part      = nullptr;  // [2 * kMaxReduceBlocks] per-block (lo, hi)
+    unsigned int*       done_counter = nullptr;  // [4] last-block tickets, zero between calls
+    unsigned long long* counts       = nullptr;  // [max_bins] histogram when the caller gives none
+    unsigned long long* nonfinite    = nullptr;  // [1]
+    void*               range        = nullptr;  // RangeParams
+    void*               result_dev   = nullptr;  // edgc_entropy_result
+    // compress / decompress
+    float*  part      = nullptr;   // split-K partial factors [S][rows][rank_pad]
+    size_t  part_elems = 0;
+    double* gram_part = nullptr;   // [gram_blocks][rank_pad*rank_pad]
+    size_t  gram_part_elems = 0;
+    double* gram      = nullptr;   // [rank_pad*rank_pad]
+    double* rinv      = nullptr;   // [rank_pad*rank_pad]
+    void*   pt        = nullptr;   // operand copy of P^ transposed: [planes][rank_pad][rows_pad] bf16
+    size_t  pt_bytes  = 0;
+};
+
+constexpr int kMaxReduceBlocks = 4096;
+
+}  // namespace edgc
+
+struct edgc_ctx {
+    int device = 0;
+    uint32_t max_bins = 0, max_rank = 0;
+    uint64_t max_rows = 0, max_cols = 0;
+    int num_cu = 256;
+    edgc::Scratch s;
+    std::string last_error;
+};
+
+namespace edgc {
+
+inline int fail(edgc_ctx* ctx, int code, const std::string& msg)
+{
+    if (ctx) ctx->last_error = msg;
+    return code;
+}
+
+#define EDGC_HIP_TRY(ctx, expr)                                                              \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return ::edgc::fail((ctx), EDGC_EHIP,                                            \
+                                std::string(#expr) + ": " + hipGetErrorString(e_));          \
+    } while (0)
+
+// splitmix64 output function on seed + golden * (ctr + 1); the sampler's slot and
+// the seeded start of Q are drawn from it (host and device).
+__host__ __device__ inline uint64_t mix64(uint64_t seed, uint64_t ctr)
+{
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull * (ctr + 1ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Geometry of the chunk-strided sample (GDS, Sec. IV-B), computed on the host.
+struct SampleGeom {
+    uint64_t n;         // elements in the buffer
+    uint64_t stride;    // chunk stride = 1 / beta
+    uint64_t slot;      // sampled residue class of the chunk index
+    uint64_t n_chunks;  // number of sampled chunks
+    uint64_t n_items;   // n_chunks * ipc
+    uint64_t n_sampled; // sampled elements
+    uint32_t chunk;     // elements per chunk
+    uint32_t ipc;       // items (vectors of VEC elements) per chunk
+    uint32_t vec;       // elements per item: 1, 4 (fp32) or 8 (bf16)
+};
+
+SampleGeom make_geom(const void* base, edgc_dtype dt, uint64_t n, uint64_t stride, uint32_t chunk,
+                     uint64_t seed, uint64_t step);
+
+// launchers (entropy.hip)
+int launch_entropy(edgc_ctx* ctx, const void* grad, edgc_dtype dt, const SampleGeom& g,
+                   uint32_t bins, const float* range, edgc_entropy_result* out,
+                   uint64_t* counts_out, hipStream_t st);
+int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uint64_t cap,
+                          hipStream_t st);
+
+// launchers (compress.hip)
+int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1,
+                  uint64_t seed, hipStream_t st);
+int launch_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dt, uint32_t m, uint32_t n,
+                    uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
+                    float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, hipStream_t st);
+int launch_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                      uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
+                      edgc_dtype dt, uint64_t ld, hipStream_t st);
+size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_rank, int num_cu);
+
+}  // namespace edgc

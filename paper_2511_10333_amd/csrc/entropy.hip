@@ -1,0 +1,499 @@
+// Down-sampled gradient entropy on gfx950 (GDS, Sec. IV-B; Definition 1 / Eq. (1)
+// estimated with an equal-width histogram).
+//
+// Two streaming kernels over the sampled chunks plus nothing else:
+//   k_minmax  range of the finite sample: per-lane min/max, wavefront DPP
+//             reduction, LDS across the block's waves, last-block finish
+//   k_hist    bin index in fp32 (separately rounded subtract / multiply, the
+//             scale comes from one correctly rounded division), LDS histogram
+//             with lane-interleaved replicas so equal bins in one wavefront hit
+//             different banks, flush to 64-bit global counters, and the last
+//             block reduces the counters to the Shannon entropy in fp64
+// The chunk-strided sample is read with 16-byte loads whenever chunks are a
+// multiple of the vector width, so a wavefront touches whole cache lines.
+#include "edgc_internal.h"
+
+#include <math.h>
+
+namespace edgc {
+
+struct RangeParams {
+    float lo, hi, w, scale;
+};
+
+constexpr int kMMBlock   = 256;
+constexpr int kHistBlock = 512;
+
+// ---------------------------------------------------------------------------
+// wavefront reductions with DPP row shifts / row broadcasts (64 lanes)
+// ---------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float identity, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v),
+                                                      CTRL, ROW_MASK, 0xf, false));
+}
+
+// Result is valid in lane 63 and returned to every lane through a read-lane.
+template <bool IS_MIN>
+__device__ __forceinline__ float wave_reduce_minmax(float v)
+{
+    const float id = IS_MIN ? INFINITY : -INFINITY;
+#define EDGC_OP(a, b) (IS_MIN ? fminf((a), (b)) : fmaxf((a), (b)))
+    v = EDGC_OP(v, (dpp_move<0x111, 0xf>(id, v)));   // row_shr:1
+    v = EDGC_OP(v, (dpp_move<0x112, 0xf>(id, v)));   // row_shr:2
+    v = EDGC_OP(v, (dpp_move<0x114, 0xf>(id, v)));   // row_shr:4
+    v = EDGC_OP(v, (dpp_move<0x118, 0xf>(id, v)));   // row_shr:8  -> lane 15 of each row
+    v = EDGC_OP(v, (dpp_move<0x142, 0xa>(id, v)));   // row_bcast:15 into rows 1 and 3
+    v = EDGC_OP(v, (dpp_move<0x143, 0xc>(id, v)));   // row_bcast:31 into rows 2 and 3
+#undef EDGC_OP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;   // lane 0
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;   // lane 0
+}
+
+// ---------------------------------------------------------------------------
+// sample addressing
+// ---------------------------------------------------------------------------
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<float> {
+    static __device__ __forceinline__ float widen(float x) { return x; }
+};
+template <> struct ElemTraits<uint16_t> {   // raw bf16 bits
+    static __device__ __forceinline__ float widen(uint16_t h)
+    {
+        return __uint_as_float(static_cast<uint32_t>(h) << 16);
+    }
+};
+
+// Loads the VEC elements of one item starting at element i0; elements at or
+// beyond n are reported invalid.  Full items use one 16-byte load.
+template <typename T, int VEC>
+__device__ __forceinline__ uint32_t load_item(const T* __restrict__ g, uint64_t i0, uint64_t n,
+                                              float (&v)[VEC])
+{
+    if constexpr (VEC == 1) {
+        v[0] = ElemTraits<T>::widen(g[i0]);
+        return 1u;
+    } else {
+        if (i0 + VEC <= n) {
+            if constexpr (sizeof(T) == 4) {
+                const float4 q = *reinterpret_cast<const float4*>(g + i0);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            } else {
+                const uint4 q = *reinterpret_cast<const uint4*>(g + i0);
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    v[2 * p]     = __uint_as_float(w[p] << 16);
+                    v[2 * p + 1] = __uint_as_float(w[p] & 0xffff0000u);
+                }
+            }
+            return (1u << VEC) - 1u;
+        }
+        uint32_t mask = 0;
+#pragma unroll
+        for (int p = 0; p < VEC; ++p) {
+            v[p] = 0.0f;
+            if (i0 + p < n) { v[p] = ElemTraits<T>::widen(g[i0 + p]); mask |= 1u << p; }
+        }
+        return mask;
+    }
+}
+
+// Walks the items owned by one thread: item t, t + G, t + 2G, ... without a
+// division in the loop.  item -> (k-th sampled chunk, e-th item in it).
+struct ItemCursor {
+    uint64_t item, k;
+    uint32_t e;
+    uint64_t dk;
+    uint32_t de;
+    __device__ __forceinline__ void init(uint64_t first, uint64_t step, uint32_t ipc)
+    {
+        item = first;
+        k = first / ipc;
+        e = static_cast<uint32_t>(first - k * ipc);
+        dk = step / ipc;
+        de = static_cast<uint32_t>(step - dk * ipc);
+    }
+    __device__ __forceinline__ void advance(uint64_t step, uint32_t ipc)
+    {
+        item += step;
+        k += dk;
+        e += de;
+        if (e >= ipc) { e -= ipc; ++k; }
+    }
+    __device__ __forceinline__ uint64_t elem0(const SampleGeom& g, int vec) const
+    {
+        return (g.slot + k * g.stride) * g.chunk + static_cast<uint64_t>(e) * vec;
+    }
+};
+
+__device__ __forceinline__ bool finite_f32(float x)
+{
+    return (__float_as_uint(x) & 0x7f800000u) != 0x7f800000u;
+}
+
+// ---------------------------------------------------------------------------
+// kernel 1: range of the finite sample
+// ---------------------------------------------------------------------------
+template <typename T, int VEC>
+__global__ __launch_bounds__(kMMBlock) void k_minmax(const T* __restrict__ g, SampleGeom geom,
+                                                     float* __restrict__ part,
+                                                     unsigned int* done, RangeParams* rp,
+                                                     float fbins)
+{
+    const uint64_t G = static_cast<uint64_t>(gridDim.x) * kMMBlock;
+    const uint64_t gtid = static_cast<uint64_t>(blockIdx.x) * kMMBlock + threadIdx.x;
+
+    float lo = INFINITY, hi = -INFINITY;
+    ItemCursor cur;
+    cur.init(gtid, G, geom.ipc);
+    constexpr int U = 4;
+    while (cur.item < geom.n_items) {
+        float v[U][VEC];
+        uint32_t mask[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            mask[u] = 0;
+            if (cur.item < geom.n_items) {
+                const uint64_t i0 = cur.elem0(geom, VEC);
+                if (i0 < geom.n) mask[u] = load_item<T, VEC>(g, i0, geom.n, v[u]);
+            }
+            cur.advance(G, geom.ipc);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int p = 0; p < VEC; ++p)
+                if (((mask[u] >> p) & 1u) && finite_f32(v[u][p])) {
+                    lo = fminf(lo, v[u][p]);
+                    hi = fmaxf(hi, v[u][p]);
+                }
+    }
+
+    __shared__ float s_lo[kMMBlock / 64], s_hi[kMMBlock / 64];
+    __shared__ bool s_last;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    lo = wave_reduce_minmax<true>(lo);
+    hi = wave_reduce_minmax<false>(hi);
+    if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kMMBlock / 64; ++w) { lo = fminf(lo, s_lo[w]); hi = fmaxf(hi, s_hi[w]); }
+        part[2 * blockIdx.x]     = lo;
+        part[2 * blockIdx.x + 1] = hi;
+        __threadfence();
+        const unsigned int ticket = atomicAdd(done, 1u);
+        s_last = (ticket == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // last block: fold the per-block partials
+    __threadfence();
+    lo = INFINITY; hi = -INFINITY;
+    for (unsigned int b = threadIdx.x; b < gridDim.x; b += kMMBlock) {
+        lo = fminf(lo, __hip_atomic_load(&part[2 * b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        hi = fmaxf(hi, __hip_atomic_load(&part[2 * b + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
+    lo = wave_reduce_minmax<true>(lo);
+    hi = wave_reduce_minmax<false>(hi);
+    __syncthreads();
+    if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kMMBlock / 64; ++w) { lo = fminf(lo, s_lo[w]); hi = fmaxf(hi, s_hi[w]); }
+        RangeParams r;
+        if (lo <= hi) {
+            r.lo = lo; r.hi = hi;
+            r.w = __fsub_rn(hi, lo);
+            r.scale = (r.w > 0.0f) ? __fdiv_rn(fbins, r.w) : 0.0f;
+        } else {   // no finite sample at all
+            r.lo = NAN; r.hi = NAN; r.w = 0.0f; r.scale = 0.0f;
+        }
+        *rp = r;
+        *done = 0u;
+    }
+}
+
+// Caller-supplied range: same derived quantities, no pass over the data.
+__global__ void k_set_range(RangeParams* rp, float lo, float hi, float fbins)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        RangeParams r;
+        r.lo = lo; r.hi = hi;
+        r.w = __fsub_rn(hi, lo);
+        r.scale = (r.w > 0.0f) ? __fdiv_rn(fbins, r.w) : 0.0f;
+        *rp = r;
+    }
+}
+
+__global__ void k_zero_counts(unsigned long long* counts, uint32_t bins, unsigned long long* nonfinite)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < bins) counts[i] = 0ull;
+    if (i == 0) *nonfinite = 0ull;
+}
+
+// ---------------------------------------------------------------------------
+// kernel 2: histogram + entropy
+// ---------------------------------------------------------------------------
+template <typename T, int VEC>
+__global__ __launch_bounds__(kHistBlock) void k_hist(
+    const T* __restrict__ g, SampleGeom geom, const RangeParams* __restrict__ rp, uint32_t bins,
+    uint32_t bins_local, uint32_t rep_shift, unsigned long long* counts,
+    unsigned long long* nonfinite, unsigned int* done, edgc_entropy_result* res)
+{
+    extern __shared__ uint32_t h[];   // [bins_local << rep_shift], replica = lane & (R-1)
+    const uint32_t bin_base = blockIdx.y * bins_local;
+    const uint32_t local_n = min(bins_local, bins - bin_base);
+    const uint32_t words = local_n << rep_shift;
+    for (uint32_t i = threadIdx.x; i < words; i += kHistBlock) h[i] = 0u;
+    __syncthreads();
+
+    const float lo = rp->lo, scale = rp->scale;
+    const float fbins = static_cast<float>(bins);
+    const uint32_t rep = threadIdx.x & ((1u << rep_shift) - 1u);
+    const bool count_nf = (blockIdx.y == 0);
+    unsigned long long nf = 0;
+
+    const uint64_t G = static_cast<uint64_t>(gridDim.x) * kHistBlock;
+    ItemCursor cur;
+    cur.init(static_cast<uint64_t>(blockIdx.x) * kHistBlock + threadIdx.x, G, geom.ipc);
+    constexpr int U = 4;
+    while (cur.item < geom.n_items) {
+        float v[U][VEC];
+        uint32_t mask[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            mask[u] = 0;
+            if (cur.item < geom.n_items) {
+                const uint64_t i0 = cur.elem0(geom, VEC);
+                if (i0 < geom.n) mask[u] = load_item<T, VEC>(g, i0, geom.n, v[u]);
+            }
+            cur.advance(G, geom.ipc);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int p = 0; p < VEC; ++p) {
+                if (!((mask[u] >> p) & 1u)) continue;
+                const float x = v[u][p];
+                if (!finite_f32(x)) { nf += count_nf ? 1ull : 0ull; continue; }
+                // bin = trunc((x - lo) * scale), each operation rounded on its own
+                const float t = __fsub_rn(x, lo);
+                float f = __fmul_rn(t, scale);
+                f = fminf(fmaxf(f, 0.0f), fbins);          // also maps NaN (inf * 0) to 0
+                const uint32_t b = min(static_cast<uint32_t>(f), bins - 1u);
+                const uint32_t rel = b - bin_base;
+                if (rel < local_n) atomicAdd(&h[(rel << rep_shift) | rep], 1u);
+            }
+    }
+    __syncthreads();
+
+    // fold the replicas and flush non-empty bins
+    for (uint32_t i = threadIdx.x; i < local_n; i += kHistBlock) {
+        uint32_t s = 0;
+        for (uint32_t r = 0; r < (1u << rep_shift); ++r) s += h[(i << rep_shift) | r];
+        if (s) atomicAdd(&counts[bin_base + i], static_cast<unsigned long long>(s));
+    }
+    nf = wave_sum_u64(nf);
+    if ((threadIdx.x & 63) == 0 && nf) atomicAdd(nonfinite, nf);
+
+    __shared__ bool s_last;
+    __shared__ double s_a[kHistBlock / 64], s_b[kHistBlock / 64];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const unsigned int ticket = atomicAdd(done, 1u);
+        s_last = (ticket == gridDim.x * gridDim.y - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // last block: H = log2 n - (1/n) sum c log2 c   (== -sum p log2 p)
+    __threadfence();
+    double acc = 0.0, tot = 0.0;
+    for (uint32_t i = threadIdx.x; i < bins; i += kHistBlock) {
+        const unsigned long long c =
+            __hip_atomic_load(&counts[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (c) {
+            const double d = static_cast<double>(c);
+            acc += d * log2(d);
+            tot += d;
+        }
+    }
+    acc = wave_sum_f64(acc);
+    tot = wave_sum_f64(tot);
+    if ((threadIdx.x & 63) == 0) { s_a[threadIdx.x >> 6] = acc; s_b[threadIdx.x >> 6] = tot; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        acc = 0.0; tot = 0.0;
+        for (int w = 0; w < kHistBlock / 64; ++w) { acc += s_a[w]; tot += s_b[w]; }
+        edgc_entropy_result r;
+        r.lo = rp->lo; r.hi = rp->hi;
+        r.n_sampled = geom.n_sampled;
+        r.n_nonfinite = __hip_atomic_load(nonfinite, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r._pad = 0;
+        if (tot > 0.0) {
+            double H = log2(tot) - acc / tot;
+            if (H < 0.0) H = 0.0;
+            const double w = static_cast<double>(rp->w);
+            r.H_bits = H;
+            r.h_diff_nats = (w > 0.0) ? H * 0.69314718055994530942 + log(w / static_cast<double>(bins))
+                                      : -INFINITY;
+            r.status = EDGC_OK;
+        } else {
+            r.H_bits = NAN; r.h_diff_nats = NAN;
+            r.status = EDGC_ENONFINITE;
+        }
+        *res = r;
+        *done = 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// sampled indices (same cursor as the kernels above)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_sample_indices(SampleGeom geom, uint64_t* __restrict__ idx,
+                                                        uint64_t cap)
+{
+    const uint64_t G = static_cast<uint64_t>(gridDim.x) * 256;
+    ItemCursor cur;
+    cur.init(static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x, G, geom.ipc);
+    const int vec = static_cast<int>(geom.vec);
+    while (cur.item < geom.n_items) {
+        const uint64_t i0 = cur.elem0(geom, vec);
+        const uint64_t pos0 = cur.k * geom.chunk + static_cast<uint64_t>(cur.e) * vec;
+        for (int p = 0; p < vec; ++p)
+            if (i0 + p < geom.n && pos0 + p < cap) idx[pos0 + p] = i0 + p;
+        cur.advance(G, geom.ipc);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+SampleGeom make_geom(const void* base, edgc_dtype dt, uint64_t n, uint64_t stride, uint32_t chunk,
+                     uint64_t seed, uint64_t step)
+{
+    SampleGeom g{};
+    const uint32_t elem = (dt == EDGC_F32) ? 4u : 2u;
+    const uint32_t V = 16u / elem;
+    const bool aligned = (reinterpret_cast<uintptr_t>(base) % 16u) == 0;
+    g.n = n;
+    g.stride = stride;
+    g.slot = mix64(seed, step) % stride;
+    g.chunk = chunk;
+    if (stride == 1) {
+        // every element is sampled whatever the chunk size: read it as long runs
+        g.slot = 0;
+        if (aligned) g.chunk = 4096;
+    }
+    const uint64_t total_chunks = (n + g.chunk - 1) / g.chunk;
+    g.n_chunks = (g.slot < total_chunks) ? (total_chunks - g.slot + stride - 1) / stride : 0;
+    g.n_sampled = 0;
+    if (g.n_chunks) {
+        const uint64_t last = g.slot + (g.n_chunks - 1) * stride;
+        const uint64_t last_len = (n - last * g.chunk < g.chunk) ? n - last * g.chunk : g.chunk;
+        g.n_sampled = (g.n_chunks - 1) * g.chunk + last_len;
+    }
+    g.vec = (aligned && g.chunk % V == 0) ? V : 1u;
+    g.ipc = g.chunk / g.vec;
+    g.n_items = g.n_chunks * g.ipc;
+    return g;
+}
+
+static uint32_t grid_for(uint64_t n_items, int block, int per_thread, int max_blocks)
+{
+    uint64_t want = (n_items + static_cast<uint64_t>(block) * per_thread - 1) /
+                    (static_cast<uint64_t>(block) * per_thread);
+    if (want < 1) want = 1;
+    if (want > static_cast<uint64_t>(max_blocks)) want = max_blocks;
+    return static_cast<uint32_t>(want);
+}
+
+template <typename T, int VEC>
+static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32_t bins,
+                       const float* range, uint64_t* counts_out, hipStream_t st)
+{
+    Scratch& s = ctx->s;
+    auto* counts = counts_out ? reinterpret_cast<unsigned long long*>(counts_out) : s.counts;
+    auto* rp = static_cast<RangeParams*>(s.range);
+    auto* res = static_cast<edgc_entropy_result*>(s.result_dev);
+    const float fbins = static_cast<float>(bins);
+
+    k_zero_counts<<<(bins + 255) / 256, 256, 0, st>>>(counts, bins, s.nonfinite);
+    if (range) {
+        k_set_range<<<1, 64, 0, st>>>(rp, range[0], range[1], fbins);
+    } else {
+        const uint32_t gx = grid_for(g.n_items, kMMBlock, 8, min(kMaxReduceBlocks, ctx->num_cu * 8));
+        k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(grad, g, s.mm_part, s.done_counter, rp, fbins);
+    }
+
+    // LDS plan: up to 64 KiB of 32-bit counters, replicated per lane where bins are few;
+    // more than 16384 bins are covered in slices of 32768 (128 KiB), one slice per blockIdx.y
+    uint32_t bins_local = bins, rep_shift = 0;
+    if (bins <= 16384) {
+        while (rep_shift < 5 && (static_cast<uint64_t>(bins) << (rep_shift + 1)) <= 16384) ++rep_shift;
+    } else if (bins > 32768) {
+        bins_local = 32768;
+    }
+    const uint32_t ny = (bins + bins_local - 1) / bins_local;
+    const size_t lds = static_cast<size_t>(bins_local << rep_shift) * sizeof(uint32_t);
+    if (lds > 64 * 1024) {
+        EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<T, VEC>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              static_cast<int>(lds)));
+    }
+    // enough items per block that zeroing and flushing the LDS histogram stays small
+    const int per_thread = (bins_local << rep_shift) > 16384 ? 64 : 16;
+    const uint32_t gx = grid_for(g.n_items, kHistBlock, per_thread, ctx->num_cu * 2);
+    k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(grad, g, rp, bins, bins_local, rep_shift,
+                                                          counts, s.nonfinite, s.done_counter + 1, res);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+int launch_entropy(edgc_ctx* ctx, const void* grad, edgc_dtype dt, const SampleGeom& g,
+                   uint32_t bins, const float* range, edgc_entropy_result* out,
+                   uint64_t* counts_out, hipStream_t st)
+{
+    int rc;
+    if (dt == EDGC_F32) {
+        const float* p = static_cast<const float*>(grad);
+        rc = (g.vec == 4) ? run_entropy<float, 4>(ctx, p, g, bins, range, counts_out, st)
+                          : run_entropy<float, 1>(ctx, p, g, bins, range, counts_out, st);
+    } else {
+        const uint16_t* p = static_cast<const uint16_t*>(grad);
+        rc = (g.vec == 8) ? run_entropy<uint16_t, 8>(ctx, p, g, bins, range, counts_out, st)
+                          : run_entropy<uint16_t, 1>(ctx, p, g, bins, range, counts_out, st);
+    }
+    if (rc != EDGC_OK) return rc;
+    EDGC_HIP_TRY(ctx, hipMemcpyAsync(out, ctx->s.result_dev, sizeof(edgc_entropy_result),
+                                     hipMemcpyDeviceToHost, st));
+    return EDGC_OK;
+}
+
+int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uint64_t cap,
+                          hipStream_t st)
+{
+    if (g.n_items == 0) return EDGC_OK;
+    const uint32_t gx = grid_for(g.n_items, 256, 4, 65535);
+    k_sample_indices<<<gx, 256, 0, st>>>(g, idx, cap);
+    EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+}  // namespace edgc

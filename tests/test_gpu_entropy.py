@@ -1,0 +1,147 @@
+"""GPU parity: edgc_sample_indices / edgc_entropy_estimate against the CPU oracle.
+
+Bar: sample indices, range and histogram counts bit-exact; entropy within 1e-5
+absolute (both sides evaluate it in fp64 from identical integer counts)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import edgc_inputs as gen
+import paper_2511_10333_amd as edgc
+from oracle import edgc_oracle as orc
+from gpu_util import ctx, to_dev
+
+pytestmark = pytest.mark.gpu
+
+H_TOL = 1e-5
+
+
+def _compare(x_host, stride, chunk, seed, step, bins, value_range=None, x_dev=None):
+    ref = orc.entropy(x_host, stride, chunk, seed, step, bins, value_range)
+    xd = to_dev(x_host) if x_dev is None else x_dev
+    counts = torch.full((bins,), -1, dtype=torch.int64, device="cuda")
+    got = ctx().entropy_estimate(xd, stride, chunk, seed, step, bins, value_range, counts)
+    assert got.status == 0
+    assert (got.n_sampled, got.n_nonfinite) == (ref.n_sampled, ref.n_nonfinite)
+    assert (got.lo, got.hi) == (ref.lo, ref.hi)
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
+    assert abs(got.H_bits - ref.H_bits) <= H_TOL
+    if math.isinf(ref.h_diff_nats):
+        assert got.h_diff_nats == ref.h_diff_nats
+    else:
+        assert abs(got.h_diff_nats - ref.h_diff_nats) <= H_TOL
+    return got, ref
+
+
+@pytest.mark.parametrize("n,stride,chunk", [(1, 1, 1), (1000, 7, 3), (4097, 100, 64), (100_000, 10, 1),
+                                             (1_048_576, 100, 64), (300_007, 4, 128), (50, 100, 8),
+                                             (70_001, 1, 64), (5000, 3, 4096)])
+def test_sample_indices_bit_exact(n, stride, chunk):
+    for seed, step in [(0, 0), (123, 7), (2**63 + 5, 2**40)]:
+        want = orc.sample_indices(n, stride, chunk, seed, step)
+        buf = torch.full((max(want.size, 1) + 8,), -1, dtype=torch.int64, device="cuda")
+        cnt = ctx().sample_indices(n, stride, chunk, seed, step, buf)
+        torch.cuda.synchronize()
+        assert cnt == want.size
+        got = buf.cpu().numpy()
+        assert np.array_equal(got[:cnt].astype(np.uint64), want)
+        assert np.all(got[cnt:] == -1)                      # nothing written past the sample
+
+
+def test_config1_matrix_sample_one_percent_256_bins():
+    w = gen.WORKLOADS["cfg1_1024sq_r4"]
+    (_, g), = gen.workload_matrices("cfg1_1024sq_r4")
+    for chunk in (64, 1):
+        for step in range(3):
+            got, ref = _compare(g.reshape(-1), w["stride"], chunk, w["seed"], step, w["bins"])
+            assert abs(got.n_sampled - g.size // 100) <= 64
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stride,chunk,bins", [(1, 64, 256), (10, 64, 4096), (100, 64, 65536),
+                                                (1000, 64, 1024), (7, 33, 1000), (10, 1, 256),
+                                                (1, 1, 100000), (3, 8, 20000)])
+def test_laplace_mixture_buffer(dtype, stride, chunk, bins):
+    n = (1 << 22) + 12345                                   # several tiles and a ragged tail
+    x = gen.laplace_mixture(n, seed=0, dtype=dtype)
+    _compare(x, stride, chunk, 7, 3, bins)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unaligned_base_pointer_uses_scalar_path(dtype):
+    n = 200_003
+    x = gen.laplace_mixture(n + 1, seed=3, dtype=dtype)
+    xd = to_dev(x)[1:]                                      # 4- or 2-byte aligned only
+    _compare(x[1:], 5, 64, 1, 1, 512, x_dev=xd)
+    _compare(x[1:], 1, 64, 1, 1, 512, x_dev=xd)
+
+
+def test_caller_range_and_outliers_clamped():
+    x = gen.laplace_mixture(500_000, seed=4)
+    _compare(x, 4, 64, 0, 0, 1024, value_range=(-0.01, 0.01))
+    _compare(x, 1, 64, 0, 0, 64, value_range=(0.0, 0.0))   # degenerate range: everything in bin 0
+
+
+def test_nonfinite_values_are_skipped_and_counted():
+    x = gen.gaussian(300_000, 1e-3, 1)
+    x[::1000] = np.nan
+    x[5::3000] = np.inf
+    x[7::5000] = -np.inf
+    got, ref = _compare(x, 1, 64, 0, 0, 512)
+    assert got.n_nonfinite == ref.n_nonfinite > 0
+
+
+def test_special_cases_constant_uniform_two_values():
+    c = np.full(100_000, 0.125, dtype=np.float32)
+    got, _ = _compare(c, 1, 64, 0, 0, 256)
+    assert got.H_bits == 0.0 and got.h_diff_nats == -math.inf
+    bins = 1024
+    u = np.repeat(np.arange(bins, dtype=np.float32) + 0.5, 5)
+    got, _ = _compare(u, 1, 64, 0, 0, bins, value_range=(0.0, float(bins)))
+    assert abs(got.H_bits - 10.0) < 1e-9
+    two = np.array([-1.0] * 4096 + [3.0] * 4096, dtype=np.float32)
+    got, _ = _compare(two, 1, 64, 0, 0, 64)
+    assert abs(got.H_bits - 1.0) < 1e-12
+
+
+def test_gaussian_lemma2_on_device():
+    sigma = 1e-3
+    x = gen.gaussian(4_000_000, sigma, 9)
+    got = ctx().entropy_estimate(to_dev(x), 1, 64, 0, 0, 4096)
+    assert abs(got.h_diff_nats - (math.log(sigma) + 0.5 * math.log(2 * math.pi * math.e))) < 5e-3
+
+
+def test_all_nonfinite_sample_reports_status_and_empty_sample_is_an_error():
+    x = torch.full((4096,), float("nan"), device="cuda")
+    got = ctx().entropy_estimate(x, 1, 64, 0, 0, 16)
+    assert got.status == edgc.binding.ENONFINITE and got.n_nonfinite == 4096
+    ok = ctx().entropy_estimate(torch.ones(4096, device="cuda"), 1, 64, 0, 0, 16)   # context still usable
+    assert ok.status == 0 and ok.H_bits == 0.0
+    # 10 elements, chunk 8 => two chunks; with stride 100 almost every step selects nothing
+    small = torch.ones(10, device="cuda")
+    step = next(s for s in range(100) if orc.sample_slot(0, s, 100) >= 2)
+    with pytest.raises(edgc.EdgcError) as e:
+        ctx().entropy_estimate(small, 100, 8, 0, step, 16)
+    assert e.value.code == edgc.binding.ENONFINITE
+
+
+def test_bad_arguments_rejected_before_launch():
+    x = torch.ones(64, device="cuda")
+    c = ctx()
+    for kw in [dict(stride=0), dict(chunk=0), dict(bins=0), dict(bins=(1 << 20) + 1)]:
+        a = dict(stride=1, chunk=1, bins=16); a.update(kw)
+        with pytest.raises(edgc.EdgcError) as e:
+            c.entropy_estimate(x, a["stride"], a["chunk"], 0, 0, a["bins"])
+        assert e.value.code == edgc.binding.EINVAL
+    with pytest.raises(edgc.EdgcError):
+        c.entropy_estimate(x, 1, 1, 0, 0, 16, value_range=(1.0, 0.0))
+
+
+def test_repeated_calls_are_deterministic():
+    x = to_dev(gen.laplace_mixture(1 << 20, seed=8))
+    a = ctx().entropy_estimate(x, 10, 64, 5, 5, 4096)
+    for _ in range(3):
+        b = ctx().entropy_estimate(x, 10, 64, 5, 5, 4096)
+        assert (a.H_bits, a.h_diff_nats, a.lo, a.hi) == (b.H_bits, b.h_diff_nats, b.lo, b.hi)
