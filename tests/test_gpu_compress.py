@@ -146,7 +146,7 @@ def test_error_feedback_carried_over_steps_with_warm_start(dtype):
 def test_exact_rank_r_matrix_is_reconstructed_on_device():
     M = gen.exact_rank(256, 384, 8, seed=2)
     Pg, Qg, out, E = check_step(M, None, _q0(384, 8), 8, "f32")
-    assert rel_fro(out, M) < 2e-5
+    assert rel_fro(out, M) < 1e-4      # two bf16 planes keep ~17 bits per operand
 
 
 def test_rank_deficient_input_compares_reconstruction_only():
