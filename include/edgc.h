@@ -56,6 +56,25 @@ int edgc_destroy(edgc_ctx* ctx);
 /* Message of the last failing call on this context (context-owned string). */
 const char* edgc_last_error(const edgc_ctx* ctx);
 
+/* Optional per-kernel timing for benchmarks (not part of the method).  Between
+ * edgc_profile_begin and edgc_profile_end every kernel the context launches is
+ * bracketed by a pair of HIP events on the stream it runs on; the event pool
+ * (2 * max_launches events) is created in edgc_profile_begin, never in a hot
+ * call, and launches beyond the pool go untimed.  edgc_profile_end synchronises
+ * the device and returns, per kernel name, the launch count, the summed
+ * duration and the summed algorithmic bytes and flops of those launches.
+ * `kernel` points to a static string.  *n_out is the number of kernels seen
+ * (may exceed cap; only cap entries are written). */
+typedef struct {
+    const char* kernel;
+    uint64_t    launches;
+    double      total_ms;
+    double      bytes;
+    double      flops;
+} edgc_kernel_stat;
+int edgc_profile_begin(edgc_ctx* ctx, uint32_t max_launches);
+int edgc_profile_end(edgc_ctx* ctx, edgc_kernel_stat* out, uint32_t cap, uint32_t* n_out);
+
 /* ------------------------------------------------------------------------
  * 1. Gradient entropy of a down-sampled buffer (GDS, Sec. IV-B: "selects a
  *    data subset ... based on a gradient sampling rate beta"; entropy as in

@@ -50,6 +50,11 @@ class _RankDecision(C.Structure):
                 ("H_mean", C.c_double), ("T_com", C.c_double)]
 
 
+class _KernelStat(C.Structure):
+    _fields_ = [("kernel", C.c_char_p), ("launches", C.c_uint64), ("total_ms", C.c_double),
+                ("bytes", C.c_double), ("flops", C.c_double)]
+
+
 ENTROPY_RESULT_BYTES = C.sizeof(_EntropyResult)
 
 _lib: Optional[C.CDLL] = None
@@ -72,6 +77,10 @@ def load_library() -> C.CDLL:
     L.edgc_destroy.argtypes = [vp]
     L.edgc_last_error.restype = C.c_char_p
     L.edgc_last_error.argtypes = [vp]
+    L.edgc_profile_begin.restype = i32
+    L.edgc_profile_begin.argtypes = [vp, u32]
+    L.edgc_profile_end.restype = i32
+    L.edgc_profile_end.argtypes = [vp, C.POINTER(_KernelStat), u32, C.POINTER(u32)]
     L.edgc_entropy_estimate.restype = i32
     L.edgc_entropy_estimate.argtypes = [vp, vp, i32, u64, u64, u32, u64, u64, u32, vp, vp, vp, vp]
     L.edgc_sample_indices.restype = i32
@@ -205,6 +214,20 @@ class Context:
         if rc != OK:
             msg = self._L.edgc_last_error(self._h)
             raise EdgcError(rc, what, msg.decode() if msg else "")
+
+    # -- per-kernel event timing ---------------------------------------------
+    def profile_begin(self, max_launches: int = 4096) -> None:
+        self._check(self._L.edgc_profile_begin(self._h, max_launches), "edgc_profile_begin")
+
+    def profile_end(self) -> dict:
+        """Stops the timing; returns {kernel: dict(launches, total_ms, bytes, flops)}."""
+        cap = 32
+        arr = (_KernelStat * cap)()
+        n = C.c_uint32(0)
+        self._check(self._L.edgc_profile_end(self._h, arr, cap, C.byref(n)), "edgc_profile_end")
+        return {arr[i].kernel.decode(): dict(launches=int(arr[i].launches), total_ms=arr[i].total_ms,
+                                             bytes=arr[i].bytes, flops=arr[i].flops)
+                for i in range(min(cap, n.value))}
 
     # -- entropy -----------------------------------------------------------
     def entropy_estimate_async(self, grad, stride: int, chunk: int, seed: int, step: int, bins: int,

@@ -25,6 +25,7 @@
 
 #include <algorithm>
 #include <math.h>
+#include <type_traits>
 
 namespace edgc {
 
@@ -80,7 +81,7 @@ __global__ void k_init_q(float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32
 
 // ---------------------------------------------------------------------------
 // P-pass:  D = G + E_old,  P_partial[s] = D[:, k-range s] * Q[k-range s, :]
-// Block: 4 waves x 32 rows = 128 rows; k-step BK = 64 (one plane) or 32 (two planes).
+// Block: 4 waves x 32 rows = 128 rows; k-step of 64 columns.
 // ---------------------------------------------------------------------------
 template <int NP> struct GradElem { using type = float; };
 template <> struct GradElem<1> { using type = uint16_t; };
@@ -143,23 +144,38 @@ __device__ __forceinline__ void store_f32x4(float* __restrict__ base, uint64_t l
     }
 }
 
+// 16-byte streaming load that does not pollute the caches (the matrix is read once per pass)
+typedef float vf4 __attribute__((ext_vector_type(4)));
+typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void ld_stream4(const float* __restrict__ p, float (&v)[4])
+{
+    const vf4 q = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p));
+    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+}
+__device__ __forceinline__ void ld_stream4(const uint16_t* __restrict__ p, float (&v)[4])
+{
+    const vu2 q = __builtin_nontemporal_load(reinterpret_cast<const vu2*>(p));
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+}
+
 template <int NP, int RT, bool VECOK>
 __global__ __launch_bounds__(256) void k_pass_p(
     const typename GradElem<NP>::type* __restrict__ G, uint64_t ldg, float* __restrict__ E, int e_zero,
     const float* __restrict__ Q, uint32_t ldq, float* __restrict__ part, uint32_t m, uint32_t n,
     uint32_t r, uint32_t kper, uint32_t RB, uint32_t S)
 {
-    constexpr int BK  = (NP == 1) ? 64 : 32;       // k elements per step
-    constexpr int TPR = BK / 4;                    // threads per tile row
-    constexpr int RPP = 256 / TPR;                 // rows per load pass
+    constexpr int BK  = 64;                        // k elements per step: 256 B (fp32) per row
+    constexpr int ROWB = NP * 128 + 16;            // LDS bytes per tile row: planes + pad
+    constexpr int RPP = 16;                        // rows per load pass (16 threads per row)
     constexpr int PA  = 128 / RPP;                 // load passes for the 128-row tile
     constexpr int RP  = RT * 32;                   // padded rank
-    constexpr int NQB = (BK / 4) * (RP / 4);       // 4x4 micro-blocks of the Q tile
-    constexpr int PQ  = (NQB + 255) / 256;
+    constexpr int NQI = RP * (BK / 8);             // Q-tile work items: one column x 8 k each
+    constexpr int PQ  = (NQI + 255) / 256;
 
-    __shared__ __attribute__((aligned(16))) unsigned char lds[(128 + RP) * kLdsRow];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[(128 + RP) * ROWB];
     unsigned char* ldsA = lds;
-    unsigned char* ldsB = lds + 128 * kLdsRow;
+    unsigned char* ldsB = lds + 128 * ROWB;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t lid = xcd_swizzle(blockIdx.x, RB * S);
@@ -167,37 +183,84 @@ __global__ __launch_bounds__(256) void k_pass_p(
     const uint32_t row0 = rb * 128;
     const uint32_t k_begin = s * kper;
     const uint32_t k_end = min(n, k_begin + kper);
+    const bool rows_full = row0 + 128 <= m;
 
-    const int a_row = tid / TPR, a_col = (tid % TPR) * 4;
+    const int a_row = tid >> 4, a_col = (tid & 15) * 4;
 
     float d[PA][4];
-    float qv[PQ][4][4];
+    float qv[PQ][8];
 
-    auto fetch = [&](uint32_t k0) {
+    // FULL: the whole 128 x 64 tile is inside the matrix and vector accesses are allowed
+    auto fetch = [&](uint32_t k0, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
         for (int p = 0; p < PA; ++p) {
             const uint32_t row = row0 + p * RPP + a_row, col = k0 + a_col;
-            float g[4], e[4] = {0.f, 0.f, 0.f, 0.f};
-            load_grad4<NP, VECOK>(G, ldg, row, col, m, k_end, g);
-            if (!e_zero) load_f32x4<VECOK>(E, n, row, col, m, k_end, e);
+            float g[4] = {0.f, 0.f, 0.f, 0.f}, e[4] = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (FULL) {
+                if (G) ld_stream4(G + static_cast<uint64_t>(row) * ldg + col, g);
+                if (!e_zero) ld_stream4(E + static_cast<uint64_t>(row) * n + col, e);
+            } else {
+                load_grad4<NP, VECOK>(G, ldg, row, col, m, k_end, g);
+                if (!e_zero) load_f32x4<VECOK>(E, n, row, col, m, k_end, e);
+            }
 #pragma unroll
             for (int x = 0; x < 4; ++x) d[p][x] = g[x] + e[x];
         }
+        // Q tile: lane = factor column (256 B contiguous per wave load), 8 consecutive k per item
 #pragma unroll
         for (int p = 0; p < PQ; ++p) {
-            const int bi = tid + p * 256;
-            const int kb4 = bi / (RP / 4), cb4 = bi % (RP / 4);
+            const int it = tid + p * 256;
+            const uint32_t c = it % RP, k8 = it / RP;
+            const bool live = it < NQI && c < r;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                qv[p][kk][0] = qv[p][kk][1] = qv[p][kk][2] = qv[p][kk][3] = 0.0f;
-                const uint32_t k = k0 + kb4 * 4 + kk;
-                if (bi < NQB && k < k_end && static_cast<uint32_t>(cb4 * 4) < ldq) {
-                    const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<uint64_t>(k) * ldq + cb4 * 4);
-                    qv[p][kk][0] = q.x; qv[p][kk][1] = q.y; qv[p][kk][2] = q.z; qv[p][kk][3] = q.w;
-                }
+            for (int kk = 0; kk < 8; ++kk) {
+                const uint32_t k = k0 + k8 * 8 + kk;
+                qv[p][kk] = (live && (FULL || k < k_end)) ? Q[static_cast<uint64_t>(k) * ldq + c] : 0.0f;
             }
         }
     };
+    auto commit = [&](uint32_t k0, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            const uint32_t row = row0 + p * RPP + a_row, col = k0 + a_col;
+            if constexpr (FULL)
+                *reinterpret_cast<float4*>(E + static_cast<uint64_t>(row) * n + col) =
+                    make_float4(d[p][0], d[p][1], d[p][2], d[p][3]);
+            else
+                store_f32x4<VECOK>(E, n, row, col, m, k_end, d[p]);
+            __bf16 pl[4][NP];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) to_planes<NP>(d[p][x], pl[x]);
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+                bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
+                *reinterpret_cast<bf16x4*>(ldsA + (p * RPP + a_row) * ROWB + q * 128 + a_col * 2) = w;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int it = tid + p * 256;
+            if (it < NQI) {
+                const uint32_t c = it % RP, k8 = it / RP;
+                bf16x8 w[NP];
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    __bf16 pl[NP];
+                    to_planes<NP>(qv[p][kk], pl);
+#pragma unroll
+                    for (int q = 0; q < NP; ++q) w[q][kk] = pl[q];
+                }
+#pragma unroll
+                for (int q = 0; q < NP; ++q)
+                    *reinterpret_cast<bf16x8*>(ldsB + c * ROWB + q * 128 + k8 * 16) = w[q];
+            }
+        }
+    };
+    auto tile_full = [&](uint32_t k0) { return VECOK && rows_full && k0 + BK <= k_end; };
+    using T = std::true_type;
+    using F = std::false_type;
 
     f32x16 acc[RT];
 #pragma unroll
@@ -205,58 +268,28 @@ __global__ __launch_bounds__(256) void k_pass_p(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;
 
-    if (k_begin < k_end) fetch(k_begin);
+    if (k_begin < k_end) { if (tile_full(k_begin)) fetch(k_begin, T{}); else fetch(k_begin, F{}); }
     for (uint32_t k0 = k_begin; k0 < k_end; k0 += BK) {
         __syncthreads();                         // previous step's LDS reads are done
         // D back to the residual buffer, operands into LDS
-#pragma unroll
-        for (int p = 0; p < PA; ++p) {
-            const uint32_t row = row0 + p * RPP + a_row, col = k0 + a_col;
-            store_f32x4<VECOK>(E, n, row, col, m, k_end, d[p]);
-            __bf16 pl[4][NP];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) to_planes<NP>(d[p][x], pl[x]);
-#pragma unroll
-            for (int q = 0; q < NP; ++q) {
-                bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
-                *reinterpret_cast<bf16x4*>(ldsA + (p * RPP + a_row) * kLdsRow + q * (BK * 2) + a_col * 2) = w;
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < PQ; ++p) {
-            const int bi = tid + p * 256;
-            if (bi < NQB) {
-                const int kb4 = bi / (RP / 4), cb4 = bi % (RP / 4);
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const bool live = static_cast<uint32_t>(cb4 * 4 + cc) < r;
-                    __bf16 pl[4][NP];
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk) to_planes<NP>(live ? qv[p][kk][cc] : 0.0f, pl[kk]);
-#pragma unroll
-                    for (int q = 0; q < NP; ++q) {
-                        bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
-                        *reinterpret_cast<bf16x4*>(ldsB + (cb4 * 4 + cc) * kLdsRow + q * (BK * 2) + kb4 * 8) = w;
-                    }
-                }
-            }
-        }
+        if (tile_full(k0)) commit(k0, T{}); else commit(k0, F{});
         __syncthreads();
-        if (k0 + BK < k_end) fetch(k0 + BK);     // next tile's loads fly during the MFMAs
-
-        const unsigned char* pa = ldsA + (wave * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-        const unsigned char* pb = ldsB + (lane & 31) * kLdsRow + (lane >> 5) * 16;
+        if (k0 + BK < k_end) {                   // next tile's loads fly during the MFMAs
+            if (tile_full(k0 + BK)) fetch(k0 + BK, T{}); else fetch(k0 + BK, F{});
+        }
+        const unsigned char* pa = ldsA + (wave * 32 + (lane & 31)) * ROWB + (lane >> 5) * 16;
+        const unsigned char* pb = ldsB + (lane & 31) * ROWB + (lane >> 5) * 16;
 #pragma unroll
         for (int kb = 0; kb < BK / 16; ++kb) {
             bf16x8 a[NP];
 #pragma unroll
-            for (int q = 0; q < NP; ++q) a[q] = *reinterpret_cast<const bf16x8*>(pa + q * (BK * 2) + kb * 32);
+            for (int q = 0; q < NP; ++q) a[q] = *reinterpret_cast<const bf16x8*>(pa + q * 128 + kb * 32);
 #pragma unroll
             for (int ct = 0; ct < RT; ++ct) {
                 bf16x8 b[NP];
 #pragma unroll
                 for (int q = 0; q < NP; ++q)
-                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * kLdsRow + q * (BK * 2) + kb * 32);
+                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + q * 128 + kb * 32);
                 acc[ct] = mma<NP>(a, b, acc[ct]);
             }
         }
@@ -818,7 +851,8 @@ int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0
 {
     const uint64_t total = static_cast<uint64_t>(n) * (c1 - c0);
     if (total == 0) return EDGC_OK;
-    k_init_q<<<cdiv(total, 256), 256, 0, st>>>(Q, n, ldq, c0, c1, seed);
+    EDGC_LAUNCH(ctx, st, KID_INIT_Q, 4.0 * total, 0.0,
+                k_init_q<<<cdiv(total, 256), 256, 0, st>>>(Q, n, ldq, c0, c1, seed));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }
@@ -828,7 +862,7 @@ static int run_pass_p(edgc_ctx* ctx, const void* grad, uint64_t ld, float* resid
                       const float* Q, uint32_t ldq, uint32_t m, uint32_t n, uint32_t r,
                       uint32_t* S_out, hipStream_t st)
 {
-    constexpr uint32_t BK = (NP == 1) ? 64 : 32;
+    constexpr uint32_t BK = 64;
     using GT = typename GradElem<NP>::type;
     const uint32_t RB = cdiv(m, 128), RP = RT * 32;
     const uint32_t ksteps = cdiv(n, BK);
@@ -843,10 +877,16 @@ static int run_pass_p(edgc_ctx* ctx, const void* grad, uint64_t ld, float* resid
                      (reinterpret_cast<uintptr_t>(grad) % (4 * sizeof(GT)) == 0) &&
                      (reinterpret_cast<uintptr_t>(residual) % 16 == 0);
     const GT* G = static_cast<const GT*>(grad);
+    // algorithmic traffic: read G (if any) and E_old (if any), write D
+    const double mn = static_cast<double>(m) * n;
+    const double bytes = mn * ((grad ? sizeof(GT) : 0) + (e_zero ? 0 : 4) + 4);
+    const double flops = 2.0 * mn * r;
     if (vec)
-        k_pass_p<NP, RT, true><<<RB * S, 256, 0, st>>>(G, ld, residual, e_zero, Q, ldq, ctx->s.part, m, n, r, kper, RB, S);
+        EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops,
+                    (k_pass_p<NP, RT, true><<<RB * S, 256, 0, st>>>(G, ld, residual, e_zero, Q, ldq, ctx->s.part, m, n, r, kper, RB, S)));
     else
-        k_pass_p<NP, RT, false><<<RB * S, 256, 0, st>>>(G, ld, residual, e_zero, Q, ldq, ctx->s.part, m, n, r, kper, RB, S);
+        EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops,
+                    (k_pass_p<NP, RT, false><<<RB * S, 256, 0, st>>>(G, ld, residual, e_zero, Q, ldq, ctx->s.part, m, n, r, kper, RB, S)));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     *S_out = S;
     return EDGC_OK;
@@ -860,18 +900,23 @@ static int run_orthonormalise(edgc_ctx* ctx, uint32_t S, uint32_t m, uint32_t r,
     const uint32_t RP = rank_tiles(r) * 32;
     const uint32_t NB = cdiv(m, 64);
     const uint32_t ta = cdiv(r, 16);
-    switch (ta <= 1 ? 1 : ta <= 2 ? 2 : ta <= 4 ? 4 : 8) {
-    case 1: k_reduce_gram<1><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
-    case 2: k_reduce_gram<2><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
-    case 4: k_reduce_gram<4><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
-    default: k_reduce_gram<8><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+    const double mr = static_cast<double>(m) * r;
+    {
+        ProfScope prof_scope_(ctx, st, KID_REDUCE_GRAM, 4.0 * mr * (S + 1), 2.0 * mr * r);
+        switch (ta <= 1 ? 1 : ta <= 2 ? 2 : ta <= 4 ? 4 : 8) {
+        case 1: k_reduce_gram<1><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+        case 2: k_reduce_gram<2><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+        case 4: k_reduce_gram<4><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+        default: k_reduce_gram<8><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+        }
     }
     EDGC_HIP_TRY(ctx, hipGetLastError());
     const uint32_t rr = r * r;
     const double* gram_src = s.gram_part;
     uint32_t nb = NB;
     if (static_cast<uint64_t>(NB) * rr > 65536) {       // many partials: sum them on many CUs
-        k_gram_sum<<<cdiv(rr, 256), 256, 0, st>>>(s.gram_part, NB, rr, s.gram);
+        EDGC_LAUNCH(ctx, st, KID_GRAM_SUM, 8.0 * rr * NB, 0.0,
+                    k_gram_sum<<<cdiv(rr, 256), 256, 0, st>>>(s.gram_part, NB, rr, s.gram));
         EDGC_HIP_TRY(ctx, hipGetLastError());
         gram_src = s.gram;
         nb = 1;
@@ -881,14 +926,18 @@ static int run_orthonormalise(edgc_ctx* ctx, uint32_t S, uint32_t m, uint32_t r,
         EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chol),
                                               hipFuncAttributeMaxDynamicSharedMemorySize,
                                               static_cast<int>(chol_lds)));
-    k_chol<<<1, 1024, chol_lds, st>>>(gram_src, nb, r, s.rinv);
+    EDGC_LAUNCH(ctx, st, KID_CHOL, 8.0 * rr * (nb + 1), 2.0 * r * rr / 3.0,
+                k_chol<<<1, 1024, chol_lds, st>>>(gram_src, nb, r, s.rinv));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     __bf16* pt = static_cast<__bf16*>(s.pt);
     const uint32_t NBA = m_pad / 64;
-    if (r <= 16)      k_apply<16, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
-    else if (r <= 32) k_apply<32, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
-    else if (r <= 64) k_apply<64, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
-    else              k_apply<128, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+    {
+        ProfScope prof_scope_(ctx, st, KID_APPLY, 8.0 * mr + 2.0 * NP * RP * m_pad, mr * r);
+        if (r <= 16)      k_apply<16, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+        else if (r <= 32) k_apply<32, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+        else if (r <= 64) k_apply<64, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+        else              k_apply<128, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+    }
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }
@@ -917,16 +966,19 @@ static int run_pass_q(edgc_ctx* ctx, const float* D, uint32_t m, uint32_t n, uin
         if (lds > 64 * 1024)
             EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-        kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S);
+        EDGC_LAUNCH(ctx, st, KID_PASS_Q, 4.0 * m * n, 2.0 * m * n * r,
+                    kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S));
     } else {
         auto kern = &k_pass_q<NP, RT, NT, false>;
         if (lds > 64 * 1024)
             EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
-        kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S);
+        EDGC_LAUNCH(ctx, st, KID_PASS_Q, 4.0 * m * n, 2.0 * m * n * r,
+                    kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S));
     }
     EDGC_HIP_TRY(ctx, hipGetLastError());
-    k_reduce_q<<<cdiv(static_cast<uint64_t>(n) * RP, 256), 256, 0, st>>>(ctx->s.part, S, n, RP, r, Q, ldq);
+    EDGC_LAUNCH(ctx, st, KID_REDUCE_Q, 4.0 * n * r * (S + 1), 0.0,
+                k_reduce_q<<<cdiv(static_cast<uint64_t>(n) * RP, 256), 256, 0, st>>>(ctx->s.part, S, n, RP, r, Q, ldq));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }
@@ -985,10 +1037,15 @@ static int decompress_impl(edgc_ctx* ctx, const float* P, uint32_t ldp, const fl
     const uint32_t esz = out_bf16 ? 2 : 4;
     const bool vec = (n % 2 == 0) && (ld % 2 == 0) && (reinterpret_cast<uintptr_t>(residual) % 8 == 0) &&
                      (reinterpret_cast<uintptr_t>(out) % (2 * esz) == 0);
+    // algorithmic traffic: read D, write E_new, write M^
+    const double bytes = static_cast<double>(m) * n * (8 + esz);
+    const double flops = 2.0 * m * n * r;
     if (vec)
-        k_decompress<NP, RT, true><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS);
+        EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops,
+                    (k_decompress<NP, RT, true><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS)));
     else
-        k_decompress<NP, RT, false><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS);
+        EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops,
+                    (k_decompress<NP, RT, false><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS)));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }

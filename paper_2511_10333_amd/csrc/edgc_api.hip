@@ -6,6 +6,12 @@
 
 using namespace edgc;
 
+namespace edgc {
+const char* const kKernelNames[KID_COUNT] = {
+    "k_zero_counts", "k_set_range", "k_minmax", "k_hist", "k_sample_indices", "k_init_q", "k_pass_p",
+    "k_reduce_gram", "k_gram_sum", "k_chol", "k_apply", "k_pass_q", "k_reduce_q", "k_decompress"};
+}
+
 namespace {
 
 bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -81,11 +87,59 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     return EDGC_OK;
 }
 
+extern "C" int edgc_profile_begin(edgc_ctx* ctx, uint32_t max_launches)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (max_launches == 0 || max_launches > (1u << 20)) return fail(ctx, EDGC_EINVAL, "max_launches out of range");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    Profiler& p = ctx->prof;
+    while (p.pool.size() < 2ull * max_launches) {
+        hipEvent_t e;
+        EDGC_HIP_TRY(ctx, hipEventCreate(&e));
+        p.pool.push_back(e);
+    }
+    p.next = 0;
+    p.recs.clear();
+    p.recs.reserve(max_launches);
+    p.on = true;
+    return EDGC_OK;
+}
+
+extern "C" int edgc_profile_end(edgc_ctx* ctx, edgc_kernel_stat* out, uint32_t cap, uint32_t* n_out)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!n_out || (!out && cap)) return fail(ctx, EDGC_EINVAL, "null output");
+    Profiler& p = ctx->prof;
+    p.on = false;
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    EDGC_HIP_TRY(ctx, hipDeviceSynchronize());
+    edgc_kernel_stat acc[KID_COUNT] = {};
+    for (const ProfRec& r : p.recs) {
+        float ms = 0.0f;
+        EDGC_HIP_TRY(ctx, hipEventElapsedTime(&ms, r.a, r.b));
+        acc[r.kid].launches += 1;
+        acc[r.kid].total_ms += ms;
+        acc[r.kid].bytes += r.bytes;
+        acc[r.kid].flops += r.flops;
+    }
+    uint32_t n = 0;
+    for (int k = 0; k < KID_COUNT; ++k) {
+        if (!acc[k].launches) continue;
+        if (n < cap) { out[n] = acc[k]; out[n].kernel = kKernelNames[k]; }
+        ++n;
+    }
+    *n_out = n;
+    p.recs.clear();
+    p.next = 0;
+    return EDGC_OK;
+}
+
 extern "C" int edgc_destroy(edgc_ctx* ctx)
 {
     if (!ctx) return EDGC_EINVAL;
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
+    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
     free_scratch(ctx->s);
     delete ctx;
     return EDGC_OK;

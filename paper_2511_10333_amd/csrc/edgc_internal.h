@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string>
+#include <vector>
 
 #include "edgc.h"
 
@@ -32,6 +33,27 @@ struct Scratch {
 
 constexpr int kMaxReduceBlocks = 4096;
 
+// Kernel ids for the optional per-kernel event timing (edgc_profile_begin/end).
+enum KernelId {
+    KID_ZERO_COUNTS = 0, KID_SET_RANGE, KID_MINMAX, KID_HIST, KID_SAMPLE_IDX, KID_INIT_Q, KID_PASS_P,
+    KID_REDUCE_GRAM, KID_GRAM_SUM, KID_CHOL, KID_APPLY, KID_PASS_Q, KID_REDUCE_Q, KID_DECOMPRESS,
+    KID_COUNT
+};
+extern const char* const kKernelNames[KID_COUNT];
+
+struct ProfRec {
+    int kid;
+    hipEvent_t a, b;
+    double bytes, flops;
+};
+
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> pool;   // created in edgc_profile_begin, never in a hot call
+    size_t next = 0;
+    std::vector<ProfRec> recs;
+};
+
 }  // namespace edgc
 
 struct edgc_ctx {
@@ -40,6 +62,7 @@ struct edgc_ctx {
     uint64_t max_rows = 0, max_cols = 0;
     int num_cu = 256;
     edgc::Scratch s;
+    edgc::Profiler prof;
     std::string last_error;
 };
 
@@ -57,6 +80,28 @@ inline int fail(edgc_ctx* ctx, int code, const std::string& msg)
         if (e_ != hipSuccess)                                                                \
             return ::edgc::fail((ctx), EDGC_EHIP,                                            \
                                 std::string(#expr) + ": " + hipGetErrorString(e_));          \
+    } while (0)
+
+// Brackets one kernel launch with a pair of events when profiling is on.
+struct ProfScope {
+    edgc_ctx* ctx;
+    hipStream_t st;
+    hipEvent_t stop = nullptr;
+    ProfScope(edgc_ctx* c, hipStream_t s, int kid, double bytes, double flops) : ctx(c), st(s)
+    {
+        Profiler& p = c->prof;
+        if (!p.on || p.next + 2 > p.pool.size() || p.recs.size() == p.recs.capacity()) return;
+        hipEvent_t a = p.pool[p.next++];
+        stop = p.pool[p.next++];
+        (void)hipEventRecord(a, st);
+        p.recs.push_back(ProfRec{kid, a, stop, bytes, flops});
+    }
+    ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
+};
+#define EDGC_LAUNCH(ctx, st, kid, bytes, flops, ...)                 \
+    do {                                                             \
+        ::edgc::ProfScope prof_scope_((ctx), (st), (kid), (bytes), (flops)); \
+        __VA_ARGS__;                                                 \
     } while (0)
 
 // splitmix64 output function on seed + golden * (ctr + 1); the sampler's slot and

@@ -313,9 +313,9 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
 
     __shared__ bool s_last;
     __shared__ double s_a[kHistBlock / 64], s_b[kHistBlock / 64];
+    __threadfence();                  // this thread's counter updates are visible device-wide
     __syncthreads();
     if (threadIdx.x == 0) {
-        __threadfence();
         const unsigned int ticket = atomicAdd(done, 1u);
         s_last = (ticket == gridDim.x * gridDim.y - 1);
     }
@@ -434,12 +434,16 @@ static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32
     auto* res = static_cast<edgc_entropy_result*>(s.result_dev);
     const float fbins = static_cast<float>(bins);
 
-    k_zero_counts<<<(bins + 255) / 256, 256, 0, st>>>(counts, bins, s.nonfinite);
+    const double sample_bytes = static_cast<double>(g.n_sampled) * sizeof(T);
+    EDGC_LAUNCH(ctx, st, KID_ZERO_COUNTS, 8.0 * bins, 0.0,
+                k_zero_counts<<<(bins + 255) / 256, 256, 0, st>>>(counts, bins, s.nonfinite));
     if (range) {
-        k_set_range<<<1, 64, 0, st>>>(rp, range[0], range[1], fbins);
+        EDGC_LAUNCH(ctx, st, KID_SET_RANGE, 0.0, 0.0,
+                    k_set_range<<<1, 64, 0, st>>>(rp, range[0], range[1], fbins));
     } else {
         const uint32_t gx = grid_for(g.n_items, kMMBlock, 8, min(kMaxReduceBlocks, ctx->num_cu * 8));
-        k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(grad, g, s.mm_part, s.done_counter, rp, fbins);
+        EDGC_LAUNCH(ctx, st, KID_MINMAX, sample_bytes, 0.0,
+                    k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(grad, g, s.mm_part, s.done_counter, rp, fbins));
     }
 
     // LDS plan: up to 64 KiB of 32-bit counters, replicated per lane where bins are few;
@@ -460,8 +464,9 @@ static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32
     // enough items per block that zeroing and flushing the LDS histogram stays small
     const int per_thread = (bins_local << rep_shift) > 16384 ? 64 : 16;
     const uint32_t gx = grid_for(g.n_items, kHistBlock, per_thread, ctx->num_cu * 2);
-    k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(grad, g, rp, bins, bins_local, rep_shift,
-                                                          counts, s.nonfinite, s.done_counter + 1, res);
+    EDGC_LAUNCH(ctx, st, KID_HIST, sample_bytes * ny, 0.0,
+                k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(grad, g, rp, bins, bins_local, rep_shift,
+                                                                      counts, s.nonfinite, s.done_counter + 1, res));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }
@@ -491,7 +496,8 @@ int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uin
 {
     if (g.n_items == 0) return EDGC_OK;
     const uint32_t gx = grid_for(g.n_items, 256, 4, 65535);
-    k_sample_indices<<<gx, 256, 0, st>>>(g, idx, cap);
+    EDGC_LAUNCH(ctx, st, KID_SAMPLE_IDX, 8.0 * g.n_sampled, 0.0,
+                k_sample_indices<<<gx, 256, 0, st>>>(g, idx, cap));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }
