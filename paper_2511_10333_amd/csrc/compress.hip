@@ -532,35 +532,32 @@ __global__ __launch_bounds__(256) void k_apply(float* __restrict__ P, uint32_t l
 
 // ---------------------------------------------------------------------------
 // Q-pass:  Q_partial[s] = D[row-range s, :]^T * P^[row-range s, :]
-// Block: 4 waves, all on the same 32*NT columns, each wave on its own 64-row
-// stages; lane (jl, g) loads rows 8g..8g+7 of a 16-row step at columns
-// NT*jl..NT*jl+NT-1, which are the A-fragments (M = column, K = row) as they
-// stand: no transposition of D.  The P^ operand comes from the transposed copy
-// through a wave-private LDS tile.  Waves are summed through LDS at the end.
+// Block: 4 waves share 64-row stages; wave w owns columns [w*32*NT, (w+1)*32*NT)
+// of the block's 128*NT-column strip.  Lane (jl, g) loads rows 8g..8g+7 of a
+// 16-row step at columns NT*jl..NT*jl+NT-1: these are MFMA A-fragments
+// (M = column, K = row) as they stand, so D is never transposed.  The P^
+// operand comes from the transposed bf16 copy through a double-buffered LDS
+// tile shared by the four waves (one barrier per stage).
 // ---------------------------------------------------------------------------
-template <int NT, bool VECOK>
+template <int NT, bool FULL>
 __device__ __forceinline__ void load_d_rows(const float* __restrict__ D, uint32_t n, uint32_t m,
                                             uint32_t row_base, uint32_t col, float (&v)[8][NT])
 {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
         const uint32_t row = row_base + q;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) v[q][t] = 0.0f;
-        if (row < m && col < n) {
-            const float* p = D + static_cast<uint64_t>(row) * n + col;
-            if (VECOK && col + NT <= n) {
-                if constexpr (NT == 4) {
-                    const float4 x = *reinterpret_cast<const float4*>(p);
-                    v[q][0] = x.x; v[q][1] = x.y; v[q][2] = x.z; v[q][3] = x.w;
-                } else {
-                    const float2 x = *reinterpret_cast<const float2*>(p);
-                    v[q][0] = x.x; v[q][1] = x.y;
-                }
+        const float* p = D + static_cast<uint64_t>(row) * n + col;
+        if constexpr (FULL) {
+            if constexpr (NT == 4) {
+                const float4 x = *reinterpret_cast<const float4*>(p);
+                v[q][0] = x.x; v[q][1] = x.y; v[q][2] = x.z; v[q][3] = x.w;
             } else {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) if (col + t < n) v[q][t] = p[t];
+                const float2 x = *reinterpret_cast<const float2*>(p);
+                v[q][0] = x.x; v[q][1] = x.y;
             }
+        } else {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) v[q][t] = (row < m && col + t < n) ? p[t] : 0.0f;
         }
     }
 }
@@ -572,20 +569,22 @@ __global__ __launch_bounds__(256) void k_pass_q(const float* __restrict__ D,
                                                 uint32_t stages_per_split, uint32_t CB, uint32_t S)
 {
     constexpr int RP = RT * 32;
-    constexpr int ROWB = NP * 128 + 16;              // LDS bytes per column c: 64 rows x NP planes + pad
-    constexpr int WAVE_LDS = RP * ROWB;
+    constexpr int ROWB = NP * 128 + 16;              // LDS bytes per factor column: 64 rows x NP planes + pad
+    constexpr int TILE = RP * ROWB;
     constexpr int W = 32 * NT;
-    extern __shared__ __attribute__((aligned(16))) unsigned char qlds[];
+    constexpr int NSEG = RP * NP * 8;                // 16-byte segments of one P^ tile
+    constexpr int PS = (NSEG + 255) / 256;
+    extern __shared__ __attribute__((aligned(16))) unsigned char qlds[];   // 2 tiles
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int jl = lane & 31, g = lane >> 5;
     const uint32_t lid = xcd_swizzle(blockIdx.x, CB * S);
     const uint32_t s = lid / CB, cb = lid % CB;
-    const uint32_t j0 = cb * W;
-    const uint32_t total_stages = m_pad / 64;
+    const uint32_t jw0 = cb * 4 * W + wave * W;
+    const uint32_t col = jw0 + NT * jl;
     const uint32_t st_begin = s * stages_per_split;
-    const uint32_t st_end = min(total_stages, st_begin + stages_per_split);
-    unsigned char* my = qlds + wave * WAVE_LDS;
+    const uint32_t st_end = min(m_pad / 64, st_begin + stages_per_split);
+    const bool cols_full = VECOK && (jw0 + W <= n);
 
     f32x16 acc[RT][NT];
 #pragma unroll
@@ -595,21 +594,47 @@ __global__ __launch_bounds__(256) void k_pass_q(const float* __restrict__ D,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[ct][t][v] = 0.0f;
 
-    const uint32_t col = j0 + NT * jl;
-    for (uint32_t st = st_begin + wave; st < st_end; st += 4) {
-        const uint32_t i0 = st * 64;
-        // P^ tile: RP columns x 64 rows x NP planes, 16-byte segments, 8 per (column, plane)
-        for (int idx = lane; idx < RP * NP * 8; idx += 64) {
-            const int seg = idx % 8, cp = idx / 8, c = cp % RP, p = cp / RP;
-            const bf16x8 w = *reinterpret_cast<const bf16x8*>(
-                pt + (static_cast<size_t>(p) * RP + c) * m_pad + i0 + seg * 8);
-            *reinterpret_cast<bf16x8*>(my + c * ROWB + p * 128 + seg * 16) = w;
+    bf16x8 seg[PS];
+    auto fetch_pt = [&](uint32_t st) {
+#pragma unroll
+        for (int p = 0; p < PS; ++p) {
+            const int it = tid + p * 256;
+            if (it < NSEG) {
+                const int sg = it % 8, cp = it / 8, c = cp % RP, pl = cp / RP;
+                seg[p] = *reinterpret_cast<const bf16x8*>(
+                    pt + (static_cast<size_t>(pl) * RP + c) * m_pad + st * 64 + sg * 8);
+            }
         }
+    };
+    auto store_pt = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < PS; ++p) {
+            const int it = tid + p * 256;
+            if (it < NSEG) {
+                const int sg = it % 8, cp = it / 8, c = cp % RP, pl = cp / RP;
+                *reinterpret_cast<bf16x8*>(qlds + buf * TILE + c * ROWB + pl * 128 + sg * 16) = seg[p];
+            }
+        }
+    };
+
+    if (st_begin < st_end) fetch_pt(st_begin);
+    int buf = 0;
+    for (uint32_t st = st_begin; st < st_end; ++st) {
+        store_pt(buf);
+        __syncthreads();     // tile `buf` is complete; every wave is past its reads of stage st-2
+        if (st + 1 < st_end) fetch_pt(st + 1);
+        const uint32_t i0 = st * 64;
+        const bool full = cols_full && (i0 + 64 <= m);
+        const unsigned char* tile = qlds + buf * TILE;
         float dv[2][8][NT];
-        load_d_rows<NT, VECOK>(D, n, m, i0 + 8 * g, col, dv[0]);
+        if (full) load_d_rows<NT, true>(D, n, m, i0 + 8 * g, col, dv[0]);
+        else      load_d_rows<NT, false>(D, n, m, i0 + 8 * g, col, dv[0]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (u + 1 < 4) load_d_rows<NT, VECOK>(D, n, m, i0 + 16 * (u + 1) + 8 * g, col, dv[(u + 1) & 1]);
+            if (u + 1 < 4) {
+                if (full) load_d_rows<NT, true>(D, n, m, i0 + 16 * (u + 1) + 8 * g, col, dv[(u + 1) & 1]);
+                else      load_d_rows<NT, false>(D, n, m, i0 + 16 * (u + 1) + 8 * g, col, dv[(u + 1) & 1]);
+            }
             bf16x8 a[NT][NP];
 #pragma unroll
             for (int t = 0; t < NT; ++t)
@@ -625,49 +650,15 @@ __global__ __launch_bounds__(256) void k_pass_q(const float* __restrict__ D,
                 bf16x8 b[NP];
 #pragma unroll
                 for (int p = 0; p < NP; ++p)
-                    b[p] = *reinterpret_cast<const bf16x8*>(my + (ct * 32 + jl) * ROWB + p * 128 + u * 32 + g * 16);
+                    b[p] = *reinterpret_cast<const bf16x8*>(tile + (ct * 32 + jl) * ROWB + p * 128 + u * 32 + g * 16);
 #pragma unroll
                 for (int t = 0; t < NT; ++t) acc[ct][t] = mma<NP>(a[t], b, acc[ct][t]);
             }
         }
+        buf ^= 1;
     }
 
-    // sum the four waves: 2,3 -> LDS, 0,1 add; 1 -> LDS, 0 adds
-    constexpr int NACC = RT * NT * 16;
-    float* red = reinterpret_cast<float*>(qlds);
-    __syncthreads();
-    if (wave >= 2) {
-#pragma unroll
-        for (int ct = 0; ct < RT; ++ct)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    red[((wave - 2) * NACC + (ct * NT + t) * 16 + v) * 64 + lane] = acc[ct][t][v];
-    }
-    __syncthreads();
-    if (wave < 2) {
-#pragma unroll
-        for (int ct = 0; ct < RT; ++ct)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    acc[ct][t][v] += red[(wave * NACC + (ct * NT + t) * 16 + v) * 64 + lane];
-    }
-    __syncthreads();
-    if (wave == 1) {
-#pragma unroll
-        for (int ct = 0; ct < RT; ++ct)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    red[((ct * NT + t) * 16 + v) * 64 + lane] = acc[ct][t][v];
-    }
-    __syncthreads();
-    if (wave != 0) return;
-    // accumulator (ct, t, v) of lane l: column j = j0 + NT*rho + t with rho = 8*(v/4) + 4*g + v%4,
+    // accumulator (ct, t, v) of lane l: column j = jw0 + NT*rho + t with rho = 8*(v/4) + 4*g + v%4,
     // factor column c = ct*32 + jl  ->  part[s][j][c]
 #pragma unroll
     for (int ct = 0; ct < RT; ++ct)
@@ -675,12 +666,12 @@ __global__ __launch_bounds__(256) void k_pass_q(const float* __restrict__ D,
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float x = acc[ct][t][v] + red[((ct * NT + t) * 16 + v) * 64 + lane];
-                const uint32_t j = j0 + NT * (8 * (v / 4) + 4 * g + (v % 4)) + t;
-                if (j < n) part[(static_cast<size_t>(s) * n + j) * RP + ct * 32 + jl] = x;
+                const uint32_t j = jw0 + NT * (8 * (v / 4) + 4 * g + (v % 4)) + t;
+                if (j < n) part[(static_cast<size_t>(s) * n + j) * RP + ct * 32 + jl] = acc[ct][t][v];
             }
 }
 
+// Q = sum of the row-split partials, in split order (four independent loads in flight)
 __global__ void k_reduce_q(const float* __restrict__ part, uint32_t S, uint32_t n, uint32_t RP,
                            uint32_t r, float* __restrict__ Q, uint32_t ldq)
 {
@@ -688,8 +679,16 @@ __global__ void k_reduce_q(const float* __restrict__ part, uint32_t S, uint32_t 
     if (t >= static_cast<uint64_t>(n) * RP) return;
     const uint32_t j = static_cast<uint32_t>(t / RP), c = static_cast<uint32_t>(t % RP);
     if (c >= r) return;
+    const size_t stride = static_cast<size_t>(n) * RP;
+    const float* p = part + static_cast<size_t>(j) * RP + c;
     float v = 0.0f;
-    for (uint32_t s = 0; s < S; ++s) v += part[(static_cast<size_t>(s) * n + j) * RP + c];
+    uint32_t s = 0;
+    for (; s + 4 <= S; s += 4) {
+        const float x0 = p[(s + 0) * stride], x1 = p[(s + 1) * stride];
+        const float x2 = p[(s + 2) * stride], x3 = p[(s + 3) * stride];
+        v += x0; v += x1; v += x2; v += x3;
+    }
+    for (; s < S; ++s) v += p[s * stride];
     Q[static_cast<size_t>(j) * ldq + c] = v;
 }
 
@@ -697,24 +696,31 @@ __global__ void k_reduce_q(const float* __restrict__ part, uint32_t S, uint32_t 
 // Decompress:  M^ = P^ Q^T -> grad_out,  E_new = D - M^ (as transmitted), in place.
 // Block: 4 waves x 32 rows; the wave's P^ rows stay in registers as A-fragments;
 // Q rows of a 64-column stage go through LDS, row 2*jl + ct of the stage at LDS
-// row ct*32 + jl so that every lane ends up with two adjacent columns.
+// row ct*32 + jl so that every lane ends up with two adjacent columns (8-byte
+// accesses, 256 B contiguous per half wave).  Q rows and D of the next stage are
+// fetched while the current stage is multiplied and written.
+// One bf16 plane <=> bf16 gradient and output; two planes <=> fp32.
 // ---------------------------------------------------------------------------
 template <int NP, int RT, bool VECOK>
 __global__ __launch_bounds__(256) void k_decompress(
     const float* __restrict__ P, uint32_t ldp, const float* __restrict__ Q, uint32_t ldq, uint32_t m,
-    uint32_t n, uint32_t r, float* __restrict__ E, void* __restrict__ out_, int out_bf16, uint64_t ldo,
+    uint32_t n, uint32_t r, float* __restrict__ E, void* __restrict__ out_, uint64_t ldo,
     uint32_t stages_per_split, uint32_t RB, uint32_t JS)
 {
+    constexpr bool OUT_BF16 = (NP == 1);
     constexpr int KT = RT * 2;                        // 16-wide k blocks over the padded rank
     constexpr int RP = RT * 32;
     constexpr int ROWB = NP * RP * 2 + 16;            // LDS bytes per Q row
+    constexpr int PQ = 64 * (RP / 4) / 256;           // float4 items of the Q stage per thread
     extern __shared__ __attribute__((aligned(16))) unsigned char dlds[];
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int jl = lane & 31, g = lane >> 5;
     const uint32_t lid = xcd_swizzle(blockIdx.x, RB * JS);
     const uint32_t js = lid % JS, rb = lid / JS;
     const uint32_t row0 = rb * 128 + wave * 32;
+    const bool rows_full = row0 + 32 <= m;
 
     // A-fragments: row row0 + jl of P^, k = kb*16 + 8g .. +8
     bf16x8 a[KT][NP];
@@ -723,10 +729,15 @@ __global__ __launch_bounds__(256) void k_decompress(
 #pragma unroll
         for (int kb = 0; kb < KT; ++kb) {
             float v[8];
+            const uint32_t c0 = kb * 16 + 8 * g;
+            if (row < m && c0 + 8 <= r) {
+                const float4 x = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0);
+                const float4 y = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0 + 4);
+                v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+            } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t c = kb * 16 + 8 * g + e;
-                v[e] = (row < m && c < r) ? P[static_cast<size_t>(row) * ldp + c] : 0.0f;
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (row < m && c0 + e < r) ? P[static_cast<size_t>(row) * ldp + c0 + e] : 0.0f;
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -741,49 +752,104 @@ __global__ __launch_bounds__(256) void k_decompress(
     const uint32_t total_stages = (n + 63) / 64;
     const uint32_t st_begin = js * stages_per_split;
     const uint32_t st_end = min(total_stages, st_begin + stages_per_split);
-    for (uint32_t st = st_begin; st < st_end; ++st) {
-        const uint32_t j0 = st * 64;
-        __syncthreads();
-        // stage Q rows j0 .. j0+63: 4 consecutive factor columns per thread
-        for (int idx = tid; idx < 64 * (RP / 4); idx += 256) {
+
+    float qv[PQ][4];
+    float dv[2][16][2];
+    auto fetch_q = [&](uint32_t st) {
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
             const int jj = idx / (RP / 4), c4 = (idx % (RP / 4)) * 4;
-            const uint32_t j = j0 + jj;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            const uint32_t j = st * 64 + jj;
+            qv[p][0] = qv[p][1] = qv[p][2] = qv[p][3] = 0.0f;
             if (j < n && static_cast<uint32_t>(c4) < ldq) {
                 const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(j) * ldq + c4);
-                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-            }
-            __bf16 pl[4][NP];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) to_planes<NP>((static_cast<uint32_t>(c4 + e) < r) ? v[e] : 0.0f, pl[e]);
-            const int lrow = (jj & 1) * 32 + (jj >> 1);
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                bf16x4 w = {pl[0][p], pl[1][p], pl[2][p], pl[3][p]};
-                *reinterpret_cast<bf16x4*>(dlds + lrow * ROWB + p * (RP * 2) + c4 * 2) = w;
+                qv[p][0] = q.x; qv[p][1] = q.y; qv[p][2] = q.z; qv[p][3] = q.w;
             }
         }
-        __syncthreads();
-
-        // D for this lane's 16 rows x 2 adjacent columns, issued before the MFMAs
-        const uint32_t col = j0 + 2 * jl;
-        float dv[16][2];
+    };
+    auto stage_q = [&]() {
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jj = idx / (RP / 4), c4 = (idx % (RP / 4)) * 4;
+            __bf16 pl[4][NP];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) to_planes<NP>((static_cast<uint32_t>(c4 + e) < r) ? qv[p][e] : 0.0f, pl[e]);
+            const int lrow = (jj & 1) * 32 + (jj >> 1);
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+                bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
+                *reinterpret_cast<bf16x4*>(dlds + lrow * ROWB + q * (RP * 2) + c4 * 2) = w;
+            }
+        }
+    };
+    auto stage_full = [&](uint32_t st) { return VECOK && rows_full && st * 64 + 64 <= n; };
+    // D of this lane's 16 rows x 2 adjacent columns
+    auto fetch_d = [&](uint32_t st, float (&d)[16][2], auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const uint32_t col = st * 64 + 2 * jl;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
-            dv[v][0] = dv[v][1] = 0.0f;
-            if (row < m && col < n) {
-                const float* p = E + static_cast<size_t>(row) * n + col;
-                if (VECOK && col + 2 <= n) {
-                    const float2 x = *reinterpret_cast<const float2*>(p);
-                    dv[v][0] = x.x; dv[v][1] = x.y;
-                } else {
-                    dv[v][0] = p[0];
-                    if (col + 1 < n) dv[v][1] = p[1];
-                }
+            const float* p = E + static_cast<size_t>(row) * n + col;
+            if constexpr (FULL) {
+                const float2 x = *reinterpret_cast<const float2*>(p);
+                d[v][0] = x.x; d[v][1] = x.y;
+            } else {
+                d[v][0] = (row < m && col < n) ? p[0] : 0.0f;
+                d[v][1] = (row < m && col + 1 < n) ? p[1] : 0.0f;
             }
         }
+    };
+    auto finish = [&](uint32_t st, const float (&d)[16][2], const f32x16 (&acc)[2], auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const uint32_t col = st * 64 + 2 * jl;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
+            float w0 = acc[0][v], w1 = acc[1][v];
+            float* e = E + static_cast<size_t>(row) * n + col;
+            if constexpr (OUT_BF16) {
+                const __bf16 h0 = static_cast<__bf16>(w0), h1 = static_cast<__bf16>(w1);
+                w0 = static_cast<float>(h0); w1 = static_cast<float>(h1);
+                __bf16* o = static_cast<__bf16*>(out_) + static_cast<size_t>(row) * ldo + col;
+                if constexpr (FULL) {
+                    bf16x2 hh = {h0, h1};
+                    *reinterpret_cast<bf16x2*>(o) = hh;
+                } else if (row < m) {
+                    if (col < n) o[0] = h0;
+                    if (col + 1 < n) o[1] = h1;
+                }
+            } else {
+                float* o = static_cast<float*>(out_) + static_cast<size_t>(row) * ldo + col;
+                if constexpr (FULL) {
+                    *reinterpret_cast<float2*>(o) = make_float2(w0, w1);
+                } else if (row < m) {
+                    if (col < n) o[0] = w0;
+                    if (col + 1 < n) o[1] = w1;
+                }
+            }
+            const float e0 = d[v][0] - w0, e1 = d[v][1] - w1;
+            if constexpr (FULL) {
+                *reinterpret_cast<float2*>(e) = make_float2(e0, e1);
+            } else if (row < m) {
+                if (col < n) e[0] = e0;
+                if (col + 1 < n) e[1] = e1;
+            }
+        }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
 
+    auto run_stage = [&](uint32_t st, float (&dcur)[16][2], float (&dnxt)[16][2]) {
+        __syncthreads();                     // previous stage's LDS reads are done
+        stage_q();
+        __syncthreads();
+        if (st + 1 < st_end) {               // next stage's loads fly during this stage's work
+            fetch_q(st + 1);
+            if (stage_full(st + 1)) fetch_d(st + 1, dnxt, T{}); else fetch_d(st + 1, dnxt, F{});
+        }
         f32x16 acc[2];
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
@@ -798,34 +864,16 @@ __global__ __launch_bounds__(256) void k_decompress(
                 acc[ct] = mma<NP>(a[kb], b, acc[ct]);
             }
         }
+        if (stage_full(st)) finish(st, dcur, acc, T{}); else finish(st, dcur, acc, F{});
+    };
 
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
-            if (row >= m || col >= n) continue;
-            float w0 = acc[0][v], w1 = acc[1][v];
-            if (out_bf16) {
-                const __bf16 h0 = static_cast<__bf16>(w0), h1 = static_cast<__bf16>(w1);
-                w0 = static_cast<float>(h0); w1 = static_cast<float>(h1);
-                __bf16* o = static_cast<__bf16*>(out_) + static_cast<size_t>(row) * ldo + col;
-                if (VECOK && col + 2 <= n) {
-                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-                    bf16x2 hh = {h0, h1};
-                    *reinterpret_cast<bf16x2*>(o) = hh;
-                } else {
-                    o[0] = h0;
-                    if (col + 1 < n) o[1] = h1;
-                }
-            } else {
-                float* o = static_cast<float*>(out_) + static_cast<size_t>(row) * ldo + col;
-                if (VECOK && col + 2 <= n) *reinterpret_cast<float2*>(o) = make_float2(w0, w1);
-                else { o[0] = w0; if (col + 1 < n) o[1] = w1; }
-            }
-            float* e = E + static_cast<size_t>(row) * n + col;
-            const float e0 = dv[v][0] - w0, e1 = dv[v][1] - w1;
-            if (VECOK && col + 2 <= n) *reinterpret_cast<float2*>(e) = make_float2(e0, e1);
-            else { e[0] = e0; if (col + 1 < n) e[1] = e1; }
-        }
+    if (st_begin < st_end) {
+        fetch_q(st_begin);
+        if (stage_full(st_begin)) fetch_d(st_begin, dv[0], T{}); else fetch_d(st_begin, dv[0], F{});
+    }
+    for (uint32_t st = st_begin; st < st_end; st += 2) {
+        run_stage(st, dv[0], dv[1]);
+        if (st + 1 < st_end) run_stage(st + 1, dv[1], dv[0]);
     }
 }
 
@@ -946,14 +994,12 @@ template <int NP, int RT, int NT>
 static int run_pass_q(edgc_ctx* ctx, const float* D, uint32_t m, uint32_t n, uint32_t r, float* Q,
                       uint32_t ldq, uint32_t m_pad, hipStream_t st)
 {
-    constexpr uint32_t RP = RT * 32, W = 32 * NT;
-    constexpr size_t stage_lds = static_cast<size_t>(4) * RP * (NP * 128 + 16);
-    constexpr size_t red_lds = static_cast<size_t>(2) * RT * NT * 16 * 64 * sizeof(float);
-    constexpr size_t lds = stage_lds > red_lds ? stage_lds : red_lds;
-    const uint32_t CB = cdiv(n, W);
+    constexpr uint32_t RP = RT * 32, W4 = 4 * 32 * NT;
+    constexpr size_t lds = static_cast<size_t>(2) * RP * (NP * 128 + 16);
+    const uint32_t CB = cdiv(n, W4);
     const uint32_t stages = m_pad / 64;
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 4;
-    uint32_t S = std::max(1u, std::min(cdiv(stages, 4), target / CB));
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 2;
+    uint32_t S = std::max(1u, std::min(stages, target / CB));
     const uint64_t cap = ctx->s.part_elems / (static_cast<uint64_t>(n) * RP);
     if (cap == 0) return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
     S = static_cast<uint32_t>(std::min<uint64_t>(S, cap));
@@ -998,8 +1044,13 @@ static int compress_impl(edgc_ctx* ctx, const void* grad, uint32_t m, uint32_t n
         if (rc != EDGC_OK) return rc;
         rc = run_orthonormalise<NP>(ctx, S, m, r, P, ldp, m_pad, st);
         if (rc != EDGC_OK) return rc;
-        if constexpr (RT == 4) rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
-        else                   rc = run_pass_q<NP, RT, 4>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
+        // wide strips (4 columns per lane) only when the accumulators fit and there are enough strips
+        if constexpr (RT == 4) {
+            rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
+        } else {
+            if (n >= 4096) rc = run_pass_q<NP, RT, 4>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
+            else           rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
+        }
         if (rc != EDGC_OK) return rc;
     }
     return EDGC_OK;
@@ -1042,10 +1093,10 @@ static int decompress_impl(edgc_ctx* ctx, const float* P, uint32_t ldp, const fl
     const double flops = 2.0 * m * n * r;
     if (vec)
         EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops,
-                    (k_decompress<NP, RT, true><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS)));
+                    (k_decompress<NP, RT, true><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, ld, sps, RB, JS)));
     else
         EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops,
-                    (k_decompress<NP, RT, false><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, out_bf16, ld, sps, RB, JS)));
+                    (k_decompress<NP, RT, false><<<RB * JS, 256, lds, st>>>(P, ldp, Q, ldq, m, n, r, residual, out, ld, sps, RB, JS)));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }
