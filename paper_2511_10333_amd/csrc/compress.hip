@@ -307,218 +307,437 @@ __global__ __launch_bounds__(256) void k_pass_p(
 }
 
 // ---------------------------------------------------------------------------
-// P = sum_s partial[s];  per-block Gram (64 rows) in fp64
+// Orthonormalisation of P (m x r): Cholesky-QR with the Gram matrix in fp64.
+//   k_reduce_gram  P = sum of the column-split partials (split order); Gram tiles of the
+//                  block's rows on v_mfma_f64_16x16x4_f64 (upper-triangle 16x16 tiles)
+//   k_gram_sum     sum of the per-block Gram tiles (many blocks, 8 loads in flight)
+//   k_chol         scaled Cholesky W = D^-1 L L^T D^-1 and R^-1 = D L^-T, one block
+//   k_apply        P^ = P R^-1 on fp64 MFMA, fp32 result in place + bf16 operand copy
+// fp64 MFMA 16x16x4 layout: lane l supplies A[i = l%16][k = l/16] and B[k = l/16][j = l%16];
+// accumulator v of lane l holds D[i = l/16 + 4v][j = l%16].
 // ---------------------------------------------------------------------------
-template <int TA>
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// t-th tile of the upper triangle of a T x T tile grid, row-major: (ta <= tb)
+__host__ __device__ inline void tri_tile(int t, int T, int& ta, int& tb)
+{
+    ta = 0;
+    int len = T;
+    while (t >= len) { t -= len; ++ta; --len; }
+    tb = ta + t;
+}
+
+template <int T16>
 __global__ __launch_bounds__(256) void k_reduce_gram(const float* __restrict__ part, uint32_t S,
                                                      uint32_t m, uint32_t RP, uint32_t r,
                                                      float* __restrict__ P, uint32_t ldp,
-                                                     double* __restrict__ gram_part)
+                                                     double* __restrict__ gram_part,
+                                                     uint32_t chunks_per_block)
 {
-    constexpr int CW = 16 * TA;
-    __shared__ float Ps[64][CW + 1];
-    const int tid = threadIdx.x;
-    const uint32_t row0 = blockIdx.x * 64;
-    for (int idx = tid; idx < 64 * CW; idx += 256) {
-        const int i = idx / CW, c = idx % CW;
-        const uint32_t row = row0 + i;
-        float v = 0.0f;
-        if (row < m && static_cast<uint32_t>(c) < r) {
-            for (uint32_t s = 0; s < S; ++s) v += part[(static_cast<size_t>(s) * m + row) * RP + c];
-            P[static_cast<size_t>(row) * ldp + c] = v;
-        }
-        Ps[i][c] = v;
+    constexpr int CW = 16 * T16;
+    constexpr int LD = CW + 16;                      // floats; 4 rows x 16 columns per read: 2-way at worst
+    constexpr int NTILE = T16 * (T16 + 1) / 2;
+    constexpr int TPW = (NTILE + 3) / 4;             // Gram tiles per wave
+    __shared__ __attribute__((aligned(16))) float Ps[64 * LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    int ta[TPW], tb[TPW];
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + 4 * q;
+        tri_tile(t < NTILE ? t : 0, T16, ta[q], tb[q]);
     }
-    __syncthreads();
-    const int ta = tid / 16, tb = tid % 16;
-    double acc[TA][TA];
+    f64x4 acc[TPW];
 #pragma unroll
-    for (int x = 0; x < TA; ++x)
+    for (int q = 0; q < TPW; ++q) acc[q] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+    const uint32_t total_chunks = (m + 63) / 64;
+    const uint32_t ch_begin = blockIdx.x * chunks_per_block;
+    const uint32_t ch_end = min(total_chunks, ch_begin + chunks_per_block);
+    const size_t sstride = static_cast<size_t>(m) * RP;
+    for (uint32_t ch = ch_begin; ch < ch_end; ++ch) {
+        const uint32_t row0 = ch * 64;
+        __syncthreads();                             // previous chunk's Gram reads are done
 #pragma unroll
-        for (int y = 0; y < TA; ++y) acc[x][y] = 0.0;
-#pragma unroll 2
-    for (int i = 0; i < 64; ++i) {
-        double a[TA], b[TA];
-#pragma unroll
-        for (int x = 0; x < TA; ++x) { a[x] = Ps[i][ta + 16 * x]; b[x] = Ps[i][tb + 16 * x]; }
-#pragma unroll
-        for (int x = 0; x < TA; ++x)
-#pragma unroll
-            for (int y = 0; y < TA; ++y) acc[x][y] = fma(a[x], b[y], acc[x][y]);
-    }
-    double* out = gram_part + static_cast<size_t>(blockIdx.x) * r * r;
-#pragma unroll
-    for (int x = 0; x < TA; ++x)
-#pragma unroll
-        for (int y = 0; y < TA; ++y) {
-            const uint32_t a = ta + 16 * x, b = tb + 16 * y;
-            if (a < r && b < r) out[a * r + b] = acc[x][y];
+        for (int it = 0; it < T16; ++it) {
+            const int idx = tid + 256 * it;
+            const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
+            const uint32_t row = row0 + i;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < m) {
+                const float* src = part + static_cast<size_t>(row) * RP + c4;
+                uint32_t sp = 0;
+                for (; sp + 4 <= S; sp += 4) {
+                    const float4 x0 = *reinterpret_cast<const float4*>(src + (sp + 0) * sstride);
+                    const float4 x1 = *reinterpret_cast<const float4*>(src + (sp + 1) * sstride);
+                    const float4 x2 = *reinterpret_cast<const float4*>(src + (sp + 2) * sstride);
+                    const float4 x3 = *reinterpret_cast<const float4*>(src + (sp + 3) * sstride);
+                    v.x += x0.x; v.y += x0.y; v.z += x0.z; v.w += x0.w;
+                    v.x += x1.x; v.y += x1.y; v.z += x1.z; v.w += x1.w;
+                    v.x += x2.x; v.y += x2.y; v.z += x2.z; v.w += x2.w;
+                    v.x += x3.x; v.y += x3.y; v.z += x3.z; v.w += x3.w;
+                }
+                for (; sp < S; ++sp) {
+                    const float4 x0 = *reinterpret_cast<const float4*>(src + sp * sstride);
+                    v.x += x0.x; v.y += x0.y; v.z += x0.z; v.w += x0.w;
+                }
+                // partial columns >= r are exact zeros (the Q tile is masked in the P-pass)
+                float* dst = P + static_cast<size_t>(row) * ldp + c4;
+                if (static_cast<uint32_t>(c4) + 4 <= r) {
+                    *reinterpret_cast<float4*>(dst) = v;
+                } else {
+                    if (static_cast<uint32_t>(c4) < r) dst[0] = v.x;
+                    if (static_cast<uint32_t>(c4) + 1 < r) dst[1] = v.y;
+                    if (static_cast<uint32_t>(c4) + 2 < r) dst[2] = v.z;
+                }
+            }
+            *reinterpret_cast<float4*>(Ps + i * LD + c4) = v;
         }
+        __syncthreads();
+        const float* pk = Ps + (lane >> 4) * LD + (lane & 15);
+#pragma unroll 4
+        for (int k0 = 0; k0 < 64; k0 += 4) {
+#pragma unroll
+            for (int q = 0; q < TPW; ++q) {
+                const double a = static_cast<double>(pk[k0 * LD + 16 * ta[q]]);
+                const double b = static_cast<double>(pk[k0 * LD + 16 * tb[q]]);
+                acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[q], 0, 0, 0);
+            }
+        }
+    }
+    // tile t of this block: 256 doubles, [i][j] with i = lane/16 + 4v, j = lane%16
+#pragma unroll
+    for (int q = 0; q < TPW; ++q) {
+        const int t = wave + 4 * q;
+        if (t < NTILE) {
+            double* out = gram_part + (static_cast<size_t>(blockIdx.x) * NTILE + t) * 256;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) out[((lane >> 4) + 4 * v) * 16 + (lane & 15)] = acc[q][v];
+        }
+    }
 }
 
-__global__ void k_gram_sum(const double* __restrict__ gram_part, uint32_t nb, uint32_t rr,
-                           double* __restrict__ gram)
+// out[e] = sum over blocks of gp[b][e], in block order within each of four interleaved
+// groups and then over the groups: a fixed tree, so the result is reproducible.
+__global__ __launch_bounds__(256) void k_gram_sum(const double* __restrict__ gp, uint32_t nb,
+                                                  uint32_t ne, double* __restrict__ out)
 {
-    const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= rr) return;
+    __shared__ double red[4][64];
+    const uint32_t e = blockIdx.x * 64 + (threadIdx.x & 63);
+    const uint32_t grp = threadIdx.x >> 6;
     double s = 0.0;
-    for (uint32_t b = 0; b < nb; ++b) s += gram_part[static_cast<size_t>(b) * rr + e];
-    gram[e] = s;
+    if (e < ne) {
+        const double* p = gp + e;
+        uint32_t b = grp;
+        for (; b + 28 < nb; b += 32) {
+            double x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = p[static_cast<size_t>(b + 4 * u) * ne];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += x[u];
+        }
+        for (; b < nb; b += 4) s += p[static_cast<size_t>(b) * ne];
+    }
+    red[grp][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (grp == 0 && e < ne) out[e] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
 }
 
 // ---------------------------------------------------------------------------
 // Scaled Cholesky of the Gram matrix and the inverse factor, one block, fp64.
 //   W = P^T P,  D = diag(W)^-1/2,  C = D W D = L L^T,  R = L^T D^-1,  R^-1 = D L^-T
+// Blocked right-looking factorisation on 16x16 tiles held in LDS: the diagonal
+// tile is factored and inverted by one wavefront in registers (read-lane
+// broadcasts), the panel solve, the trailing update and the blocked inverse
+// X = L^-1 run on fp64 MFMA with one tile per wavefront.  X tiles below the
+// diagonal are stored transposed in the (otherwise unused) upper tiles.
 // A pivot of C below kPivotEps marks a column that is numerically dependent on
-// the previous ones: its P^ column becomes zero and it is left out of later
-// projections.
+// the previous ones: it is removed from the factorisation (row and column of X
+// zero), so its P^ column is zero and later columns are not projected on it.
+// `tiles` holds nb sets of upper-triangle tiles (nb > 1 only for a single tile).
 // ---------------------------------------------------------------------------
 constexpr double kPivotEps = 1e-11;
+constexpr int kCholThreads = 1024;
 
-__global__ __launch_bounds__(1024) void k_chol(const double* __restrict__ gram_in, uint32_t nb,
-                                               uint32_t r, double* __restrict__ rinv)
+__device__ __forceinline__ double readlane_f64(double x, int src_lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src_lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src_lane);
+    return __hiloint2double(hi, lo);
+}
+
+// Lanes 0..15 hold row `lane` of a symmetric 16x16 tile in a[0..15] (entries k <= lane are
+// used).  On return a[] holds row `lane` of its Cholesky factor L, x[] holds COLUMN `lane`
+// of X = L^-1 (x[i] = X[i][lane]), with rows and columns of dead pivots zeroed; the return
+// value has bit k set when pivot k was dead.  Must be called by a whole wavefront.
+__device__ __forceinline__ uint32_t chol16_factor_invert(double (&a)[16], double (&x)[16], int lane)
+{
+    uint32_t dead = 0;
+    double rd[16];                                   // 1 / L_kk, wave-uniform
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const double d = readlane_f64(a[k], k);
+        const bool ok = d > kPivotEps;
+        const double rs = ok ? rsqrt(d) : 0.0;
+        rd[k] = ok ? rs : 1.0;
+        if (!ok) dead |= 1u << k;
+        const double lk = (lane == k) ? (ok ? d * rs : 1.0) : a[k] * rs;
+        a[k] = lk;
+#pragma unroll
+        for (int j = k + 1; j < 16; ++j) a[j] = fma(-lk, readlane_f64(lk, j), a[j]);
+    }
+    // column `lane` of X by forward substitution: X[i][c] = -rd_i * sum_{k=c}^{i-1} L[i][k] X[k][c]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        double sacc = 0.0;
+#pragma unroll
+        for (int k = 0; k < i; ++k) sacc = fma(readlane_f64(a[k], i), x[k], sacc);   // x[k] = 0 for k < lane
+        x[i] = (lane == i) ? rd[i] : ((lane < i) ? -rd[i] * sacc : 0.0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (((dead >> i) & 1u) || ((dead >> (lane & 15)) & 1u)) x[i] = 0.0;
+    return dead;
+}
+
+__global__ __launch_bounds__(kCholThreads) void k_chol(const double* __restrict__ tiles, uint32_t nb,
+                                                       uint32_t r, uint32_t T16, double* __restrict__ rinv)
 {
     extern __shared__ double sm[];
-    const uint32_t ld = r + 1;
-    double* L = sm;                    // [r][r+1]
-    double* dsc = sm + static_cast<size_t>(r) * ld;   // [r] column scales
-    double* tmp = dsc + r;             // [r]
-    int* dead = reinterpret_cast<int*>(tmp + r);       // [r]
-    const int tid = threadIdx.x;
-    const uint32_t rr = r * r;
+    const int T = static_cast<int>(T16);
+    const int RPAD = 16 * T, LDA = RPAD + 1;
+    double* A = sm;                                   // [RPAD][LDA]: lower tiles L, upper tiles X^T
+    double* Xd = A + RPAD * LDA;                      // [T][16][17]: inverses of the diagonal tiles
+    double* dsc = Xd + T * 16 * 17;                   // [RPAD] column scales
+    double* red = dsc + RPAD;                         // [kCholThreads] partial sums (single tile only)
+    uint32_t* deadmask = reinterpret_cast<uint32_t*>(red + kCholThreads);   // [T]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = kCholThreads / 64;
+    const uint32_t ntile = T16 * (T16 + 1) / 2, ne = ntile * 256;
+    const int lr = lane & 15, lq = lane >> 4;         // MFMA fragment coordinates
 
-    for (uint32_t e = tid; e < rr; e += 1024) {
-        double s = 0.0;
-        for (uint32_t b = 0; b < nb; ++b) s += gram_in[static_cast<size_t>(b) * rr + e];
-        L[(e / r) * ld + (e % r)] = s;
-    }
-    __syncthreads();
-    for (uint32_t j = tid; j < r; j += 1024) {
-        const double w = L[j * ld + j];
-        dsc[j] = (w > 0.0) ? 1.0 / sqrt(w) : 0.0;
-        dead[j] = 0;
-    }
-    __syncthreads();
-    for (uint32_t e = tid; e < rr; e += 1024) {
-        const uint32_t a = e / r, b = e % r;
-        L[a * ld + b] *= dsc[a] * dsc[b];
-    }
-    __syncthreads();
-
-    // left-looking Cholesky: 8 lanes per row share the dot product over k < j
-    const uint32_t row = tid >> 3, sub = tid & 7;
-    for (uint32_t j = 0; j < r; ++j) {
-        double v = 0.0;
-        if (row >= j && row < r) {
-            for (uint32_t k = sub; k < j; k += 8) v = fma(L[row * ld + k], L[j * ld + k], v);
+    // ---- assemble the Gram matrix (lower triangle) ----
+    for (int e = tid; e < RPAD * LDA; e += kCholThreads) A[e] = 0.0;
+    if (nb > 1) {                                     // ne == 256: four interleaved groups per entry
+        const uint32_t e = tid & 255, grp = tid >> 8;
+        double sacc = 0.0;
+        uint32_t b = grp;
+        for (; b + 28 < nb; b += 32) {
+            double xx[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xx[u] = tiles[static_cast<size_t>(b + 4 * u) * ne + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sacc += xx[u];
         }
-        v += __shfl_xor(v, 1, 64);
-        v += __shfl_xor(v, 2, 64);
-        v += __shfl_xor(v, 4, 64);
-        if (row >= j && row < r && sub == 0) tmp[row] = L[row * ld + j] - v;
+        for (; b < nb; b += 4) sacc += tiles[static_cast<size_t>(b) * ne + e];
+        red[tid] = sacc;
         __syncthreads();
-        const double piv = tmp[j];
-        if (row >= j && row < r && sub == 0) {
-            if (piv > kPivotEps) {
-                const double ljj = sqrt(piv);
-                L[row * ld + j] = (row == j) ? ljj : tmp[row] / ljj;
-            } else {
-                L[row * ld + j] = (row == j) ? 1.0 : 0.0;
-                if (row == j) dead[j] = 1;
-            }
-        }
+        if (tid < 256) red[tid] = ((red[tid] + red[tid + 256]) + red[tid + 512]) + red[tid + 768];
         __syncthreads();
     }
+    __syncthreads();
+    for (uint32_t e = tid; e < ne; e += kCholThreads) {
+        const double w = (nb > 1) ? red[e] : tiles[e];
+        int ta, tb;
+        tri_tile(static_cast<int>(e >> 8), T, ta, tb);
+        const int a = 16 * ta + ((e >> 4) & 15), b = 16 * tb + (e & 15);
+        if (a <= b) A[b * LDA + a] = w;
+    }
+    __syncthreads();
+    for (int j = tid; j < RPAD; j += kCholThreads) {
+        const double w = A[j * LDA + j];
+        dsc[j] = (w > 0.0) ? rsqrt(w) : 0.0;
+    }
+    __syncthreads();
+    for (int e = tid; e < RPAD * RPAD; e += kCholThreads) {
+        const int a = e / RPAD, b = e % RPAD;
+        if (b <= a) A[a * LDA + b] *= dsc[a] * dsc[b];
+    }
+    __syncthreads();
 
-    // X = L^-1 column by column (8 lanes per column, x_k kept in registers of lane k % 8),
-    // then row k of R^-1:  rinv[k][c] = d_k * X[c][k]  for c >= k
-    const uint32_t col = tid >> 3;
-    if (col < r) {
-        double xr[16];                       // X[k][col] for k = 8*t + sub
+    // ---- blocked right-looking Cholesky ----
+    for (int p = 0; p < T; ++p) {
+        const int j0 = 16 * p;
+        if (wave == 0) {
+            double a[16], x[16];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) xr[t] = 0.0;
-        const bool col_dead = dead[col] != 0;
-        for (uint32_t i = col; i < r; ++i) {
-            double xi;
-            if (i == col) {
-                xi = 1.0 / L[col * ld + col];
-            } else {
-                double v = 0.0;
+            for (int k = 0; k < 16; ++k) { a[k] = (lane < 16) ? A[(j0 + lane) * LDA + j0 + k] : 0.0; x[k] = 0.0; }
+            const uint32_t dead = chol16_factor_invert(a, x, lane);
+            if (lane < 16) {
 #pragma unroll
-                for (int t = 0; t < 16; ++t) {
-                    const uint32_t k = 8 * t + sub;
-                    if (k >= col && k < i) v = fma(L[i * ld + k], xr[t], v);
+                for (int k = 0; k < 16; ++k) {
+                    if (k <= lane) A[(j0 + lane) * LDA + j0 + k] = a[k];
+                    Xd[(p * 16 + k) * 17 + lane] = x[k];          // X[k][lane]
                 }
-                v += __shfl_xor(v, 1, 64);
-                v += __shfl_xor(v, 2, 64);
-                v += __shfl_xor(v, 4, 64);
-                xi = -v / L[i * ld + i];
+            }
+            if (lane == 0) deadmask[p] = dead;
+        }
+        __syncthreads();
+        // panel solve: L_ip = C_ip X_pp^T for tiles i > p
+        for (int i = p + 1 + wave; i < T; i += NW) {
+            f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const double av = A[(16 * i + lr) * LDA + j0 + 4 * kk + lq];
+                const double bv = Xd[(p * 16 + lr) * 17 + 4 * kk + lq];     // X_pp[b = lr][k]
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
             }
 #pragma unroll
-            for (int t = 0; t < 16; ++t)
-                if (static_cast<uint32_t>(8 * t) + sub == i) xr[t] = xi;
-            if (sub == 0) {
-                const bool zero = col_dead || dead[i] != 0;
-                // entry (k = col, c = i) of R^-1
-                rinv[static_cast<size_t>(col) * r + i] = zero ? 0.0 : dsc[col] * xi;
-            }
+            for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + j0 + lr] = acc[v];
         }
-        // strictly lower part of R^-1 is zero
-        for (uint32_t c = sub; c < col; c += 8) rinv[static_cast<size_t>(col) * r + c] = 0.0;
+        __syncthreads();
+        // trailing update: C_ic -= L_ip L_cp^T for p < c <= i
+        const int rem = T - p - 1, npair = rem * (rem + 1) / 2;
+        for (int idx = wave; idx < npair; idx += NW) {
+            int ci, ii;                                  // (c, i) offsets with c <= i, row-major over the triangle
+            tri_tile(idx, rem, ci, ii);
+            const int c = p + 1 + ci, i = p + 1 + ii;
+            f64x4 acc;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] = A[(16 * i + lq + 4 * v) * LDA + 16 * c + lr];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const double av = -A[(16 * i + lr) * LDA + j0 + 4 * kk + lq];
+                const double bv = A[(16 * c + lr) * LDA + j0 + 4 * kk + lq];  // L_cp[b = lr][k]
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + 16 * c + lr] = acc[v];
+        }
+        __syncthreads();
+    }
+
+    // ---- blocked inverse: X_ip = -X_ii * sum_{k=p}^{i-1} L_ik X_kp, by tile distance ----
+    // X_ip (i > p) is kept transposed in the upper tile (p, i): A[16p + b][16i + a] = X_ip[a][b]
+    for (int dist = 1; dist < T; ++dist) {
+        for (int p = wave; p + dist < T; p += NW) {
+            const int i = p + dist;
+            f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+            for (int k = p; k < i; ++k) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const double av = A[(16 * i + lr) * LDA + 16 * k + 4 * kk + lq];          // L_ik[a][kk']
+                    const double bv = (k == p) ? Xd[(p * 16 + 4 * kk + lq) * 17 + lr]           // X_pp[kk'][b]
+                                               : A[(16 * p + lr) * LDA + 16 * k + 4 * kk + lq]; // X_kp[kk'][b]
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                }
+            }
+            // park S = sum in the target tile (natural orientation), then X_ip = -X_ii S
+#pragma unroll
+            for (int v = 0; v < 4; ++v) A[(16 * p + lq + 4 * v) * LDA + 16 * i + lr] = acc[v];
+            f64x4 xo = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const double av = -Xd[(i * 16 + lr) * 17 + 4 * kk + lq];                       // X_ii[a][k]
+                const double bv = A[(16 * p + 4 * kk + lq) * LDA + 16 * i + lr];               // S[k][b]
+                xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, xo, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) A[(16 * p + lr) * LDA + 16 * i + lq + 4 * v] = xo[v];  // transposed
+        }
+        __syncthreads();
+    }
+
+    // ---- R^-1[k][c] = d_k X[c][k] for k <= c, zero elsewhere and for removed columns ----
+    for (uint32_t e = tid; e < r * r; e += kCholThreads) {
+        const uint32_t k = e / r, c = e % r;
+        double v = 0.0;
+        const bool dk = (deadmask[k >> 4] >> (k & 15)) & 1u, dc = (deadmask[c >> 4] >> (c & 15)) & 1u;
+        if (k <= c && !dk && !dc) {
+            const double xv = ((k >> 4) == (c >> 4)) ? Xd[((c >> 4) * 16 + (c & 15)) * 17 + (k & 15)]
+                                                     : A[k * LDA + c];
+            v = dsc[k] * xv;
+        }
+        rinv[e] = v;
     }
 }
 
 // ---------------------------------------------------------------------------
-// P^ = P R^-1 in fp64 (64 rows per block), fp32 result in place, and the bf16
-// operand copy Pt[plane][c][i] (i contiguous, rows padded to a multiple of 64)
-// that the Q-pass reads as MFMA B-fragments.
+// P^ = P R^-1 on fp64 MFMA (64 rows per block, 16 per wave), fp32 result in place,
+// and the bf16 operand copy Pt[plane][c][i] (i contiguous, rows padded to a
+// multiple of 64) that the Q-pass reads as MFMA B-fragments.
 // ---------------------------------------------------------------------------
-template <int CW, int NP>
+template <int T16, int NP>
 __global__ __launch_bounds__(256) void k_apply(float* __restrict__ P, uint32_t ldp,
                                                const double* __restrict__ rinv, uint32_t m,
                                                uint32_t r, __bf16* __restrict__ pt, uint32_t m_pad,
                                                uint32_t RP)
 {
-    constexpr int NR = 64 * CW / 256;      // rows per thread
-    constexpr int RS = 256 / CW;           // row stride between a thread's rows
-    __shared__ float Ps[64][CW + 1];
-    const int tid = threadIdx.x;
+    constexpr int CW = 16 * T16;
+    constexpr int LD = CW + 4;             // floats; 16 rows x 4 columns per read: 2-way at worst
+    __shared__ __attribute__((aligned(16))) float Ps[64 * LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row0 = blockIdx.x * 64;
-    for (int idx = tid; idx < 64 * CW; idx += 256) {
-        const int i = idx / CW, c = idx % CW;
+#pragma unroll
+    for (int it = 0; it < T16; ++it) {
+        const int idx = tid + 256 * it;
+        const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
         const uint32_t row = row0 + i;
-        Ps[i][c] = (row < m && static_cast<uint32_t>(c) < r) ? P[static_cast<size_t>(row) * ldp + c] : 0.0f;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < m) {
+            const float* src = P + static_cast<size_t>(row) * ldp + c4;
+            if (static_cast<uint32_t>(c4) + 4 <= r) {
+                v = *reinterpret_cast<const float4*>(src);
+            } else {
+                if (static_cast<uint32_t>(c4) < r) v.x = src[0];
+                if (static_cast<uint32_t>(c4) + 1 < r) v.y = src[1];
+                if (static_cast<uint32_t>(c4) + 2 < r) v.z = src[2];
+            }
+        }
+        *reinterpret_cast<float4*>(Ps + i * LD + c4) = v;
     }
     __syncthreads();
-    const int c = tid % CW, ih = tid / CW;
-    double acc[NR];
+
+    f64x4 acc[T16];
 #pragma unroll
-    for (int x = 0; x < NR; ++x) acc[x] = 0.0;
-    // R^-1 is upper triangular: column c needs k <= c; the wave runs to its largest c
-    const uint32_t cmax = static_cast<uint32_t>(CW >= 64 ? (c | 63) : (CW - 1));
-    const uint32_t kend = min(r, cmax + 1);
-    for (uint32_t k = 0; k < kend; ++k) {
-        const double rk = (static_cast<uint32_t>(c) < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
+    for (int tc = 0; tc < T16; ++tc) acc[tc] = f64x4{0.0, 0.0, 0.0, 0.0};
+    const float* pa = Ps + (16 * wave + (lane & 15)) * LD + (lane >> 4);
+    const uint32_t kq = lane >> 4, cl = lane & 15;
+    const uint32_t ksteps = (r + 3) / 4;
+    for (uint32_t kk = 0; kk < ksteps; ++kk) {
+        const double a = static_cast<double>(pa[4 * kk]);
+        const uint32_t k = 4 * kk + kq;
 #pragma unroll
-        for (int x = 0; x < NR; ++x) acc[x] = fma(static_cast<double>(Ps[ih + RS * x][k]), rk, acc[x]);
+        for (int tc = 0; tc < T16; ++tc) {
+            // R^-1 is upper triangular: column tile tc needs k <= 16*tc + 15
+            if (4 * kk <= static_cast<uint32_t>(16 * tc + 15)) {
+                const uint32_t c = 16 * tc + cl;
+                const double b = (k < r && c < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
+                acc[tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[tc], 0, 0, 0);
+            }
+        }
     }
     __syncthreads();
 #pragma unroll
-    for (int x = 0; x < NR; ++x) {
-        const int i = ih + RS * x;
-        const float v = static_cast<float>(acc[x]);
-        Ps[i][c] = v;
+    for (int tc = 0; tc < T16; ++tc)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            Ps[(16 * wave + (lane >> 4) + 4 * v) * LD + 16 * tc + (lane & 15)] = static_cast<float>(acc[tc][v]);
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < T16; ++it) {
+        const int idx = tid + 256 * it;
+        const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
         const uint32_t row = row0 + i;
-        if (row < m && static_cast<uint32_t>(c) < r) P[static_cast<size_t>(row) * ldp + c] = v;
+        if (row < m) {
+            const float4 v = *reinterpret_cast<const float4*>(Ps + i * LD + c4);
+            float* dst = P + static_cast<size_t>(row) * ldp + c4;
+            if (static_cast<uint32_t>(c4) + 4 <= r) {
+                *reinterpret_cast<float4*>(dst) = v;
+            } else {
+                if (static_cast<uint32_t>(c4) < r) dst[0] = v.x;
+                if (static_cast<uint32_t>(c4) + 1 < r) dst[1] = v.y;
+                if (static_cast<uint32_t>(c4) + 2 < r) dst[2] = v.z;
+            }
+        }
     }
-    __syncthreads();
     // transposed operand copy: 8 consecutive rows of one column per 16-byte store
     for (uint32_t idx = tid; idx < RP * 8; idx += 256) {
         const uint32_t cc = idx / 8, q = idx % 8;
         bf16x8 w[NP];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float v = (cc < static_cast<uint32_t>(CW)) ? Ps[8 * q + e][cc] : 0.0f;
+            const float v = (cc < static_cast<uint32_t>(CW)) ? Ps[(8 * q + e) * LD + cc] : 0.0f;
             __bf16 pl[NP];
             to_planes<NP>(v, pl);
 #pragma unroll
@@ -946,45 +1165,52 @@ static int run_orthonormalise(edgc_ctx* ctx, uint32_t S, uint32_t m, uint32_t r,
 {
     Scratch& s = ctx->s;
     const uint32_t RP = rank_tiles(r) * 32;
-    const uint32_t NB = cdiv(m, 64);
-    const uint32_t ta = cdiv(r, 16);
+    const uint32_t t16 = r <= 16 ? 1 : r <= 32 ? 2 : r <= 64 ? 4 : 8;   // 16-wide tiles per side
+    const uint32_t ntile = t16 * (t16 + 1) / 2, ne = ntile * 256;
+    const uint32_t chunks = cdiv(m, 64);
+    const uint32_t cpb = std::max(1u, chunks / (static_cast<uint32_t>(ctx->num_cu) * 2));
+    const uint32_t NB = cdiv(chunks, cpb);
+    if (static_cast<uint64_t>(NB) * ne > s.gram_part_elems)
+        return fail(ctx, EDGC_EINVAL, "Gram scratch too small for this shape");
     const double mr = static_cast<double>(m) * r;
     {
         ProfScope prof_scope_(ctx, st, KID_REDUCE_GRAM, 4.0 * mr * (S + 1), 2.0 * mr * r);
-        switch (ta <= 1 ? 1 : ta <= 2 ? 2 : ta <= 4 ? 4 : 8) {
-        case 1: k_reduce_gram<1><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
-        case 2: k_reduce_gram<2><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
-        case 4: k_reduce_gram<4><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
-        default: k_reduce_gram<8><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part); break;
+        switch (t16) {
+        case 1: k_reduce_gram<1><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part, cpb); break;
+        case 2: k_reduce_gram<2><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part, cpb); break;
+        case 4: k_reduce_gram<4><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part, cpb); break;
+        default: k_reduce_gram<8><<<NB, 256, 0, st>>>(s.part, S, m, RP, r, P, ldp, s.gram_part, cpb); break;
         }
     }
     EDGC_HIP_TRY(ctx, hipGetLastError());
-    const uint32_t rr = r * r;
-    const double* gram_src = s.gram_part;
+    const double* tiles = s.gram_part;
     uint32_t nb = NB;
-    if (static_cast<uint64_t>(NB) * rr > 65536) {       // many partials: sum them on many CUs
-        EDGC_LAUNCH(ctx, st, KID_GRAM_SUM, 8.0 * rr * NB, 0.0,
-                    k_gram_sum<<<cdiv(rr, 256), 256, 0, st>>>(s.gram_part, NB, rr, s.gram));
+    if (NB > 1 && t16 > 1) {                     // the Cholesky block only sums a single tile itself
+        EDGC_LAUNCH(ctx, st, KID_GRAM_SUM, 8.0 * ne * NB, 0.0,
+                    k_gram_sum<<<cdiv(ne, 64), 256, 0, st>>>(s.gram_part, NB, ne, s.gram));
         EDGC_HIP_TRY(ctx, hipGetLastError());
-        gram_src = s.gram;
+        tiles = s.gram;
         nb = 1;
     }
-    const size_t chol_lds = (static_cast<size_t>(r) * (r + 1) + 2 * r) * sizeof(double) + r * sizeof(int);
+    const size_t rpad = 16 * t16;
+    const size_t chol_lds = (rpad * (rpad + 1) + t16 * 16 * 17 + rpad + kCholThreads) * sizeof(double) + t16 * sizeof(uint32_t);
     if (chol_lds > 64 * 1024)
         EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chol),
                                               hipFuncAttributeMaxDynamicSharedMemorySize,
                                               static_cast<int>(chol_lds)));
-    EDGC_LAUNCH(ctx, st, KID_CHOL, 8.0 * rr * (nb + 1), 2.0 * r * rr / 3.0,
-                k_chol<<<1, 1024, chol_lds, st>>>(gram_src, nb, r, s.rinv));
+    EDGC_LAUNCH(ctx, st, KID_CHOL, 8.0 * ne * nb + 8.0 * r * r, 2.0 * r * r * r / 3.0,
+                k_chol<<<1, kCholThreads, chol_lds, st>>>(tiles, nb, r, t16, s.rinv));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     __bf16* pt = static_cast<__bf16*>(s.pt);
     const uint32_t NBA = m_pad / 64;
     {
         ProfScope prof_scope_(ctx, st, KID_APPLY, 8.0 * mr + 2.0 * NP * RP * m_pad, mr * r);
-        if (r <= 16)      k_apply<16, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
-        else if (r <= 32) k_apply<32, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
-        else if (r <= 64) k_apply<64, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
-        else              k_apply<128, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP);
+        switch (t16) {
+        case 1: k_apply<1, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP); break;
+        case 2: k_apply<2, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP); break;
+        case 4: k_apply<4, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP); break;
+        default: k_apply<8, NP><<<NBA, 256, 0, st>>>(P, ldp, s.rinv, m, r, pt, m_pad, RP); break;
+        }
     }
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;

@@ -61,7 +61,8 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     const uint64_t rp = (max_rank <= 32) ? 32 : (max_rank <= 64 ? 64 : 128);
     const uint64_t rows_pad = (max_rows + 63) / 64 * 64;
     s.part_elems = compress_part_elems(max_rows, max_cols, max_rank, ctx->num_cu);
-    s.gram_part_elems = (rows_pad / 64) * static_cast<uint64_t>(max_rank) * max_rank;
+    // per-block upper-triangle 16x16 Gram tiles: at most 36 tiles of 256 doubles per 64-row chunk
+    s.gram_part_elems = (rows_pad / 64) * 36ull * 256ull;
     s.pt_bytes = 2ull * rp * rows_pad * 2ull;
     bool ok = true;
     ok = ok && dev_alloc(&s.mm_part, 2 * kMaxReduceBlocks) == hipSuccess;
@@ -72,7 +73,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     ok = ok && hipMalloc(&s.result_dev, sizeof(edgc_entropy_result)) == hipSuccess;
     ok = ok && dev_alloc(&s.part, s.part_elems) == hipSuccess;
     ok = ok && dev_alloc(&s.gram_part, s.gram_part_elems) == hipSuccess;
-    ok = ok && dev_alloc(&s.gram, static_cast<size_t>(max_rank) * max_rank) == hipSuccess;
+    ok = ok && dev_alloc(&s.gram, static_cast<size_t>(36) * 256) == hipSuccess;
     ok = ok && dev_alloc(&s.rinv, static_cast<size_t>(max_rank) * max_rank) == hipSuccess;
     ok = ok && hipMalloc(&s.pt, s.pt_bytes) == hipSuccess;
     ok = ok && hipMemset(s.done_counter, 0, 4 * sizeof(unsigned int)) == hipSuccess;
