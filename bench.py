@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--workload", default="cfg2_gpt_h2048_r16")
     ap.add_argument("--rank", type=int, default=0, help="override the workload's rank")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="issue every launch eagerly instead of replaying a captured HIP graph")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="HIP streams (one library context each) the layers are spread over; 0 = one per layer")
     return ap.parse_args()
 
 
@@ -66,8 +70,14 @@ def main() -> int:
     mats = gen.workload_matrices(args.workload)
     max_m = max(s.m for s, _ in mats)
     max_n = max(s.n for s, _ in mats)
-    ctx = edgc.Context(0, max_bins=w["bins"], max_rank=max(r, 4), max_rows=max_m, max_cols=max_n)
+    n_streams = args.streams or len(mats)
+    # one context (scratch) per stream: independent layers overlap their small kernels
+    ctxs = [edgc.Context(0, max_bins=w["bins"], max_rank=max(r, 4), max_rows=max_m, max_cols=max_n)
+            for _ in range(n_streams)]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    ctx = ctxs[0]
 
+    NBUF = 3   # entropy results are read two steps after they are enqueued: the GPU never waits for the host
     # device state per layer: gradient, residual, warm-started Q, P, output
     layers = []
     for li, (spec, g) in enumerate(mats):
@@ -79,11 +89,11 @@ def main() -> int:
         Q = torch.zeros((spec.n, ldf), dtype=torch.float32, device="cuda")
         ctx.init_q(Q, 0, r, w["seed"] + li)
         layers.append(dict(
-            spec=spec, G=G, Q=Q,
+            spec=spec, G=G, Q=Q, ctx=ctxs[li % n_streams], stream=streams[li % n_streams],
             E=torch.empty((spec.m, spec.n), dtype=torch.float32, device="cuda"),
             P=torch.empty((spec.m, ldf), dtype=torch.float32, device="cuda"),
             out=torch.empty_like(G), fresh=True,
-            ent=[torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(2)],
+            ent=[torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(NBUF)],
         ))
     torch.cuda.synchronize()
 
@@ -92,45 +102,102 @@ def main() -> int:
                           total_iters=args.steps + args.warmup, min_warmup_frac=0.10)
     state = edgc.RankState()
     decisions = []
-    step_events = [torch.cuda.Event(), torch.cuda.Event()]
+    step_events = [[torch.cuda.Event() for _ in range(n_streams)] for _ in range(NBUF)]
     counter = {"step": 0}
+
+    for L in layers:
+        L["flat"] = L["G"].view(-1)
+    graph = {"g": None}
+
+    def rank_rule(t):
+        # the rank rule consumes the entropies of step t-2 (on the host by now), so that one
+        # whole step is always queued on the GPU while the host works
+        if t > 1:
+            for ev in step_events[(t - 2) % NBUF]:
+                ev.synchronize()
+            H = [edgc.EntropyResult.from_buffer(L["ent"][(t - 2) % NBUF].numpy().tobytes()).h_diff_nats
+                 for L in layers]
+            decisions.append(edgc.select_rank(state, H, 1, prm))
+
+    def compress_all():
+        for L in layers:
+            c, st = L["ctx"], L["stream"]
+            c.compress(L["G"], L["E"], L["fresh"], L["Q"], L["P"], r, stream=st)
+            c.decompress(L["P"], L["Q"], r, L["E"], L["out"], stream=st)
+            L["fresh"] = False
 
     def one_step():
         t = counter["step"]
-        # the rank rule consumes the entropies of the previous step (already on the host)
-        if t > 0:
-            step_events[(t - 1) & 1].synchronize()
-            H = [edgc.EntropyResult.from_buffer(L["ent"][(t - 1) & 1].numpy().tobytes()).h_diff_nats
-                 for L in layers]
-            decisions.append(edgc.select_rank(state, H, 1, prm))
-        for L in layers:
-            ctx.entropy_estimate_async(L["G"].view(-1), w["stride"], w["chunk"], w["seed"], t, w["bins"],
-                                       L["ent"][t & 1])
-            ctx.compress(L["G"], L["E"], L["fresh"], L["Q"], L["P"], r)
-            ctx.decompress(L["P"], L["Q"], r, L["E"], L["out"])
-            L["fresh"] = False
-        step_events[t & 1].record()
+        rank_rule(t)
+        if graph["g"] is None:
+            for L in layers:
+                L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t, w["bins"],
+                                                L["ent"][t % NBUF], stream=L["stream"])
+            compress_all()
+            for si, st in enumerate(streams):
+                step_events[t % NBUF][si].record(st)
+        else:
+            # entropy launches stay eager (their sampling slot changes with the step); the
+            # compress + decompress launches of all layers are one captured graph
+            with torch.cuda.stream(main_stream):
+                for L in layers:
+                    L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
+                                                    w["bins"], L["ent"][t % NBUF], stream=main_stream)
+                graph["g"].replay()
+                for ev in step_events[t % NBUF]:
+                    ev.record(main_stream)
         counter["step"] = t + 1
+
+    main_stream = torch.cuda.Stream()
 
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+    graphed = False
+    if not args.no_graph:
+        try:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=main_stream, capture_error_mode="thread_local"):
+                for st in streams:
+                    st.wait_stream(main_stream)
+                compress_all()
+                for st in streams:
+                    main_stream.wait_stream(st)
+            graph["g"] = g
+            graphed = True
+            torch.cuda.synchronize()
+            for _ in range(2):          # untimed replays
+                one_step()
+            torch.cuda.synchronize()
+        except Exception as exc:        # fall back to eager launches
+            print("bench.py: graph capture failed (%s); running eagerly" % exc, file=sys.stderr)
+            graph["g"] = None
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
+    t_issued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    host_issue_ms = (t_issued - t0) * 1e3 / args.steps
 
     elem_bytes = 2 if bf16 else 4
     grad_bytes = sum(s.m * s.n for s, _ in mats) * elem_bytes
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # second pass of the same K steps with every kernel bracketed by HIP events on its stream
-    ctx.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)
+    # second pass of the same K steps, launched eagerly, with every kernel bracketed by HIP
+    # events on its stream
+    graph["g"] = None
+    for c in ctxs:
+        c.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)
     for _ in range(args.steps):
         one_step()
-    stats = ctx.profile_end()
+    stats = {}
+    for c in ctxs:
+        for name, sdict in c.profile_end().items():
+            acc = stats.setdefault(name, dict(launches=0, total_ms=0.0, bytes=0.0, flops=0.0))
+            for k in acc:
+                acc[k] += sdict[k]
     kernels = {}
     for name, s in stats.items():
         avg_us = s["total_ms"] * 1e3 / s["launches"]
@@ -171,12 +238,15 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": ["%dx%d" % (s.m, s.n) for s, _ in mats],
                    "rank": r, "stride": w["stride"], "chunk": w["chunk"], "bins": w["bins"],
+                   "streams": n_streams, "hip_graph": graphed,
                    "gradient_bytes_per_step": grad_bytes},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "mfma": mfma,
         "last_rank_decision": decisions[-1].rank if decisions else None,
+        "host_issue_ms_per_step": round(host_issue_ms, 4),
     }
     print(json.dumps(line))
-    ctx.close()
+    for c in ctxs:
+        c.close()
     return 0
 
 

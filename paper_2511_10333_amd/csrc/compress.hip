@@ -1113,6 +1113,31 @@ size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_ra
     return static_cast<size_t>(std::max(p_rows, q_cols) * RP);
 }
 
+// Kernels that may need more than 64 KiB of dynamic LDS get the limit raised once, at context
+// creation, so that hot calls make no attribute calls.
+template <int NP, int RT, int NT>
+static hipError_t allow_lds_pass_q()
+{
+    constexpr int lds = 2 * RT * 32 * (NP * 128 + 16);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_pass_q<NP, RT, NT, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_pass_q<NP, RT, NT, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+
+int prepare_compress_kernels(edgc_ctx* ctx)
+{
+    constexpr int chol_max = (128 * 129 + 8 * 16 * 17 + 128 + kCholThreads) * 8 + 64;
+    EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chol),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, chol_max));
+    EDGC_HIP_TRY(ctx, (allow_lds_pass_q<1, 4, 2>()));
+    EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 4, 2>()));
+    EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 2>()));
+    EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 4>()));
+    return EDGC_OK;
+}
+
 int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1,
                   uint64_t seed, hipStream_t st)
 {
@@ -1194,10 +1219,6 @@ static int run_orthonormalise(edgc_ctx* ctx, uint32_t S, uint32_t m, uint32_t r,
     }
     const size_t rpad = 16 * t16;
     const size_t chol_lds = (rpad * (rpad + 1) + t16 * 16 * 17 + rpad + kCholThreads) * sizeof(double) + t16 * sizeof(uint32_t);
-    if (chol_lds > 64 * 1024)
-        EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chol),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              static_cast<int>(chol_lds)));
     EDGC_LAUNCH(ctx, st, KID_CHOL, 8.0 * ne * nb + 8.0 * r * r, 2.0 * r * r * r / 3.0,
                 k_chol<<<1, kCholThreads, chol_lds, st>>>(tiles, nb, r, t16, s.rinv));
     EDGC_HIP_TRY(ctx, hipGetLastError());
@@ -1235,16 +1256,10 @@ static int run_pass_q(edgc_ctx* ctx, const float* D, uint32_t m, uint32_t n, uin
     const __bf16* pt = static_cast<const __bf16*>(ctx->s.pt);
     if (vec) {
         auto kern = &k_pass_q<NP, RT, NT, true>;
-        if (lds > 64 * 1024)
-            EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
         EDGC_LAUNCH(ctx, st, KID_PASS_Q, 4.0 * m * n, 2.0 * m * n * r,
                     kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S));
     } else {
         auto kern = &k_pass_q<NP, RT, NT, false>;
-        if (lds > 64 * 1024)
-            EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
         EDGC_LAUNCH(ctx, st, KID_PASS_Q, 4.0 * m * n, 2.0 * m * n * r,
                     kern<<<CB * S, 256, lds, st>>>(D, pt, m_pad, ctx->s.part, m, n, sps, CB, S));
     }

@@ -8,7 +8,7 @@ using namespace edgc;
 
 namespace edgc {
 const char* const kKernelNames[KID_COUNT] = {
-    "k_zero_counts", "k_set_range", "k_minmax", "k_hist", "k_sample_indices", "k_init_q", "k_pass_p",
+    "k_set_range", "k_minmax", "k_hist", "k_sample_indices", "k_init_q", "k_pass_p",
     "k_reduce_gram", "k_gram_sum", "k_chol", "k_apply", "k_pass_q", "k_reduce_q", "k_decompress"};
 }
 
@@ -78,6 +78,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     ok = ok && hipMalloc(&s.pt, s.pt_bytes) == hipSuccess;
     ok = ok && hipMemset(s.done_counter, 0, 4 * sizeof(unsigned int)) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
+    ok = ok && prepare_entropy_kernels(ctx) == EDGC_OK && prepare_compress_kernels(ctx) == EDGC_OK;
     if (!ok) {
         (void)hipGetLastError();
         free_scratch(s);

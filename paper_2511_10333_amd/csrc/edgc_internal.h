@@ -35,7 +35,7 @@ constexpr int kMaxReduceBlocks = 4096;
 
 // Kernel ids for the optional per-kernel event timing (edgc_profile_begin/end).
 enum KernelId {
-    KID_ZERO_COUNTS = 0, KID_SET_RANGE, KID_MINMAX, KID_HIST, KID_SAMPLE_IDX, KID_INIT_Q, KID_PASS_P,
+    KID_SET_RANGE = 0, KID_MINMAX, KID_HIST, KID_SAMPLE_IDX, KID_INIT_Q, KID_PASS_P,
     KID_REDUCE_GRAM, KID_GRAM_SUM, KID_CHOL, KID_APPLY, KID_PASS_Q, KID_REDUCE_Q, KID_DECOMPRESS,
     KID_COUNT
 };
@@ -146,6 +146,8 @@ int launch_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dt, uint32_t m, 
 int launch_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
                       uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
                       edgc_dtype dt, uint64_t ld, hipStream_t st);
+int prepare_compress_kernels(edgc_ctx* ctx);
+int prepare_entropy_kernels(edgc_ctx* ctx);
 size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_rank, int num_cu);
 
 }  // namespace edgc

@@ -151,10 +151,14 @@ template <typename T, int VEC>
 __global__ __launch_bounds__(kMMBlock) void k_minmax(const T* __restrict__ g, SampleGeom geom,
                                                      float* __restrict__ part,
                                                      unsigned int* done, RangeParams* rp,
-                                                     float fbins)
+                                                     float fbins, unsigned long long* counts,
+                                                     uint32_t bins, unsigned long long* nonfinite)
 {
     const uint64_t G = static_cast<uint64_t>(gridDim.x) * kMMBlock;
     const uint64_t gtid = static_cast<uint64_t>(blockIdx.x) * kMMBlock + threadIdx.x;
+    // the histogram kernel that follows on the stream accumulates into zeroed counters
+    for (uint64_t b = gtid; b < bins; b += G) counts[b] = 0ull;
+    if (gtid == 0) *nonfinite = 0ull;
 
     float lo = INFINITY, hi = -INFINITY;
     ItemCursor cur;
@@ -227,9 +231,13 @@ __global__ __launch_bounds__(kMMBlock) void k_minmax(const T* __restrict__ g, Sa
     }
 }
 
-// Caller-supplied range: same derived quantities, no pass over the data.
-__global__ void k_set_range(RangeParams* rp, float lo, float hi, float fbins)
+// Caller-supplied range: same derived quantities, no pass over the data; zeroes the counters.
+__global__ void k_set_range(RangeParams* rp, float lo, float hi, float fbins,
+                            unsigned long long* counts, uint32_t bins, unsigned long long* nonfinite)
 {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < bins) counts[i] = 0ull;
+    if (i == 0) *nonfinite = 0ull;
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         RangeParams r;
         r.lo = lo; r.hi = hi;
@@ -237,13 +245,6 @@ __global__ void k_set_range(RangeParams* rp, float lo, float hi, float fbins)
         r.scale = (r.w > 0.0f) ? __fdiv_rn(fbins, r.w) : 0.0f;
         *rp = r;
     }
-}
-
-__global__ void k_zero_counts(unsigned long long* counts, uint32_t bins, unsigned long long* nonfinite)
-{
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < bins) counts[i] = 0ull;
-    if (i == 0) *nonfinite = 0ull;
 }
 
 // ---------------------------------------------------------------------------
@@ -435,39 +436,53 @@ static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32
     const float fbins = static_cast<float>(bins);
 
     const double sample_bytes = static_cast<double>(g.n_sampled) * sizeof(T);
-    EDGC_LAUNCH(ctx, st, KID_ZERO_COUNTS, 8.0 * bins, 0.0,
-                k_zero_counts<<<(bins + 255) / 256, 256, 0, st>>>(counts, bins, s.nonfinite));
     if (range) {
-        EDGC_LAUNCH(ctx, st, KID_SET_RANGE, 0.0, 0.0,
-                    k_set_range<<<1, 64, 0, st>>>(rp, range[0], range[1], fbins));
+        EDGC_LAUNCH(ctx, st, KID_SET_RANGE, 8.0 * bins, 0.0,
+                    k_set_range<<<(bins + 255) / 256, 256, 0, st>>>(rp, range[0], range[1], fbins, counts,
+                                                                     bins, s.nonfinite));
     } else {
-        const uint32_t gx = grid_for(g.n_items, kMMBlock, 8, min(kMaxReduceBlocks, ctx->num_cu * 8));
+        // one unrolled round of four 16-byte loads per thread while the sample is small
+        const uint32_t gx = grid_for(g.n_items, kMMBlock, 4, min(kMaxReduceBlocks, ctx->num_cu * 4));
         EDGC_LAUNCH(ctx, st, KID_MINMAX, sample_bytes, 0.0,
-                    k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(grad, g, s.mm_part, s.done_counter, rp, fbins));
+                    k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(grad, g, s.mm_part, s.done_counter, rp, fbins,
+                                                              counts, bins, s.nonfinite));
     }
 
     // LDS plan: up to 64 KiB of 32-bit counters, replicated per lane where bins are few;
     // more than 16384 bins are covered in slices of 32768 (128 KiB), one slice per blockIdx.y
+    // small samples get few blocks of few items each, and then fewer replicas so that zeroing
+    // and folding the LDS histogram does not outweigh the sampling itself
+    const bool small = g.n_items <= static_cast<uint64_t>(kHistBlock) * 4 * ctx->num_cu * 2;
+    const uint32_t word_cap = small ? 4096u : 16384u;
     uint32_t bins_local = bins, rep_shift = 0;
     if (bins <= 16384) {
-        while (rep_shift < 5 && (static_cast<uint64_t>(bins) << (rep_shift + 1)) <= 16384) ++rep_shift;
+        while (rep_shift < 5 && (static_cast<uint64_t>(bins) << (rep_shift + 1)) <= word_cap) ++rep_shift;
     } else if (bins > 32768) {
         bins_local = 32768;
     }
     const uint32_t ny = (bins + bins_local - 1) / bins_local;
     const size_t lds = static_cast<size_t>(bins_local << rep_shift) * sizeof(uint32_t);
-    if (lds > 64 * 1024) {
-        EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<T, VEC>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                                              static_cast<int>(lds)));
-    }
     // enough items per block that zeroing and flushing the LDS histogram stays small
-    const int per_thread = (bins_local << rep_shift) > 16384 ? 64 : 16;
+    const int per_thread = small ? 4 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
     const uint32_t gx = grid_for(g.n_items, kHistBlock, per_thread, ctx->num_cu * 2);
     EDGC_LAUNCH(ctx, st, KID_HIST, sample_bytes * ny, 0.0,
                 k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(grad, g, rp, bins, bins_local, rep_shift,
                                                                       counts, s.nonfinite, s.done_counter + 1, res));
     EDGC_HIP_TRY(ctx, hipGetLastError());
+    return EDGC_OK;
+}
+
+int prepare_entropy_kernels(edgc_ctx* ctx)
+{
+    constexpr int lds = 32768 * 4;     // one slice of 32768 bins
+    EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<float, 4>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<float, 1>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<uint16_t, 8>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<uint16_t, 1>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     return EDGC_OK;
 }
 
