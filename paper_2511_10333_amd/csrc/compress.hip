@@ -45,6 +45,50 @@ __device__ __forceinline__ void to_planes(float x, __bf16 (&p)[NP])
     if constexpr (NP == 2) p[1] = static_cast<__bf16>(x - static_cast<float>(p[0]));
 }
 
+// Two floats -> packed bf16 pairs, one 32-bit word per plane (v_cvt_pk_bf16_f32, RNE):
+// w[0] = (bf16(x), bf16(y)); with two planes w[1] holds the rounded remainders.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <int NP>
+__device__ __forceinline__ void pack_pair(float x, float y, uint32_t (&w)[NP])
+{
+    const f32x2 v = {x, y};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    w[0] = __builtin_bit_cast(uint32_t, h);
+    if constexpr (NP == 2) {
+        const f32x2 hf = __builtin_convertvector(h, f32x2);
+        const bf16x2 l = __builtin_convertvector(v - hf, bf16x2);
+        w[1] = __builtin_bit_cast(uint32_t, l);
+    }
+}
+// eight floats -> one MFMA fragment per plane
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <int NP>
+__device__ __forceinline__ void pack8(const float (&v)[8], bf16x8 (&f)[NP])
+{
+    uint32_t w[4][NP];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pack_pair<NP>(v[2 * i], v[2 * i + 1], w[i]);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const u32x4 q = {w[0][p], w[1][p], w[2][p], w[3][p]};
+        f[p] = __builtin_bit_cast(bf16x8, q);
+    }
+}
+template <int NP>
+__device__ __forceinline__ void pack4(const float (&v)[4], bf16x4 (&f)[NP])
+{
+    uint32_t w[2][NP];
+    pack_pair<NP>(v[0], v[1], w[0]);
+    pack_pair<NP>(v[2], v[3], w[1]);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const u32x2 q = {w[0][p], w[1][p]};
+        f[p] = __builtin_bit_cast(bf16x4, q);
+    }
+}
+
 template <int NP>
 __device__ __forceinline__ f32x16 mma(const bf16x8 (&a)[NP], const bf16x8 (&b)[NP], f32x16 acc)
 {
@@ -230,14 +274,11 @@ __global__ __launch_bounds__(256) void k_pass_p(
                     make_float4(d[p][0], d[p][1], d[p][2], d[p][3]);
             else
                 store_f32x4<VECOK>(E, n, row, col, m, k_end, d[p]);
-            __bf16 pl[4][NP];
+            bf16x4 w[NP];
+            pack4<NP>(d[p], w);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) to_planes<NP>(d[p][x], pl[x]);
-#pragma unroll
-            for (int q = 0; q < NP; ++q) {
-                bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
-                *reinterpret_cast<bf16x4*>(ldsA + (p * RPP + a_row) * ROWB + q * 128 + a_col * 2) = w;
-            }
+            for (int q = 0; q < NP; ++q)
+                *reinterpret_cast<bf16x4*>(ldsA + (p * RPP + a_row) * ROWB + q * 128 + a_col * 2) = w[q];
         }
 #pragma unroll
         for (int p = 0; p < PQ; ++p) {
@@ -245,13 +286,7 @@ __global__ __launch_bounds__(256) void k_pass_p(
             if (it < NQI) {
                 const uint32_t c = it % RP, k8 = it / RP;
                 bf16x8 w[NP];
-#pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    __bf16 pl[NP];
-                    to_planes<NP>(qv[p][kk], pl);
-#pragma unroll
-                    for (int q = 0; q < NP; ++q) w[q][kk] = pl[q];
-                }
+                pack8<NP>(qv[p], w);
 #pragma unroll
                 for (int q = 0; q < NP; ++q)
                     *reinterpret_cast<bf16x8*>(ldsB + c * ROWB + q * 128 + k8 * 16) = w[q];
@@ -735,14 +770,10 @@ __global__ __launch_bounds__(256) void k_apply(float* __restrict__ P, uint32_t l
     for (uint32_t idx = tid; idx < RP * 8; idx += 256) {
         const uint32_t cc = idx / 8, q = idx % 8;
         bf16x8 w[NP];
+        float v8[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float v = (cc < static_cast<uint32_t>(CW)) ? Ps[(8 * q + e) * LD + cc] : 0.0f;
-            __bf16 pl[NP];
-            to_planes<NP>(v, pl);
-#pragma unroll
-            for (int p = 0; p < NP; ++p) w[p][e] = pl[p];
-        }
+        for (int e = 0; e < 8; ++e) v8[e] = (cc < static_cast<uint32_t>(CW)) ? Ps[(8 * q + e) * LD + cc] : 0.0f;
+        pack8<NP>(v8, w);
 #pragma unroll
         for (int p = 0; p < NP; ++p)
             *reinterpret_cast<bf16x8*>(pt + (static_cast<size_t>(p) * RP + cc) * m_pad + row0 + 8 * q) = w[p];
@@ -770,9 +801,11 @@ __device__ __forceinline__ void load_d_rows(const float* __restrict__ D, uint32_
             if constexpr (NT == 4) {
                 const float4 x = *reinterpret_cast<const float4*>(p);
                 v[q][0] = x.x; v[q][1] = x.y; v[q][2] = x.z; v[q][3] = x.w;
-            } else {
+            } else if constexpr (NT == 2) {
                 const float2 x = *reinterpret_cast<const float2*>(p);
                 v[q][0] = x.x; v[q][1] = x.y;
+            } else {
+                v[q][0] = p[0];
             }
         } else {
 #pragma unroll
@@ -845,25 +878,23 @@ __global__ __launch_bounds__(256) void k_pass_q(const float* __restrict__ D,
         const uint32_t i0 = st * 64;
         const bool full = cols_full && (i0 + 64 <= m);
         const unsigned char* tile = qlds + buf * TILE;
-        float dv[2][8][NT];
-        if (full) load_d_rows<NT, true>(D, n, m, i0 + 8 * g, col, dv[0]);
-        else      load_d_rows<NT, false>(D, n, m, i0 + 8 * g, col, dv[0]);
+        // all of the stage's D loads are issued at once (the other waves of the SIMD compute meanwhile)
+        float dv[4][8][NT];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (u + 1 < 4) {
-                if (full) load_d_rows<NT, true>(D, n, m, i0 + 16 * (u + 1) + 8 * g, col, dv[(u + 1) & 1]);
-                else      load_d_rows<NT, false>(D, n, m, i0 + 16 * (u + 1) + 8 * g, col, dv[(u + 1) & 1]);
-            }
+            if (full) load_d_rows<NT, true>(D, n, m, i0 + 16 * u + 8 * g, col, dv[u]);
+            else      load_d_rows<NT, false>(D, n, m, i0 + 16 * u + 8 * g, col, dv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
             bf16x8 a[NT][NP];
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
+            for (int t = 0; t < NT; ++t) {
+                float col8[8];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    __bf16 pl[NP];
-                    to_planes<NP>(dv[u & 1][q][t], pl);
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) a[t][p][q] = pl[p];
-                }
+                for (int q = 0; q < 8; ++q) col8[q] = dv[u][q][t];
+                pack8<NP>(col8, a[t]);
+            }
 #pragma unroll
             for (int ct = 0; ct < RT; ++ct) {
                 bf16x8 b[NP];
@@ -958,13 +989,7 @@ __global__ __launch_bounds__(256) void k_decompress(
                 for (int e = 0; e < 8; ++e)
                     v[e] = (row < m && c0 + e < r) ? P[static_cast<size_t>(row) * ldp + c0 + e] : 0.0f;
             }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                __bf16 pl[NP];
-                to_planes<NP>(v[e], pl);
-#pragma unroll
-                for (int p = 0; p < NP; ++p) a[kb][p][e] = pl[p];
-            }
+            pack8<NP>(v, a[kb]);
         }
     }
 
@@ -992,15 +1017,15 @@ __global__ __launch_bounds__(256) void k_decompress(
         for (int p = 0; p < PQ; ++p) {
             const int idx = tid + p * 256;
             const int jj = idx / (RP / 4), c4 = (idx % (RP / 4)) * 4;
-            __bf16 pl[4][NP];
+            float m4[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) to_planes<NP>((static_cast<uint32_t>(c4 + e) < r) ? qv[p][e] : 0.0f, pl[e]);
+            for (int e = 0; e < 4; ++e) m4[e] = (static_cast<uint32_t>(c4 + e) < r) ? qv[p][e] : 0.0f;
+            bf16x4 w[NP];
+            pack4<NP>(m4, w);
             const int lrow = (jj & 1) * 32 + (jj >> 1);
 #pragma unroll
-            for (int q = 0; q < NP; ++q) {
-                bf16x4 w = {pl[0][q], pl[1][q], pl[2][q], pl[3][q]};
-                *reinterpret_cast<bf16x4*>(dlds + lrow * ROWB + q * (RP * 2) + c4 * 2) = w;
-            }
+            for (int q = 0; q < NP; ++q)
+                *reinterpret_cast<bf16x4*>(dlds + lrow * ROWB + q * (RP * 2) + c4 * 2) = w[q];
         }
     };
     auto stage_full = [&](uint32_t st) { return VECOK && rows_full && st * 64 + 64 <= n; };
@@ -1134,7 +1159,7 @@ int prepare_compress_kernels(edgc_ctx* ctx)
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<1, 4, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 4, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 2>()));
-    EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 4>()));
+
     return EDGC_OK;
 }
 
@@ -1158,7 +1183,8 @@ static int run_pass_p(edgc_ctx* ctx, const void* grad, uint64_t ld, float* resid
     using GT = typename GradElem<NP>::type;
     const uint32_t RB = cdiv(m, 128), RP = RT * 32;
     const uint32_t ksteps = cdiv(n, BK);
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 4;
+    // measured: bf16 gradients stream best with ~2 blocks per CU, fp32 with ~4
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : (NP == 1 ? 2u : 4u));
     uint32_t S = std::max(1u, std::min(ksteps, target / RB));
     const uint64_t cap = ctx->s.part_elems / (static_cast<uint64_t>(m) * RP);
     if (cap == 0) return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
@@ -1239,14 +1265,14 @@ static int run_orthonormalise(edgc_ctx* ctx, uint32_t S, uint32_t m, uint32_t r,
 
 template <int NP, int RT, int NT>
 static int run_pass_q(edgc_ctx* ctx, const float* D, uint32_t m, uint32_t n, uint32_t r, float* Q,
-                      uint32_t ldq, uint32_t m_pad, hipStream_t st)
+                      uint32_t ldq, uint32_t m_pad, uint32_t smax, hipStream_t st)
 {
     constexpr uint32_t RP = RT * 32, W4 = 4 * 32 * NT;
     constexpr size_t lds = static_cast<size_t>(2) * RP * (NP * 128 + 16);
     const uint32_t CB = cdiv(n, W4);
     const uint32_t stages = m_pad / 64;
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 2;
-    uint32_t S = std::max(1u, std::min(stages, target / CB));
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_q ? ctx->tune_q : 2u);
+    uint32_t S = std::max(1u, std::min(std::min(stages, smax), target / CB));
     const uint64_t cap = ctx->s.part_elems / (static_cast<uint64_t>(n) * RP);
     if (cap == 0) return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
     S = static_cast<uint32_t>(std::min<uint64_t>(S, cap));
@@ -1285,13 +1311,11 @@ static int compress_impl(edgc_ctx* ctx, const void* grad, uint32_t m, uint32_t n
         if (rc != EDGC_OK) return rc;
         rc = run_orthonormalise<NP>(ctx, S, m, r, P, ldp, m_pad, st);
         if (rc != EDGC_OK) return rc;
-        // wide strips (4 columns per lane) only when the accumulators fit and there are enough strips
-        if constexpr (RT == 4) {
-            rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
-        } else {
-            if (n >= 4096) rc = run_pass_q<NP, RT, 4>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
-            else           rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, st);
-        }
+        // Strip width: 128*NT columns per block.  Every block writes a strip x rank partial, so it
+        // should stream at least ~10 x rank rows; the widest strip that still gives one block per CU
+        // under that limit is used (NT <= 2 when the rank needs all accumulators).
+        // two columns per lane (256-column strips): two to three waves per SIMD hide the load latency
+        rc = run_pass_q<NP, RT, 2>(ctx, residual, m, n, r, Q, ldq, m_pad, 1u << 30, st);
         if (rc != EDGC_OK) return rc;
     }
     return EDGC_OK;
@@ -1322,7 +1346,7 @@ static int decompress_impl(edgc_ctx* ctx, const float* P, uint32_t ldp, const fl
     constexpr size_t lds = static_cast<size_t>(64) * (NP * RP * 2 + 16);
     const uint32_t RB = cdiv(m, 128);
     const uint32_t stages = cdiv(n, 64);
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * 4;
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_d ? ctx->tune_d : (NP == 1 ? 2u : 4u));
     uint32_t JS = std::max(1u, std::min(stages, target / RB));
     const uint32_t sps = cdiv(stages, JS);
     JS = cdiv(stages, sps);

@@ -2,6 +2,8 @@
 // scratch management, and hand-off to the kernel launchers.  No computation here.
 #include "edgc_internal.h"
 
+#include <algorithm>
+#include <cstdlib>
 #include <new>
 
 using namespace edgc;
@@ -56,6 +58,11 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->num_cu = prop.multiProcessorCount;
+
+    // developer knobs for launch-shape sweeps (environment, read once per context)
+    if (const char* e = getenv("EDGC_TUNE_P")) ctx->tune_p = std::max(1, atoi(e));
+    if (const char* e = getenv("EDGC_TUNE_Q")) ctx->tune_q = std::max(1, atoi(e));
+    if (const char* e = getenv("EDGC_TUNE_D")) ctx->tune_d = std::max(1, atoi(e));
 
     Scratch& s = ctx->s;
     const uint64_t rp = (max_rank <= 32) ? 32 : (max_rank <= 64 ? 64 : 128);

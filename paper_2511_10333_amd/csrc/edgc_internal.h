@@ -61,6 +61,9 @@ struct edgc_ctx {
     uint32_t max_bins = 0, max_rank = 0;
     uint64_t max_rows = 0, max_cols = 0;
     int num_cu = 256;
+    // launch-shape overrides for sweeps (blocks per CU aimed at by the P-pass, Q-pass and
+    // decompress); 0 = the built-in choice
+    uint32_t tune_p = 0, tune_q = 0, tune_d = 0;
     edgc::Scratch s;
     edgc::Profiler prof;
     std::string last_error;
