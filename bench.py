@@ -27,7 +27,11 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this command (see profiles/); None until such a run has been recorded.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/k_pass_p_cfg2_traffic.md: (2 x FETCH_SIZE + WRITE_SIZE) KiB per launch, the factors
+    # coming from the same counters on a plain 1 GiB device copy (FETCH_SIZE reads half the bytes)
+    ("cfg2_gpt_h2048_r16", "k_pass_p"): int((2 * 4.84e4 + 6.25e4) * 1024),
+}
 
 
 def parse_args():
@@ -38,6 +42,9 @@ def parse_args():
     ap.add_argument("--workload", default="cfg2_gpt_h2048_r16")
     ap.add_argument("--rank", type=int, default=0, help="override the workload's rank")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--no-graph", action="store_true",
                     help="issue every launch eagerly instead of replaying a captured HIP graph")
     ap.add_argument("--streams", type=int, default=0,
@@ -63,6 +70,17 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                          "launches": 5}))
+        return 0
 
     w = gen.WORKLOADS[args.workload]
     r = args.rank or w["rank"]
@@ -185,9 +203,12 @@ def main() -> int:
     grad_bytes = sum(s.m * s.n for s, _ in mats) * elem_bytes
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # second pass of the same K steps, launched eagerly, with every kernel bracketed by HIP
-    # events on its stream
+    # second pass of the same K steps, launched eagerly on ONE stream so that every kernel has
+    # the GPU to itself, each bracketed by HIP events on that stream
     graph["g"] = None
+    torch.cuda.synchronize()
+    for L in layers:
+        L["stream"] = streams[0]
     for c in ctxs:
         c.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)
     for _ in range(args.steps):
@@ -198,6 +219,7 @@ def main() -> int:
             acc = stats.setdefault(name, dict(launches=0, total_ms=0.0, bytes=0.0, flops=0.0))
             for k in acc:
                 acc[k] += sdict[k]
+            event_overhead_us = sdict["event_overhead_ms"] * 1e3
     kernels = {}
     for name, s in stats.items():
         avg_us = s["total_ms"] * 1e3 / s["launches"]
@@ -212,24 +234,33 @@ def main() -> int:
                     traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                     avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
                     algorithmic_bytes_per_launch=round(ds["bytes"] / ds["launches"]),
-                    timing="HIP events around every launch, second pass of the same K steps")
+                    timing="HIP events around every launch (minus %.2f us, what an empty event pair reads); "
+                           "second pass of the same K steps, launches serialised on one stream" % event_overhead_us)
     mfma = {k: dict(tflops=v["tflops"], frac_of_bf16_peak=round(v["tflops"] / BF16_MFMA_PEAK_TFLOPS, 4))
             for k, v in kernels.items() if k in ("k_pass_p", "k_pass_q", "k_decompress") and v["tflops"]}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import edgc_oracle as orc
-        tc0 = time.perf_counter()
+        q0s = []
         for li, (spec, g) in enumerate(mats):
-            orc.entropy(g.reshape(-1), w["stride"], w["chunk"], w["seed"], 0, w["bins"])
             Q0 = np.zeros((spec.n, r), dtype=np.float32)
             orc.init_q(Q0, 0, r, w["seed"] + li)
-            P, Q1, D = orc.compress(g, None, Q0, r)
-            orc.decompress(P, Q1, D, orc.BF16 if bf16 else orc.F32)
-        tc1 = time.perf_counter()
-        cpu_baseline = dict(value=round(grad_bytes / (tc1 - tc0) / 1e9, 4), unit="GB/s", cores=orc.num_threads(),
-                            kind="oracle", seconds=round(tc1 - tc0, 2),
-                            sample="one full step of the workload (all %d matrices), oracle as it stands" % len(mats))
+            q0s.append(Q0)
+        reps, tc0 = 0, time.perf_counter()
+        while True:                      # whole steps until about 10 s of CPU work (at most 200 steps)
+            for li, (spec, g) in enumerate(mats):
+                orc.entropy(g.reshape(-1), w["stride"], w["chunk"], w["seed"], reps, w["bins"])
+                P, Q1, D = orc.compress(g, None, q0s[li], r)
+                orc.decompress(P, Q1, D, orc.BF16 if bf16 else orc.F32)
+            reps += 1
+            tc1 = time.perf_counter()
+            if tc1 - tc0 >= 10.0 or reps >= 200:
+                break
+        cpu_baseline = dict(value=round(reps * grad_bytes / (tc1 - tc0) / 1e9, 4), unit="GB/s",
+                            cores=orc.num_threads(), kind="oracle", seconds=round(tc1 - tc0, 2),
+                            sample="%d full steps of the workload (all %d matrices each), oracle as it stands"
+                                   % (reps, len(mats)))
 
     line = {
         "metric": "gradient GB/s through entropy+rank-r compress/decompress; % HBM/MFMA roofline",

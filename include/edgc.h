@@ -60,9 +60,11 @@ const char* edgc_last_error(const edgc_ctx* ctx);
  * edgc_profile_begin and edgc_profile_end every kernel the context launches is
  * bracketed by a pair of HIP events on the stream it runs on; the event pool
  * (2 * max_launches events) is created in edgc_profile_begin, never in a hot
- * call, and launches beyond the pool go untimed.  edgc_profile_end synchronises
- * the device and returns, per kernel name, the launch count, the summed
- * duration and the summed algorithmic bytes and flops of those launches.
+ * call, and launches beyond the pool go untimed (16 <= max_launches <= 2^20).
+ * edgc_profile_end synchronises the device and returns, per kernel name, the
+ * launch count, the summed duration (each bracket minus what an empty event
+ * pair reads, event_overhead_ms, measured in edgc_profile_begin) and the summed
+ * algorithmic bytes and flops of those launches.
  * `kernel` points to a static string.  *n_out is the number of kernels seen
  * (may exceed cap; only cap entries are written). */
 typedef struct {
@@ -71,6 +73,7 @@ typedef struct {
     double      total_ms;
     double      bytes;
     double      flops;
+    double      event_overhead_ms;
 } edgc_kernel_stat;
 int edgc_profile_begin(edgc_ctx* ctx, uint32_t max_launches);
 int edgc_profile_end(edgc_ctx* ctx, edgc_kernel_stat* out, uint32_t cap, uint32_t* n_out);

@@ -52,7 +52,7 @@ class _RankDecision(C.Structure):
 
 class _KernelStat(C.Structure):
     _fields_ = [("kernel", C.c_char_p), ("launches", C.c_uint64), ("total_ms", C.c_double),
-                ("bytes", C.c_double), ("flops", C.c_double)]
+                ("bytes", C.c_double), ("flops", C.c_double), ("event_overhead_ms", C.c_double)]
 
 
 ENTROPY_RESULT_BYTES = C.sizeof(_EntropyResult)
@@ -226,7 +226,8 @@ class Context:
         n = C.c_uint32(0)
         self._check(self._L.edgc_profile_end(self._h, arr, cap, C.byref(n)), "edgc_profile_end")
         return {arr[i].kernel.decode(): dict(launches=int(arr[i].launches), total_ms=arr[i].total_ms,
-                                             bytes=arr[i].bytes, flops=arr[i].flops)
+                                             bytes=arr[i].bytes, flops=arr[i].flops,
+                                             event_overhead_ms=arr[i].event_overhead_ms)
                 for i in range(min(cap, n.value))}
 
     # -- entropy -----------------------------------------------------------

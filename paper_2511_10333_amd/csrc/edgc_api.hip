@@ -99,7 +99,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
 extern "C" int edgc_profile_begin(edgc_ctx* ctx, uint32_t max_launches)
 {
     if (!ctx) return EDGC_EINVAL;
-    if (max_launches == 0 || max_launches > (1u << 20)) return fail(ctx, EDGC_EINVAL, "max_launches out of range");
+    if (max_launches < 16 || max_launches > (1u << 20)) return fail(ctx, EDGC_EINVAL, "max_launches out of range");
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
     Profiler& p = ctx->prof;
     while (p.pool.size() < 2ull * max_launches) {
@@ -110,6 +110,22 @@ extern "C" int edgc_profile_begin(edgc_ctx* ctx, uint32_t max_launches)
     p.next = 0;
     p.recs.clear();
     p.recs.reserve(max_launches);
+    // What an event pair reads with nothing between the two records: subtracted from every
+    // bracketed launch in edgc_profile_end (median of 15 pairs on the default stream).
+    {
+        constexpr int kPairs = 15;
+        float gap[kPairs];
+        EDGC_HIP_TRY(ctx, hipDeviceSynchronize());
+        for (int i = 0; i < kPairs; ++i) {
+            EDGC_HIP_TRY(ctx, hipEventRecord(p.pool[2 * i], nullptr));
+            EDGC_HIP_TRY(ctx, hipEventRecord(p.pool[2 * i + 1], nullptr));
+        }
+        EDGC_HIP_TRY(ctx, hipDeviceSynchronize());
+        for (int i = 0; i < kPairs; ++i)
+            EDGC_HIP_TRY(ctx, hipEventElapsedTime(&gap[i], p.pool[2 * i], p.pool[2 * i + 1]));
+        std::sort(gap, gap + kPairs);
+        p.empty_pair_ms = gap[kPairs / 2];
+    }
     p.on = true;
     return EDGC_OK;
 }
@@ -127,7 +143,8 @@ extern "C" int edgc_profile_end(edgc_ctx* ctx, edgc_kernel_stat* out, uint32_t c
         float ms = 0.0f;
         EDGC_HIP_TRY(ctx, hipEventElapsedTime(&ms, r.a, r.b));
         acc[r.kid].launches += 1;
-        acc[r.kid].total_ms += ms;
+        acc[r.kid].total_ms += std::max(0.0, static_cast<double>(ms) - p.empty_pair_ms);
+        acc[r.kid].event_overhead_ms = p.empty_pair_ms;
         acc[r.kid].bytes += r.bytes;
         acc[r.kid].flops += r.flops;
     }

@@ -52,6 +52,7 @@ struct Profiler {
     std::vector<hipEvent_t> pool;   // created in edgc_profile_begin, never in a hot call
     size_t next = 0;
     std::vector<ProfRec> recs;
+    double empty_pair_ms = 0.0;     // elapsed time an empty event pair reports
 };
 
 }  // namespace edgc
