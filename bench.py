@@ -45,8 +45,10 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
-    ap.add_argument("--no-graph", action="store_true",
-                    help="issue every launch eagerly instead of replaying a captured HIP graph")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the compress/decompress launches from a captured HIP graph instead of issuing "
+                         "them eagerly (measured slower here: the graph's branches overlap less than the streams)")
+    ap.add_argument("--no-graph", action="store_true", help="kept for compatibility: eager launches are the default")
     ap.add_argument("--streams", type=int, default=0,
                     help="HIP streams (one library context each) the layers are spread over; 0 = one per layer")
     return ap.parse_args()
@@ -93,6 +95,9 @@ def main() -> int:
     ctxs = [edgc.Context(0, max_bins=w["bins"], max_rank=max(r, 4), max_rows=max_m, max_cols=max_n)
             for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    # the entropy estimate only reads the gradient and uses scratch of its own, so it runs on a
+    # stream of its own beside the layer's compress/decompress chain
+    ent_streams = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else streams
     ctx = ctxs[0]
 
     NBUF = 3   # entropy results are read two steps after they are enqueued: the GPU never waits for the host
@@ -108,6 +113,7 @@ def main() -> int:
         ctx.init_q(Q, 0, r, w["seed"] + li)
         layers.append(dict(
             spec=spec, G=G, Q=Q, ctx=ctxs[li % n_streams], stream=streams[li % n_streams],
+            estream=ent_streams[li % n_streams],
             E=torch.empty((spec.m, spec.n), dtype=torch.float32, device="cuda"),
             P=torch.empty((spec.m, ldf), dtype=torch.float32, device="cuda"),
             out=torch.empty_like(G), fresh=True,
@@ -120,7 +126,7 @@ def main() -> int:
                           total_iters=args.steps + args.warmup, min_warmup_frac=0.10)
     state = edgc.RankState()
     decisions = []
-    step_events = [[torch.cuda.Event() for _ in range(n_streams)] for _ in range(NBUF)]
+    step_events = [[torch.cuda.Event() for _ in range(2 * n_streams)] for _ in range(NBUF)]
     counter = {"step": 0}
 
     for L in layers:
@@ -150,20 +156,24 @@ def main() -> int:
         if graph["g"] is None:
             for L in layers:
                 L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t, w["bins"],
-                                                L["ent"][t % NBUF], stream=L["stream"])
+                                                L["ent"][t % NBUF], stream=L["estream"])
             compress_all()
             for si, st in enumerate(streams):
                 step_events[t % NBUF][si].record(st)
+            for si, st in enumerate(ent_streams):
+                step_events[t % NBUF][n_streams + si].record(st)
         else:
             # entropy launches stay eager (their sampling slot changes with the step); the
             # compress + decompress launches of all layers are one captured graph
+            for L in layers:
+                L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
+                                                w["bins"], L["ent"][t % NBUF], stream=L["estream"])
             with torch.cuda.stream(main_stream):
-                for L in layers:
-                    L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
-                                                    w["bins"], L["ent"][t % NBUF], stream=main_stream)
                 graph["g"].replay()
-                for ev in step_events[t % NBUF]:
+                for ev in step_events[t % NBUF][:n_streams]:
                     ev.record(main_stream)
+            for si, st in enumerate(ent_streams):
+                step_events[t % NBUF][n_streams + si].record(st)
         counter["step"] = t + 1
 
     main_stream = torch.cuda.Stream()
@@ -172,7 +182,7 @@ def main() -> int:
         one_step()
     torch.cuda.synchronize()
     graphed = False
-    if not args.no_graph:
+    if args.graph and not args.no_graph:
         try:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=main_stream, capture_error_mode="thread_local"):
@@ -208,7 +218,8 @@ def main() -> int:
     graph["g"] = None
     torch.cuda.synchronize()
     for L in layers:
-        L["stream"] = streams[0]
+        L["stream"] = L["estream"] = streams[0]
+    ent_streams = streams
     for c in ctxs:
         c.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)
     for _ in range(args.steps):
