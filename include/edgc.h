@@ -211,6 +211,88 @@ int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q,
                     uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
                     edgc_dtype dtype, uint64_t ld, void* hip_stream);
 
+/* ------------------------------------------------------------------------
+ * 4. Rank bounds, the linear communication-time model and stage alignment
+ *    (host only, except edgc_measure_rank_costs which times this library's
+ *    own kernels).
+ *
+ *    Sec. IV-D-1: compression at rank r pays when
+ *        T_com(r) = T_compress + D_compressed / B + T_decompress <= D_original / B,
+ *    the first rank that violates this closes the range and gives r_max; the
+ *    footnote puts r_min between r_max/6 and r_max/4.  The same section models
+ *    T_com(r) = eta * r.  Sec. IV-D-4 / Algorithm 2: stage i of the pipeline
+ *    gets the rank whose predicted time is T_com(stage 1) + (i-1) * T_microBack,
+ *    clamped to the bounds.  Sec. IV-B: with iteration sampling rate alpha the
+ *    entropy is measured once every 1/alpha iterations of a window.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    uint32_t rank;
+    uint32_t _pad;
+    double   t_compress;        /* seconds                                               */
+    double   t_decompress;      /* seconds                                               */
+    double   bytes_compressed;  /* D_compressed: what a rank-r exchange sends, in bytes  */
+} edgc_rank_cost;
+
+typedef struct {
+    uint32_t r_max;             /* 0 => no candidate pays at this bandwidth              */
+    uint32_t r_min;             /* ceil(r_max / divisor), at least 1; 0 when r_max == 0  */
+    double   t_uncompressed;    /* D_original / B, seconds                               */
+} edgc_rank_bounds_result;
+
+/* costs: host, n entries in strictly ascending rank.  bandwidth in bytes per
+ * second.  r_min_divisor in [4, 6].  t_com_out: host, n entries or NULL,
+ * receives T_com of every candidate.  Candidates are scanned upwards and the
+ * scan stops at the first one that violates the inequality, so a candidate
+ * above it never becomes r_max even if it satisfies the inequality again.
+ * Errors: EDGC_EINVAL for null pointers, n == 0, non-ascending ranks, a
+ * non-positive bandwidth or size, a negative time, or a divisor outside
+ * [4, 6]; EDGC_ENONFINITE for a NaN/Inf input. */
+int edgc_rank_bounds(const edgc_rank_cost* costs, uint32_t n, double bytes_original,
+                     double bandwidth, double r_min_divisor, edgc_rank_bounds_result* out,
+                     double* t_com_out);
+
+/* Least-squares fit through the origin of T_com(r) = eta * r over n points
+ * (host arrays): eta = sum(r T) / sum(r^2); *mape_percent (may be NULL) =
+ * 100 * mean(|T - eta r| / T).  Errors: EDGC_EINVAL for null pointers, n == 0,
+ * a zero rank or a non-positive time; EDGC_ENONFINITE for NaN/Inf. */
+int edgc_fit_eta(const uint32_t* ranks, const double* t_com, uint32_t n, double* eta,
+                 double* mape_percent);
+
+/* Algorithm 2.  ranks_out[0] = r_stage1 (stage 1 keeps the rank Algorithm 1
+ * gave it); for stage i = 2..n_stages the budget is eta * r_stage1 +
+ * (i-1) * t_microback and the rank is floor(budget / eta + 1e-9), clamped to
+ * [r_min, r_max], then lowered to the largest allowed rank not above it (the
+ * smallest allowed rank when none is; allowed: host, ascending, or NULL).
+ * t_com_out (host, n_stages entries or NULL) receives eta * rank per stage.
+ * Errors: EDGC_EINVAL for null ranks_out, n_stages == 0, eta <= 0,
+ * t_microback < 0, r_min == 0, r_min > r_max or a non-ascending allowed set;
+ * EDGC_ENONFINITE for NaN/Inf. */
+int edgc_stage_ranks(uint32_t r_stage1, double t_microback, double eta, uint32_t r_min,
+                     uint32_t r_max, const uint32_t* allowed, uint32_t n_allowed,
+                     uint32_t n_stages, uint32_t* ranks_out, double* t_com_out);
+
+/* Returns 1 when the entropy is to be measured at window-relative iteration
+ * iter_in_window with period = 1/alpha (iterations 0, period, 2*period, ...),
+ * 0 when not, EDGC_EINVAL when period == 0. */
+int edgc_entropy_due(uint64_t iter_in_window, uint32_t period);
+
+/* Times edgc_compress and edgc_decompress of this library on the caller's
+ * buffers (arguments as for those two calls; grad_out must not alias grad
+ * here) at each of n_ranks candidate ranks (host array, ascending): one
+ * untimed round, then `reps` rounds of compress followed by decompress, each
+ * call bracketed by HIP events on hip_stream.  costs_out[i] (host) receives
+ * the rank, the mean time of either call in seconds, and bytes_compressed =
+ * (m + n) * rank * 4 (P and Q in fp32, what the two exchanges of a data-
+ * parallel step would carry).  Overwrites residual, Q, P and grad_out;
+ * synchronises the stream; not a hot-path call.
+ * Errors: those of edgc_compress / edgc_decompress, EDGC_EINVAL for reps == 0
+ * or n_ranks == 0. */
+int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m,
+                            uint32_t n, uint64_t ld, float* residual, float* Q, uint32_t ldq,
+                            float* P, uint32_t ldp, void* grad_out, const uint32_t* ranks,
+                            uint32_t n_ranks, uint32_t reps, edgc_rank_cost* costs_out,
+                            void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 from dataclasses import dataclass
-from typing import Optional, Sequence
+from typing import List, Optional, Sequence
 
 F32, BF16 = 0, 1
 OK, EINVAL, ENOMEM, EHIP, ENOTIMPL, ENONFINITE = 0, -1, -2, -3, -4, -5
@@ -88,6 +88,20 @@ def load_library() -> C.CDLL:
     L.edgc_select_rank.restype = i32
     L.edgc_select_rank.argtypes = [C.POINTER(_RankState), vp, u32, u64, C.POINTER(_RankParams),
                                    C.POINTER(_RankDecision)]
+    L.edgc_rank_bounds.restype = i32
+    L.edgc_rank_bounds.argtypes = [C.POINTER(_RankCost), u32, C.c_double, C.c_double, C.c_double,
+                                   C.POINTER(_RankBounds), C.POINTER(C.c_double)]
+    L.edgc_fit_eta.restype = i32
+    L.edgc_fit_eta.argtypes = [C.POINTER(u32), C.POINTER(C.c_double), u32, C.POINTER(C.c_double),
+                               C.POINTER(C.c_double)]
+    L.edgc_stage_ranks.restype = i32
+    L.edgc_stage_ranks.argtypes = [u32, C.c_double, C.c_double, u32, u32, C.POINTER(u32), u32, u32,
+                                   C.POINTER(u32), C.POINTER(C.c_double)]
+    L.edgc_entropy_due.restype = i32
+    L.edgc_entropy_due.argtypes = [u64, u32]
+    L.edgc_measure_rank_costs.restype = i32
+    L.edgc_measure_rank_costs.argtypes = [vp, vp, i32, u32, u32, u64, vp, vp, u32, vp, u32, vp,
+                                          C.POINTER(u32), u32, u32, C.POINTER(_RankCost), vp]
     L.edgc_init_q.restype = i32
     L.edgc_init_q.argtypes = [vp, vp, u32, u32, u32, u32, u64, vp]
     L.edgc_compress.restype = i32
@@ -96,6 +110,31 @@ def load_library() -> C.CDLL:
     L.edgc_decompress.argtypes = [vp, vp, u32, vp, u32, u32, u32, u32, vp, vp, i32, u64, vp]
     _lib = L
     return L
+
+
+class _RankCost(C.Structure):
+    _fields_ = [("rank", C.c_uint32), ("_pad", C.c_uint32), ("t_compress", C.c_double),
+                ("t_decompress", C.c_double), ("bytes_compressed", C.c_double)]
+
+
+class _RankBounds(C.Structure):
+    _fields_ = [("r_max", C.c_uint32), ("r_min", C.c_uint32), ("t_uncompressed", C.c_double)]
+
+
+@dataclass
+class RankCost:
+    rank: int
+    t_compress: float
+    t_decompress: float
+    bytes_compressed: float
+
+
+@dataclass
+class RankBounds:
+    r_max: int
+    r_min: int
+    t_uncompressed: float
+    t_com: List[float]
 
 
 @dataclass
@@ -168,6 +207,56 @@ def select_rank(state: RankState, H_window: Sequence[float], iters_in_window: in
     state.have_ref, state.compressing = st.have_ref, st.compressing
     state.H_ref, state.r_prev, state.iters_seen = st.H_ref, st.r_prev, int(st.iters_seen)
     return RankDecision(int(dec.rank), dec.r_unclamped, dec.H_mean, dec.T_com)
+
+
+def rank_bounds(costs: Sequence[RankCost], bytes_original: float, bandwidth: float,
+                r_min_divisor: float = 4.0) -> RankBounds:
+    """edgc_rank_bounds: host-only."""
+    L = load_library()
+    arr = (_RankCost * max(len(costs), 1))()
+    for i, c in enumerate(costs):
+        arr[i] = _RankCost(c.rank, 0, c.t_compress, c.t_decompress, c.bytes_compressed)
+    out = _RankBounds()
+    t = (C.c_double * max(len(costs), 1))()
+    rc = L.edgc_rank_bounds(arr, len(costs), bytes_original, bandwidth, r_min_divisor, C.byref(out), t)
+    if rc != OK:
+        raise EdgcError(rc, "edgc_rank_bounds")
+    return RankBounds(int(out.r_max), int(out.r_min), out.t_uncompressed, list(t)[:len(costs)])
+
+
+def fit_eta(ranks: Sequence[int], t_com: Sequence[float]):
+    """edgc_fit_eta: host-only.  Returns (eta, MAPE in percent)."""
+    L = load_library()
+    n = len(ranks)
+    r = (C.c_uint32 * max(n, 1))(*[int(x) for x in ranks])
+    t = (C.c_double * max(n, 1))(*[float(x) for x in t_com][:n])
+    eta, mape = C.c_double(0), C.c_double(0)
+    rc = L.edgc_fit_eta(r, t, n if len(t_com) == n else 0, C.byref(eta), C.byref(mape))
+    if rc != OK:
+        raise EdgcError(rc, "edgc_fit_eta")
+    return eta.value, mape.value
+
+
+def stage_ranks(r_stage1: int, t_microback: float, eta: float, r_min: int, r_max: int, n_stages: int,
+                allowed: Optional[Sequence[int]] = None):
+    """edgc_stage_ranks: host-only.  Returns (ranks per stage, predicted T_com per stage)."""
+    L = load_library()
+    ranks = (C.c_uint32 * max(n_stages, 1))()
+    t = (C.c_double * max(n_stages, 1))()
+    al = (C.c_uint32 * len(allowed))(*allowed) if allowed else None
+    rc = L.edgc_stage_ranks(r_stage1, t_microback, eta, r_min, r_max, al, len(allowed) if allowed else 0,
+                            n_stages, ranks, t)
+    if rc != OK:
+        raise EdgcError(rc, "edgc_stage_ranks")
+    return [int(x) for x in ranks][:n_stages], list(t)[:n_stages]
+
+
+def entropy_due(iter_in_window: int, period: int) -> bool:
+    """edgc_entropy_due: host-only."""
+    rc = load_library().edgc_entropy_due(iter_in_window, period)
+    if rc < 0:
+        raise EdgcError(rc, "edgc_entropy_due")
+    return bool(rc)
 
 
 def _dtype_code(t) -> int:
@@ -290,3 +379,18 @@ class Context:
             self._h, P.data_ptr(), P.shape[1], Q.data_ptr(), Q.shape[1], m, n, r, residual.data_ptr(),
             grad_out.data_ptr(), _dtype_code(grad_out), grad_out.stride(0), _stream_handle(stream))
         self._check(rc, "edgc_decompress")
+
+    def measure_rank_costs(self, grad, residual, Q, P, grad_out, ranks: Sequence[int], reps: int = 5,
+                           stream=None) -> List[RankCost]:
+        """edgc_measure_rank_costs: times compress and decompress at each rank on these buffers
+        (all overwritten except grad); synchronises the stream."""
+        m, n = grad.shape
+        rk = (C.c_uint32 * max(len(ranks), 1))(*[int(r) for r in ranks])
+        out = (_RankCost * max(len(ranks), 1))()
+        rc = self._L.edgc_measure_rank_costs(
+            self._h, grad.data_ptr(), _dtype_code(grad), m, n, grad.stride(0), residual.data_ptr(),
+            Q.data_ptr(), Q.shape[1], P.data_ptr(), P.shape[1], grad_out.data_ptr(), rk, len(ranks),
+            reps, out, _stream_handle(stream))
+        self._check(rc, "edgc_measure_rank_costs")
+        return [RankCost(int(c.rank), c.t_compress, c.t_decompress, c.bytes_compressed)
+                for c in list(out)[:len(ranks)]]

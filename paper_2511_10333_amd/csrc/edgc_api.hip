@@ -274,3 +274,60 @@ extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, cons
     return launch_decompress(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld,
                              static_cast<hipStream_t>(hip_stream));
 }
+
+// Sec. IV-D-1 asks for T_compress and T_decompress measured on the system at hand: time this
+// library's own two calls at every candidate rank.
+extern "C" int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m,
+                                       uint32_t n, uint64_t ld, float* residual, float* Q, uint32_t ldq,
+                                       float* P, uint32_t ldp, void* grad_out, const uint32_t* ranks,
+                                       uint32_t n_ranks, uint32_t reps, edgc_rank_cost* costs_out,
+                                       void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!ranks || !costs_out || n_ranks == 0 || reps == 0)
+        return fail(ctx, EDGC_EINVAL, "null ranks/costs_out, n_ranks == 0 or reps == 0");
+    if (grad_out == grad) return fail(ctx, EDGC_EINVAL, "grad_out must not alias grad while measuring");
+    for (uint32_t i = 0; i < n_ranks; ++i)
+        if (ranks[i] == 0 || (i && ranks[i] <= ranks[i - 1])) return fail(ctx, EDGC_EINVAL, "ranks must ascend");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    int rc = EDGC_OK;
+    auto hip_ok = [&](hipError_t e, const char* what) {
+        if (e == hipSuccess) return true;
+        rc = fail(ctx, EDGC_EHIP, what);
+        return false;
+    };
+    for (auto& e : ev)
+        if (!hip_ok(hipEventCreate(&e), "hipEventCreate")) break;
+    for (uint32_t i = 0; rc == EDGC_OK && i < n_ranks; ++i) {
+        const uint32_t r = ranks[i];
+        double t_c = 0.0, t_d = 0.0;
+        // round 0 is untimed and starts from a zero residual and fresh Q columns
+        rc = edgc_init_q(ctx, Q, n, ldq, 0, r, 0x5eedULL + r, hip_stream);
+        for (uint32_t rep = 0; rc == EDGC_OK && rep <= reps; ++rep) {
+            if (!hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) break;
+            rc = edgc_compress(ctx, grad, dtype, m, n, ld, residual, rep == 0, Q, ldq, P, ldp, r, 1, hip_stream);
+            if (rc != EDGC_OK) break;
+            if (!hip_ok(hipEventRecord(ev[1], st), "hipEventRecord")) break;
+            rc = edgc_decompress(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld, hip_stream);
+            if (rc != EDGC_OK) break;
+            if (!hip_ok(hipEventRecord(ev[2], st), "hipEventRecord")) break;
+            if (!hip_ok(hipEventSynchronize(ev[2]), "hipEventSynchronize")) break;
+            if (rep == 0) continue;
+            float ms_c = 0.f, ms_d = 0.f;
+            if (!hip_ok(hipEventElapsedTime(&ms_c, ev[0], ev[1]), "hipEventElapsedTime")) break;
+            if (!hip_ok(hipEventElapsedTime(&ms_d, ev[1], ev[2]), "hipEventElapsedTime")) break;
+            t_c += ms_c;
+            t_d += ms_d;
+        }
+        costs_out[i].rank = r;
+        costs_out[i]._pad = 0;
+        costs_out[i].t_compress = 1e-3 * t_c / reps;
+        costs_out[i].t_decompress = 1e-3 * t_d / reps;
+        costs_out[i].bytes_compressed = 4.0 * (static_cast<double>(m) + static_cast<double>(n)) * r;
+    }
+    for (auto& e : ev)
+        if (e) (void)hipEventDestroy(e);
+    return rc;
+}

@@ -218,3 +218,42 @@ def test_hidden5120_bf16_attention_projection_full_size(r):
     w = gen.WORKLOADS["cfg4_gpt_h5120_bf16"]
     G = gen.lowrank_plus_noise(5120, 5120, 512, w["decay"], w["noise"], 1, "bf16")
     check_step(G, None, _q0(5120, r), r, "bf16")
+
+
+# ---------------------------------------------------------------------------
+# rank-cost measurement (Sec. IV-D-1): the call runs the same two entry points, so what it
+# leaves behind is one more valid step at the last rank; times are positive and sane
+# ---------------------------------------------------------------------------
+def test_measure_rank_costs_runs_the_two_calls_and_reports_bytes():
+    m, n, ranks = 512, 768, [4, 8, 16, 32]
+    g = gen.lowrank_plus_noise(m, n, 64, 0.9, 1e-4, 3)
+    c = ctx()
+    gd = to_dev(g)
+    res, out = torch.empty((m, n), device="cuda"), torch.empty((m, n), device="cuda")
+    Q, P = torch.empty((n, 32), device="cuda"), torch.empty((m, 32), device="cuda")
+    costs = c.measure_rank_costs(gd, res, Q, P, out, ranks, reps=3)
+    torch.cuda.synchronize()
+    assert [k.rank for k in costs] == ranks
+    for k in costs:
+        assert 1e-6 < k.t_compress < 5e-3 and 1e-6 < k.t_decompress < 5e-3
+        assert k.bytes_compressed == 4.0 * (m + n) * k.rank
+    # the buffers hold the last round at rank 32: P orthonormal, out + E = D, and the
+    # error-feedback sum over the 1 + 3 rounds since the residual was reset
+    Ph = to_host(P).astype(np.float64)
+    assert np.abs(Ph.T @ Ph - np.eye(32)).max() <= 1e-4
+    # ... and they equal what the same sequence of plain calls leaves (one untimed round from
+    # a zero residual and seeded Q columns, then three more)
+    res2, out2 = torch.empty_like(res), torch.empty_like(out)
+    Q2, P2 = torch.empty_like(Q), torch.empty_like(P)
+    c.init_q(Q2, 0, 32, 0x5EED + 32)
+    for rep in range(4):
+        c.compress(gd, res2, rep == 0, Q2, P2, 32)
+        c.decompress(P2, Q2, 32, res2, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(res, res2) and torch.equal(out, out2) and torch.equal(P, P2) and torch.equal(Q, Q2)
+    with pytest.raises(edgc.EdgcError):
+        c.measure_rank_costs(gd, res, Q, P, gd, ranks, reps=3)           # aliasing refused
+    with pytest.raises(edgc.EdgcError):
+        c.measure_rank_costs(gd, res, Q, P, out, ranks, reps=0)
+    with pytest.raises(edgc.EdgcError):
+        c.measure_rank_costs(gd, res, Q, P, out, [8, 4], reps=1)

@@ -35,6 +35,8 @@ def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(b._EntropyResult) == 48
     assert ctypes.sizeof(b._RankDecision) == 32
     assert ctypes.sizeof(b._RankState) == 32
+    assert ctypes.sizeof(b._RankCost) == 32
+    assert ctypes.sizeof(b._RankBounds) == 16
 
 
 def _both(prm_kwargs, windows):
