@@ -293,6 +293,59 @@ int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, u
                             uint32_t n_ranks, uint32_t reps, edgc_rank_cost* costs_out,
                             void* hip_stream);
 
+/* ------------------------------------------------------------------------
+ * 5. Batched calls: every gradient tensor of a pipeline stage in one launch
+ *    sequence (Sec. IV-C: the rank is adjusted per window and per stage, so a
+ *    stage's tensors share one rank; Sec. IV-D: DAC works on stages).  Each
+ *    kernel of the compressor runs once over the whole list (the grid is the
+ *    concatenation of the tensors' tiles), which removes the per-tensor launch
+ *    and ramp-up cost that dominates for small matrices.
+ *
+ *    A tensor that compression cannot shrink is sent as it stands: one with a
+ *    single row or column (biases, norm weights), or one whose factors are not
+ *    smaller than itself, (m + n) r >= m n.  edgc_tensor_bypassed tells which
+ *    (1 = sent as it stands, 0 = compressed, EDGC_EINVAL for a zero argument).
+ *    For such a tensor edgc_compress_batch does nothing and
+ *    edgc_decompress_batch copies grad to grad_out when the two differ; its
+ *    residual, Q and P may be NULL.
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    const void* grad;           /* device m x n (ld) of the batch's dtype                  */
+    void*       grad_out;       /* device m x n (ld_out); may be the same buffer as grad   */
+    float*      residual;       /* device m x n fp32 (dense): as for edgc_compress         */
+    float*      Q;              /* device n x ldq fp32                                     */
+    float*      P;              /* device m x ldp fp32                                     */
+    uint64_t    ld, ld_out;
+    uint32_t    m, n, ldq, ldp;
+    int32_t     residual_is_zero;
+    uint32_t    _pad;
+} edgc_tensor;
+
+int edgc_tensor_bypassed(uint32_t m, uint32_t n, uint32_t r);
+
+/* Allocates the scratch of a batch: position i of later batch calls may hold a
+ * tensor of up to rows[i] x cols[i] (host arrays).  Replaces an earlier
+ * reservation; synchronises the device; not a hot call.  Like the context's
+ * own scratch, the slots serve one stream at a time.
+ * Errors: EDGC_EINVAL for null arrays, EDGC_ENOMEM. */
+int edgc_reserve_batch(edgc_ctx* ctx, const uint32_t* rows, const uint32_t* cols, uint32_t count);
+
+/* tensors: host array of `count` descriptors (read during the call only; the
+ * device buffers they name are caller-owned).  Tensor i uses batch slot i.
+ * What is computed per compressed tensor is exactly edgc_compress /
+ * edgc_decompress at rank r; results are bit-identical to the single-tensor
+ * calls when the launch shapes agree and equal to rounding otherwise.
+ * edgc_compress_batch reads grad, ld, residual, residual_is_zero, Q, P;
+ * edgc_decompress_batch reads P, Q, residual, grad_out, ld_out (and grad, ld
+ * of tensors sent as they stand).
+ * Errors: as for the single-tensor calls, EDGC_EINVAL also for count above the
+ * reservation or a tensor larger than its slot.  Nothing is launched when a
+ * descriptor is rejected. */
+int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count, edgc_dtype dtype,
+                        uint32_t r, uint32_t power_iters, void* hip_stream);
+int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                          edgc_dtype dtype, uint32_t r, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -102,6 +102,14 @@ def load_library() -> C.CDLL:
     L.edgc_measure_rank_costs.restype = i32
     L.edgc_measure_rank_costs.argtypes = [vp, vp, i32, u32, u32, u64, vp, vp, u32, vp, u32, vp,
                                           C.POINTER(u32), u32, u32, C.POINTER(_RankCost), vp]
+    L.edgc_tensor_bypassed.restype = i32
+    L.edgc_tensor_bypassed.argtypes = [u32, u32, u32]
+    L.edgc_reserve_batch.restype = i32
+    L.edgc_reserve_batch.argtypes = [vp, C.POINTER(u32), C.POINTER(u32), u32]
+    L.edgc_compress_batch.restype = i32
+    L.edgc_compress_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, u32, vp]
+    L.edgc_decompress_batch.restype = i32
+    L.edgc_decompress_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
     L.edgc_init_q.restype = i32
     L.edgc_init_q.argtypes = [vp, vp, u32, u32, u32, u32, u64, vp]
     L.edgc_compress.restype = i32
@@ -110,6 +118,25 @@ def load_library() -> C.CDLL:
     L.edgc_decompress.argtypes = [vp, vp, u32, vp, u32, u32, u32, u32, vp, vp, i32, u64, vp]
     _lib = L
     return L
+
+
+class _Tensor(C.Structure):
+    _fields_ = [("grad", C.c_void_p), ("grad_out", C.c_void_p), ("residual", C.c_void_p),
+                ("Q", C.c_void_p), ("P", C.c_void_p), ("ld", C.c_uint64), ("ld_out", C.c_uint64),
+                ("m", C.c_uint32), ("n", C.c_uint32), ("ldq", C.c_uint32), ("ldp", C.c_uint32),
+                ("residual_is_zero", C.c_int32), ("_pad", C.c_uint32)]
+
+
+@dataclass
+class Tensor:
+    """One entry of a batch: torch CUDA tensors (``residual``, ``Q``, ``P`` may be None for a
+    tensor that is sent as it stands; 1-D gradients are taken as one row)."""
+    grad: object
+    grad_out: object
+    residual: object = None
+    Q: object = None
+    P: object = None
+    residual_is_zero: bool = False
 
 
 class _RankCost(C.Structure):
@@ -259,6 +286,14 @@ def entropy_due(iter_in_window: int, period: int) -> bool:
     return bool(rc)
 
 
+def tensor_bypassed(m: int, n: int, r: int) -> bool:
+    """edgc_tensor_bypassed: True when an m x n tensor is sent as it stands at rank r."""
+    rc = load_library().edgc_tensor_bypassed(m, n, r)
+    if rc < 0:
+        raise EdgcError(rc, "edgc_tensor_bypassed")
+    return bool(rc)
+
+
 def _dtype_code(t) -> int:
     import torch
     if t.dtype == torch.float32:
@@ -394,3 +429,44 @@ class Context:
         self._check(rc, "edgc_measure_rank_costs")
         return [RankCost(int(c.rank), c.t_compress, c.t_decompress, c.bytes_compressed)
                 for c in list(out)[:len(ranks)]]
+
+    # -- batched calls -----------------------------------------------------
+    def reserve_batch(self, shapes: Sequence[Sequence[int]]) -> None:
+        """edgc_reserve_batch: position i of later batches holds at most shapes[i] = (rows, cols)."""
+        n = len(shapes)
+        rows = (C.c_uint32 * max(n, 1))(*[int(s[0]) for s in shapes])
+        cols = (C.c_uint32 * max(n, 1))(*[int(s[1]) for s in shapes])
+        self._check(self._L.edgc_reserve_batch(self._h, rows, cols, n), "edgc_reserve_batch")
+
+    @staticmethod
+    def _marshal(tensors: Sequence[Tensor]):
+        arr = (_Tensor * max(len(tensors), 1))()
+        code = None
+        for i, t in enumerate(tensors):
+            g = t.grad if t.grad is not None else t.grad_out
+            m, n = (1, g.numel()) if g.dim() == 1 else g.shape
+            ld = lambda x: (x.stride(0) if x.dim() == 2 else x.numel()) if x is not None else 0
+            ptr = lambda x: x.data_ptr() if x is not None else None
+            arr[i] = _Tensor(ptr(t.grad), ptr(t.grad_out), ptr(t.residual), ptr(t.Q), ptr(t.P),
+                             ld(t.grad), ld(t.grad_out), m, n,
+                             t.Q.shape[1] if t.Q is not None else 0,
+                             t.P.shape[1] if t.P is not None else 0,
+                             1 if t.residual_is_zero else 0, 0)
+            c = _dtype_code(g)
+            if code is not None and c != code:
+                raise TypeError("all gradients of a batch must have one dtype")
+            code = c
+        return arr, (code if code is not None else F32)
+
+    def compress_batch(self, tensors: Sequence[Tensor], r: int, power_iters: int = 1, stream=None) -> None:
+        """edgc_compress_batch over a list of :class:`Tensor`."""
+        arr, code = self._marshal(tensors)
+        rc = self._L.edgc_compress_batch(self._h, arr, len(tensors), code, r, power_iters,
+                                         _stream_handle(stream))
+        self._check(rc, "edgc_compress_batch")
+
+    def decompress_batch(self, tensors: Sequence[Tensor], r: int, stream=None) -> None:
+        """edgc_decompress_batch over a list of :class:`Tensor`."""
+        arr, code = self._marshal(tensors)
+        rc = self._L.edgc_decompress_batch(self._h, arr, len(tensors), code, r, _stream_handle(stream))
+        self._check(rc, "edgc_decompress_batch")

@@ -25,6 +25,16 @@ hipError_t dev_alloc(T** p, size_t count)
     return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T));
 }
 
+void free_batch(edgc_ctx* ctx)
+{
+    for (BatchSlot& b : ctx->batch) {
+        for (void* p : {static_cast<void*>(b.part), static_cast<void*>(b.gram_part),
+                        static_cast<void*>(b.gram), static_cast<void*>(b.rinv), b.pt})
+            if (p) (void)hipFree(p);
+    }
+    ctx->batch.clear();
+}
+
 void free_scratch(Scratch& s)
 {
     void* ptrs[] = {s.mm_part, s.done_counter, s.counts, s.nonfinite, s.range, s.result_dev,
@@ -166,6 +176,7 @@ extern "C" int edgc_destroy(edgc_ctx* ctx)
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
+    free_batch(ctx);
     free_scratch(ctx->s);
     delete ctx;
     return EDGC_OK;
@@ -232,16 +243,26 @@ extern "C" int edgc_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, ui
 }
 
 static int check_factor_args(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
-                             uint32_t m, uint32_t n, uint32_t r, uint64_t ld)
+                             uint32_t m, uint32_t n, uint32_t r, uint64_t ld, uint64_t max_rows,
+                             uint64_t max_cols)
 {
     if (!P || !Q) return fail(ctx, EDGC_EINVAL, "null P or Q");
     if (m == 0 || n == 0) return fail(ctx, EDGC_EINVAL, "empty matrix");
-    if (m > ctx->max_rows || n > ctx->max_cols) return fail(ctx, EDGC_EINVAL, "matrix larger than the context");
+    if (m > max_rows || n > max_cols) return fail(ctx, EDGC_EINVAL, "matrix larger than the context");
     if (r == 0 || r > m || r > n || r > ctx->max_rank) return fail(ctx, EDGC_EINVAL, "rank out of range");
     if (ld < n || ldp < r || ldq < r) return fail(ctx, EDGC_EINVAL, "leading dimension too small");
     if (ldp % 4 || ldq % 4 || !aligned_to(P, 16) || !aligned_to(Q, 16))
         return fail(ctx, EDGC_EINVAL, "P and Q need 16-byte alignment and leading dimensions that are multiples of 4");
     return EDGC_OK;
+}
+
+// scratch of the context itself: serves one tensor
+static void own_scratch(edgc_ctx* ctx, TensorArgs& t, TensorScratch& cap)
+{
+    Scratch& s = ctx->s;
+    t.part = s.part; t.gram_part = s.gram_part; t.gram = s.gram; t.rinv = s.rinv; t.pt = s.pt;
+    cap.part_elems = s.part_elems;
+    cap.gram_part_elems = s.gram_part_elems;
 }
 
 extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
@@ -251,13 +272,20 @@ extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, 
     if (!ctx) return EDGC_EINVAL;
     if (!grad || !residual) return fail(ctx, EDGC_EINVAL, "null grad or residual");
     if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
-    if (int rc = check_factor_args(ctx, P, ldp, Q, ldq, m, n, r, ld)) return rc;
+    if (int rc = check_factor_args(ctx, P, ldp, Q, ldq, m, n, r, ld, ctx->max_rows, ctx->max_cols)) return rc;
     if (power_iters == 0) return fail(ctx, EDGC_EINVAL, "power_iters must be >= 1");
     if (!aligned_to(grad, dtype == EDGC_F32 ? 4 : 2) || !aligned_to(residual, 4))
         return fail(ctx, EDGC_EINVAL, "grad or residual misaligned");
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
-    return launch_compress(ctx, grad, dtype, m, n, ld, residual, residual_is_zero, Q, ldq, P, ldp, r,
-                           power_iters, static_cast<hipStream_t>(hip_stream));
+    Group g{};
+    g.count = 1;
+    g.r = r;
+    TensorArgs& t = g.t[0];
+    t.G = grad; t.ldg = ld; t.E = residual; t.e_zero = residual_is_zero ? 1 : 0;
+    t.Q = Q; t.ldq = ldq; t.P = P; t.ldp = ldp; t.m = m; t.n = n;
+    TensorScratch cap;
+    own_scratch(ctx, t, cap);
+    return launch_compress(ctx, g, &cap, dtype, power_iters, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
@@ -267,12 +295,167 @@ extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, cons
     if (!ctx) return EDGC_EINVAL;
     if (!residual || !grad_out) return fail(ctx, EDGC_EINVAL, "null residual or grad_out");
     if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
-    if (int rc = check_factor_args(ctx, P, ldp, Q, ldq, m, n, r, ld)) return rc;
+    if (int rc = check_factor_args(ctx, P, ldp, Q, ldq, m, n, r, ld, ctx->max_rows, ctx->max_cols)) return rc;
     if (!aligned_to(grad_out, dtype == EDGC_F32 ? 4 : 2) || !aligned_to(residual, 4))
         return fail(ctx, EDGC_EINVAL, "grad_out or residual misaligned");
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
-    return launch_decompress(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld,
-                             static_cast<hipStream_t>(hip_stream));
+    Group g{};
+    g.count = 1;
+    g.r = r;
+    TensorArgs& t = g.t[0];
+    t.E = residual; t.Q = const_cast<float*>(Q); t.ldq = ldq; t.P = const_cast<float*>(P); t.ldp = ldp;
+    t.out = grad_out; t.ldo = ld; t.m = m; t.n = n;
+    return launch_decompress(ctx, g, dtype, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---------------------------------------------------------------------------
+// Batched calls: all 2-D gradients of a pipeline stage in one launch sequence.
+// ---------------------------------------------------------------------------
+extern "C" int edgc_tensor_bypassed(uint32_t m, uint32_t n, uint32_t r)
+{
+    if (m == 0 || n == 0 || r == 0) return EDGC_EINVAL;
+    if (m == 1 || n == 1) return 1;
+    return (static_cast<uint64_t>(m) + n) * r >= static_cast<uint64_t>(m) * n ? 1 : 0;
+}
+
+extern "C" int edgc_reserve_batch(edgc_ctx* ctx, const uint32_t* rows, const uint32_t* cols, uint32_t count)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (count && (!rows || !cols)) return fail(ctx, EDGC_EINVAL, "null shape arrays");
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    EDGC_HIP_TRY(ctx, hipDeviceSynchronize());          // nothing may still be using the old slots
+    free_batch(ctx);
+    const uint64_t rp = (ctx->max_rank <= 32) ? 32 : (ctx->max_rank <= 64 ? 64 : 128);
+    ctx->batch.resize(count);
+    bool ok = true;
+    for (uint32_t i = 0; i < count && ok; ++i) {
+        BatchSlot& b = ctx->batch[i];
+        b.rows = rows[i];
+        b.cols = cols[i];
+        if (rows[i] == 0 || cols[i] == 0 || rows[i] == 1 || cols[i] == 1) continue;   // never compressed
+        const uint64_t rows_pad = (static_cast<uint64_t>(rows[i]) + 63) / 64 * 64;
+        b.cap.part_elems = compress_part_elems(rows[i], cols[i], ctx->max_rank, ctx->num_cu);
+        b.cap.gram_part_elems = (rows_pad / 64) * 36ull * 256ull;
+        ok = ok && dev_alloc(&b.part, b.cap.part_elems) == hipSuccess;
+        ok = ok && dev_alloc(&b.gram_part, b.cap.gram_part_elems) == hipSuccess;
+        ok = ok && dev_alloc(&b.gram, static_cast<size_t>(36) * 256) == hipSuccess;
+        ok = ok && dev_alloc(&b.rinv, static_cast<size_t>(ctx->max_rank) * ctx->max_rank) == hipSuccess;
+        ok = ok && hipMalloc(&b.pt, 2ull * rp * rows_pad * 2ull) == hipSuccess;
+    }
+    if (!ok) {
+        (void)hipGetLastError();
+        free_batch(ctx);
+        return fail(ctx, EDGC_ENOMEM, "batch scratch allocation failed");
+    }
+    return EDGC_OK;
+}
+
+namespace {
+
+// Checks one descriptor; returns 1 when the tensor is sent as it stands, 0 when it is
+// compressed, < 0 on error.
+int check_batch_tensor(edgc_ctx* ctx, const edgc_tensor& d, uint32_t i, edgc_dtype dtype, uint32_t r,
+                       bool need_grad, bool need_out)
+{
+    if (d.m == 0 || d.n == 0) return fail(ctx, EDGC_EINVAL, "empty tensor in batch");
+    if ((need_grad && !d.grad) || (need_out && !d.grad_out)) return fail(ctx, EDGC_EINVAL, "null gradient pointer in batch");
+    const uint32_t esz = dtype == EDGC_F32 ? 4 : 2;
+    if ((need_grad && (!aligned_to(d.grad, esz) || d.ld < d.n)) ||
+        (need_out && (!aligned_to(d.grad_out, esz) || d.ld_out < d.n)))
+        return fail(ctx, EDGC_EINVAL, "gradient misaligned or leading dimension too small in batch");
+    if (edgc_tensor_bypassed(d.m, d.n, r) == 1) return 1;
+    const BatchSlot& b = ctx->batch[i];
+    if (d.m > b.rows || d.n > b.cols || !b.part)
+        return fail(ctx, EDGC_EINVAL, "tensor larger than the batch slot reserved for its position");
+    if (!d.residual || !aligned_to(d.residual, 4)) return fail(ctx, EDGC_EINVAL, "null or misaligned residual in batch");
+    if (int rc = check_factor_args(ctx, d.P, d.ldp, d.Q, d.ldq, d.m, d.n, r, d.n, b.rows, b.cols)) return rc;
+    return 0;
+}
+
+}  // namespace
+
+extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                   edgc_dtype dtype, uint32_t r, uint32_t power_iters, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (count == 0) return EDGC_OK;
+    if (!tensors) return fail(ctx, EDGC_EINVAL, "null tensor list");
+    if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
+    if (r == 0 || r > ctx->max_rank) return fail(ctx, EDGC_EINVAL, "rank out of range");
+    if (power_iters == 0) return fail(ctx, EDGC_EINVAL, "power_iters must be >= 1");
+    if (count > ctx->batch.size()) return fail(ctx, EDGC_EINVAL, "more tensors than reserved batch slots");
+    std::vector<int> kind(count);
+    for (uint32_t i = 0; i < count; ++i) {
+        kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, true, false);
+        if (kind[i] < 0) return kind[i];
+    }
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Group g{};
+    TensorScratch cap[kMaxGroup];
+    g.r = r;
+    auto flush = [&]() -> int {
+        if (g.count == 0) return EDGC_OK;
+        const int rc = launch_compress(ctx, g, cap, dtype, power_iters, st);
+        g = Group{};
+        g.r = r;
+        return rc;
+    };
+    for (uint32_t i = 0; i < count; ++i) {
+        if (kind[i] == 1) continue;
+        const edgc_tensor& d = tensors[i];
+        const BatchSlot& b = ctx->batch[i];
+        TensorArgs& t = g.t[g.count];
+        t.G = d.grad; t.ldg = d.ld; t.E = d.residual; t.e_zero = d.residual_is_zero ? 1 : 0;
+        t.Q = d.Q; t.ldq = d.ldq; t.P = d.P; t.ldp = d.ldp; t.m = d.m; t.n = d.n;
+        t.part = b.part; t.gram_part = b.gram_part; t.gram = b.gram; t.rinv = b.rinv; t.pt = b.pt;
+        cap[g.count] = b.cap;
+        if (++g.count == kMaxGroup)
+            if (int rc = flush()) return rc;
+    }
+    return flush();
+}
+
+extern "C" int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                     edgc_dtype dtype, uint32_t r, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (count == 0) return EDGC_OK;
+    if (!tensors) return fail(ctx, EDGC_EINVAL, "null tensor list");
+    if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
+    if (r == 0 || r > ctx->max_rank) return fail(ctx, EDGC_EINVAL, "rank out of range");
+    if (count > ctx->batch.size()) return fail(ctx, EDGC_EINVAL, "more tensors than reserved batch slots");
+    std::vector<int> kind(count);
+    for (uint32_t i = 0; i < count; ++i) {
+        kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, false, true);
+        if (kind[i] < 0) return kind[i];
+        if (kind[i] == 1 && !tensors[i].grad) return fail(ctx, EDGC_EINVAL, "null gradient pointer in batch");
+    }
+    EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    Group g{};
+    g.r = r;
+    auto flush = [&]() -> int {
+        if (g.count == 0) return EDGC_OK;
+        const int rc = launch_decompress(ctx, g, dtype, st);
+        g = Group{};
+        g.r = r;
+        return rc;
+    };
+    const uint32_t esz = dtype == EDGC_F32 ? 4 : 2;
+    for (uint32_t i = 0; i < count; ++i) {
+        const edgc_tensor& d = tensors[i];
+        if (kind[i] == 1) {                      // sent as it stands: hand the gradient on
+            if (int rc = launch_copy_rows(ctx, d.grad, d.ld, d.grad_out, d.ld_out, d.m, d.n, esz, st)) return rc;
+            continue;
+        }
+        TensorArgs& t = g.t[g.count];
+        t.E = d.residual; t.Q = d.Q; t.ldq = d.ldq; t.P = d.P; t.ldp = d.ldp;
+        t.out = d.grad_out; t.ldo = d.ld_out; t.m = d.m; t.n = d.n;
+        if (++g.count == kMaxGroup)
+            if (int rc = flush()) return rc;
+    }
+    return flush();
 }
 
 // Sec. IV-D-1 asks for T_compress and T_decompress measured on the system at hand: time this

@@ -33,6 +33,58 @@ struct Scratch {
 
 constexpr int kMaxReduceBlocks = 4096;
 
+// ---------------------------------------------------------------------------
+// Grouped launches of the compressor.  Every compressor kernel works on a list of tensors:
+// the grid is the concatenation of the tensors' block ranges and a block finds its tensor
+// from `first`.  The list travels by value in the kernel arguments (no table upload); a
+// single-tensor call is a group of one.
+// ---------------------------------------------------------------------------
+constexpr int kMaxGroup = 16;
+
+struct TensorArgs {
+    const void* G;          // gradient (m x n, ldg), or null: D is re-read as it stands
+    float*  E;              // residual: E_old in, D out (P-pass); D in, E_new out (decompress)
+    float*  Q;              // n x r (ldq)
+    float*  P;              // m x r (ldp)
+    void*   out;            // decompressed gradient (m x n, ldo)
+    float*  part;           // split partials: [S][rows][rank_pad]
+    double* gram_part;      // per-block upper-triangle Gram tiles
+    double* gram;           // summed Gram tiles
+    double* rinv;           // r x r inverse factor
+    void*   pt;             // transposed bf16 copy of P^: [planes][rank_pad][m_pad]
+    const double* tiles;    // what k_chol reads: gram_part (nb sets) or gram (one set)
+    uint64_t ldg, ldo;
+    uint32_t ldq, ldp, m, n, m_pad;
+    int32_t  e_zero;
+    uint32_t sp;            // column splits the P-pass wrote (k_reduce_gram sums them)
+    uint32_t sq;            // row splits the Q-pass wrote (k_reduce_q sums them)
+    uint32_t nb;            // Gram sets in `tiles`
+    uint32_t d0, d1;        // decomposition of the launch at hand (set by the host before it)
+    uint32_t first;         // first block of this tensor in the grouped grid
+};
+
+struct Group {
+    uint32_t count;
+    uint32_t r;             // rank, the same for every tensor of a group
+    TensorArgs t[kMaxGroup];
+};
+
+// scratch capacities behind one tensor's pointers (host side only)
+struct TensorScratch {
+    size_t part_elems = 0, gram_part_elems = 0;
+};
+
+// Scratch of one position of a batch (edgc_reserve_batch), sized for that position's shape.
+struct BatchSlot {
+    uint32_t rows = 0, cols = 0;
+    float*  part = nullptr;
+    double* gram_part = nullptr;
+    double* gram = nullptr;
+    double* rinv = nullptr;
+    void*   pt = nullptr;
+    TensorScratch cap;
+};
+
 // Kernel ids for the optional per-kernel event timing (edgc_profile_begin/end).
 enum KernelId {
     KID_SET_RANGE = 0, KID_MINMAX, KID_HIST, KID_SAMPLE_IDX, KID_INIT_Q, KID_PASS_P,
@@ -66,6 +118,7 @@ struct edgc_ctx {
     // decompress); 0 = the built-in choice
     uint32_t tune_p = 0, tune_q = 0, tune_d = 0;
     edgc::Scratch s;
+    std::vector<edgc::BatchSlot> batch;
     edgc::Profiler prof;
     std::string last_error;
 };
@@ -144,12 +197,12 @@ int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uin
 // launchers (compress.hip)
 int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1,
                   uint64_t seed, hipStream_t st);
-int launch_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dt, uint32_t m, uint32_t n,
-                    uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
-                    float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, hipStream_t st);
-int launch_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
-                      uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
-                      edgc_dtype dt, uint64_t ld, hipStream_t st);
+// `g` holds the tensors' pointers, shapes and scratch; the launchers fill in the rest.
+int launch_compress(edgc_ctx* ctx, Group& g, const TensorScratch* cap, edgc_dtype dt,
+                    uint32_t power_iters, hipStream_t st);
+int launch_decompress(edgc_ctx* ctx, Group& g, edgc_dtype dt, hipStream_t st);
+int launch_copy_rows(edgc_ctx* ctx, const void* src, uint64_t ld_src, void* dst, uint64_t ld_dst,
+                     uint32_t m, uint32_t n, uint32_t elem_bytes, hipStream_t st);
 int prepare_compress_kernels(edgc_ctx* ctx);
 int prepare_entropy_kernels(edgc_ctx* ctx);
 size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_rank, int num_cu);

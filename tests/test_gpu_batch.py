@@ -1,0 +1,167 @@
+"""Batched compress / decompress (every tensor of a stage in one launch sequence) against the
+oracle, tensor by tensor, and against the single-tensor entry points."""
+import numpy as np
+import pytest
+import torch
+
+import edgc_inputs as gen
+import paper_2511_10333_amd as edgc
+from oracle import edgc_oracle as orc
+from gpu_util import rel_fro, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-3, "bf16": 1e-2}
+
+
+def _widen(a):
+    return gen.bf16_bits_to_f32(a) if a.dtype == np.uint16 else a
+
+
+class Stage:
+    """Host and device state of a list of gradient tensors that share one rank."""
+
+    def __init__(self, shapes, r, dtype, seed=0, ragged_ld=False):
+        self.shapes, self.r, self.dtype = shapes, r, dtype
+        self.ctx = edgc.Context(0, max_rank=128, max_rows=64, max_cols=64)    # own scratch unused here
+        self.ctx.reserve_batch([s if len(s) == 2 else (1, s[0]) for s in shapes])
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.G, self.Q, self.E = [], [], []
+        self.t = []
+        for i, s in enumerate(shapes):
+            if len(s) == 1:                                   # 1-D tensor: never compressed
+                g = gen.gaussian(s[0], 1e-3, seed + i).astype(np.float32)
+                g = gen.to_bf16_bits(g) if dtype == "bf16" else g
+                self.G.append(g); self.Q.append(None); self.E.append(None)
+                self.t.append(edgc.Tensor(to_dev(g), torch.zeros(s[0], dtype=tdt, device="cuda")))
+                continue
+            m, n = s
+            g = gen.lowrank_plus_noise(m, n, min(m, n, 48), 0.9, 1e-4, seed + i, dtype=dtype)
+            self.G.append(g)
+            if edgc.tensor_bypassed(m, n, r):
+                self.Q.append(None); self.E.append(None)
+                self.t.append(edgc.Tensor(to_dev(g), torch.zeros((m, n), dtype=tdt, device="cuda")))
+                continue
+            ldq = (r + 3) // 4 * 4
+            q = np.zeros((n, ldq), dtype=np.float32)
+            orc.init_q(q, 0, r, 100 + i)
+            self.Q.append(q)
+            self.E.append(None)
+            gd = to_dev(g)
+            if ragged_ld:                                     # rows embedded in a wider buffer
+                wide = torch.zeros((m, n + 8), dtype=tdt, device="cuda")
+                wide[:, :n] = gd
+                gd = wide[:, :n]
+            self.t.append(edgc.Tensor(gd, torch.zeros((m, n), dtype=tdt, device="cuda"),
+                                      torch.full((m, n), float("nan"), device="cuda"), to_dev(q),
+                                      torch.full((m, ldq), 7.0, device="cuda"), True))
+
+    def compressed(self, i):
+        return self.Q[i] is not None
+
+    def step_device(self):
+        self.ctx.compress_batch(self.t, self.r)
+        self.ctx.decompress_batch(self.t, self.r)
+        torch.cuda.synchronize()
+        for t in self.t:
+            t.residual_is_zero = False
+
+    def step_oracle_and_compare(self):
+        r, tol = self.r, TOL[self.dtype]
+        code = orc.BF16 if self.dtype == "bf16" else orc.F32
+        for i, g in enumerate(self.G):
+            t = self.t[i]
+            if not self.compressed(i):
+                assert np.array_equal(to_host(t.grad_out).reshape(g.shape), g), f"tensor {i} must pass through"
+                continue
+            first = self.E[i] is None
+            Po, Qo, Do = orc.compress(g, self.E[i], np.ascontiguousarray(self.Q[i][:, :r]), r)
+            out_o, E_o = orc.decompress(Po, Qo, Do, code)
+            self.Q[i][:, :r] = Qo
+            self.E[i] = E_o
+            nD = np.linalg.norm(Do.astype(np.float64))
+            assert rel_fro(to_host(t.P)[:, :r], Po) <= tol, i
+            assert rel_fro(to_host(t.Q)[:, :r], Qo) <= tol, i
+            assert rel_fro(_widen(to_host(t.grad_out)), _widen(out_o)) <= tol, i
+            assert np.linalg.norm(to_host(t.residual).astype(np.float64) - E_o) <= tol * nD, i
+            # D = M^ + E_new on the device (first step: its D is the oracle's D bit for bit)
+            if first:
+                assert rel_fro(to_host(t.residual) + _widen(to_host(t.grad_out)), Do) <= 1e-6
+
+
+MIXED = [(384, 640), (100,), (130, 70), (6, 200), (257, 129), (512, 256), (64,)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("r", [4, 16])
+def test_mixed_stage_matches_oracle_over_three_steps(dtype, r):
+    st = Stage(MIXED, r, dtype, seed=3)
+    assert not st.compressed(1) and not st.compressed(6)          # 1-D
+    assert st.compressed(3) == (not edgc.tensor_bypassed(6, 200, r))
+    for _ in range(3):                                            # residual carried from step to step
+        st.step_device()
+        st.step_oracle_and_compare()
+
+
+def test_ragged_leading_dimension_and_rank_48():
+    st = Stage([(200, 328), (192, 192), (333, 100)], 48, "f32", seed=9, ragged_ld=True)
+    st.step_device()
+    st.step_oracle_and_compare()
+
+
+def test_more_tensors_than_one_group_holds():
+    shapes = [(64 + 8 * i, 96 + 4 * i) for i in range(21)]        # 21 > 16 tensors per launch
+    st = Stage(shapes, 8, "f32", seed=11)
+    st.step_device()
+    st.step_oracle_and_compare()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_batch_equals_single_tensor_calls(dtype):
+    shapes, r = [(512, 768), (256, 1024), (1024, 256)], 16
+    st = Stage(shapes, r, dtype, seed=21)
+    single = edgc.Context(0, max_rank=128, max_rows=1024, max_cols=1024)
+    ref = []
+    for t in st.t:                                                 # same inputs through the single calls
+        Q, P = t.Q.clone(), torch.empty_like(t.P)
+        E, out = torch.empty_like(t.residual), torch.empty_like(t.grad_out)
+        single.compress(t.grad, E, True, Q, P, r)
+        single.decompress(P, Q, r, E, out)
+        ref.append((P, Q, E, out))
+    st.step_device()
+    for t, (P, Q, E, out) in zip(st.t, ref):
+        # the launch shapes differ (a batch shares the GPU among its tensors), so sums are taken
+        # in another order: equal to rounding, not bit for bit
+        assert rel_fro(to_host(t.P)[:, :r], to_host(P)[:, :r]) <= 2e-5
+        assert rel_fro(to_host(t.Q)[:, :r], to_host(Q)[:, :r]) <= 2e-5
+        assert rel_fro(_widen(to_host(t.grad_out)), _widen(to_host(out))) <= (1e-2 if dtype == "bf16" else 2e-5)
+    # a batch of one has the single call's launch shape: bit for bit
+    one = Stage([shapes[0]], r, dtype, seed=21)
+    one.step_device()
+    P, Q, E, out = ref[0]
+    assert torch.equal(one.t[0].P[:, :r], P[:, :r]) and torch.equal(one.t[0].Q[:, :r], Q[:, :r])
+    assert torch.equal(one.t[0].residual, E) and torch.equal(one.t[0].grad_out, out)
+
+
+def test_batch_rejects_bad_descriptors_before_launching():
+    st = Stage([(256, 256), (128, 384)], 8, "f32", seed=5)
+    before = [t.P.clone() for t in st.t]
+    big = edgc.Tensor(torch.zeros((300, 256), device="cuda"), torch.zeros((300, 256), device="cuda"),
+                      torch.zeros((300, 256), device="cuda"), torch.zeros((256, 8), device="cuda"),
+                      torch.zeros((300, 8), device="cuda"), True)
+    with pytest.raises(edgc.EdgcError):                            # larger than its slot
+        st.ctx.compress_batch([big, st.t[1]], 8)
+    with pytest.raises(edgc.EdgcError):                            # more tensors than slots
+        st.ctx.compress_batch(st.t + [st.t[0]], 8)
+    with pytest.raises(edgc.EdgcError):                            # rank above the context's
+        st.ctx.compress_batch(st.t, 129)
+    bad = edgc.Tensor(st.t[1].grad, st.t[1].grad_out, None, st.t[1].Q, st.t[1].P, True)
+    with pytest.raises(edgc.EdgcError):                            # second descriptor is bad:
+        st.ctx.compress_batch([st.t[0], bad], 8)                   # nothing of the first may run
+    torch.cuda.synchronize()
+    for t, p in zip(st.t, before):
+        assert torch.equal(t.P, p)
+    with pytest.raises(TypeError):
+        st.ctx.compress_batch([st.t[0], edgc.Tensor(st.t[1].grad.bfloat16(), st.t[1].grad_out.bfloat16())], 8)
+    st.ctx.compress_batch([], 8)                                   # empty batch: nothing to do
+    st.ctx.decompress_batch([], 8)
