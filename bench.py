@@ -49,6 +49,11 @@ def parse_args():
                     help="replay the compress/decompress launches from a captured HIP graph instead of issuing "
                          "them eagerly (measured slower here: the graph's branches overlap less than the streams)")
     ap.add_argument("--no-graph", action="store_true", help="kept for compatibility: eager launches are the default")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="N > 0: compress/decompress through the batched entry points, the layers split into N "
+                         "groups (balanced by size), each group one launch sequence on its own stream")
+    ap.add_argument("--ent-streams", type=int, default=0,
+                    help="streams the entropy estimates are spread over; 0 = one per compress stream")
     ap.add_argument("--streams", type=int, default=0,
                     help="HIP streams (one library context each) the layers are spread over; 0 = one per layer")
     return ap.parse_args()
@@ -97,7 +102,9 @@ def main() -> int:
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     # the entropy estimate only reads the gradient and uses scratch of its own, so it runs on a
     # stream of its own beside the layer's compress/decompress chain
-    ent_streams = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else streams
+    n_ent = args.ent_streams or n_streams
+    ent_streams = [torch.cuda.Stream() for _ in range(n_ent)] if (n_streams > 1 or args.ent_streams) else streams
+    n_ent = len(ent_streams)
     ctx = ctxs[0]
 
     NBUF = 3   # entropy results are read two steps after they are enqueued: the GPU never waits for the host
@@ -113,7 +120,7 @@ def main() -> int:
         ctx.init_q(Q, 0, r, w["seed"] + li)
         layers.append(dict(
             spec=spec, G=G, Q=Q, ctx=ctxs[li % n_streams], stream=streams[li % n_streams],
-            estream=ent_streams[li % n_streams],
+            estream=ent_streams[li % n_ent],
             E=torch.empty((spec.m, spec.n), dtype=torch.float32, device="cuda"),
             P=torch.empty((spec.m, ldf), dtype=torch.float32, device="cuda"),
             out=torch.empty_like(G), fresh=True,
@@ -121,12 +128,33 @@ def main() -> int:
         ))
     torch.cuda.synchronize()
 
+    # batched mode: groups of layers, each with a context whose batch slots fit the group
+    groups = []
+    if args.batch > 0:
+        order = sorted(range(len(layers)), key=lambda i: -layers[i]["spec"].m * layers[i]["spec"].n)
+        members = [[] for _ in range(min(args.batch, len(layers)))]
+        load = [0] * len(members)
+        for i in order:                                  # largest first into the lightest group
+            k = load.index(min(load))
+            members[k].append(i)
+            load[k] += layers[i]["spec"].m * layers[i]["spec"].n
+        for k, idx in enumerate(members):
+            idx.sort()
+            gctx = edgc.Context(0, max_bins=16, max_rank=max(r, 4), max_rows=64, max_cols=64)
+            gctx.reserve_batch([(layers[i]["spec"].m, layers[i]["spec"].n) for i in idx])
+            tensors = [edgc.Tensor(layers[i]["G"], layers[i]["out"], layers[i]["E"], layers[i]["Q"],
+                                   layers[i]["P"], True) for i in idx]
+            groups.append(dict(ctx=gctx, tensors=tensors, stream=streams[k % n_streams]))
+        ctxs_all = ctxs + [g["ctx"] for g in groups]
+    else:
+        ctxs_all = ctxs
+
     ref = min(mats, key=lambda t: t[0].m * t[0].n)[0]
     prm = edgc.RankParams(ref.m, ref.n, r_min=r, r_max=r, step_limit=8, allowed=[r],
                           total_iters=args.steps + args.warmup, min_warmup_frac=0.10)
     state = edgc.RankState()
     decisions = []
-    step_events = [[torch.cuda.Event() for _ in range(2 * n_streams)] for _ in range(NBUF)]
+    step_events = [[torch.cuda.Event() for _ in range(n_streams + n_ent)] for _ in range(NBUF)]
     counter = {"step": 0}
 
     for L in layers:
@@ -144,6 +172,13 @@ def main() -> int:
             decisions.append(edgc.select_rank(state, H, 1, prm))
 
     def compress_all():
+        if groups:
+            for g in groups:
+                g["ctx"].compress_batch(g["tensors"], r, stream=g["stream"])
+                g["ctx"].decompress_batch(g["tensors"], r, stream=g["stream"])
+                for t in g["tensors"]:
+                    t.residual_is_zero = False
+            return
         for L in layers:
             c, st = L["ctx"], L["stream"]
             c.compress(L["G"], L["E"], L["fresh"], L["Q"], L["P"], r, stream=st)
@@ -209,6 +244,16 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     host_issue_ms = (t_issued - t0) * 1e3 / args.steps
 
+    # host cost of issuing one step with an idle GPU behind it (no back-pressure)
+    idle_issue = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        ti0 = time.perf_counter()
+        one_step()
+        idle_issue.append((time.perf_counter() - ti0) * 1e3)
+    torch.cuda.synchronize()
+    host_issue_idle_ms = sorted(idle_issue)[len(idle_issue) // 2]
+
     elem_bytes = 2 if bf16 else 4
     grad_bytes = sum(s.m * s.n for s, _ in mats) * elem_bytes
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
@@ -219,13 +264,15 @@ def main() -> int:
     torch.cuda.synchronize()
     for L in layers:
         L["stream"] = L["estream"] = streams[0]
-    ent_streams = streams
-    for c in ctxs:
+    for g in groups:
+        g["stream"] = streams[0]
+    ent_streams = [streams[0]] * n_ent
+    for c in ctxs_all:
         c.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)
     for _ in range(args.steps):
         one_step()
     stats = {}
-    for c in ctxs:
+    for c in ctxs_all:
         for name, sdict in c.profile_end().items():
             acc = stats.setdefault(name, dict(launches=0, total_ms=0.0, bytes=0.0, flops=0.0))
             for k in acc:
@@ -280,14 +327,15 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": ["%dx%d" % (s.m, s.n) for s, _ in mats],
                    "rank": r, "stride": w["stride"], "chunk": w["chunk"], "bins": w["bins"],
-                   "streams": n_streams, "hip_graph": graphed,
+                   "streams": n_streams, "hip_graph": graphed, "batch_groups": len(groups),
                    "gradient_bytes_per_step": grad_bytes},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "mfma": mfma,
         "last_rank_decision": decisions[-1].rank if decisions else None,
         "host_issue_ms_per_step": round(host_issue_ms, 4),
+        "host_issue_idle_gpu_ms_per_step": round(host_issue_idle_ms, 4),
     }
     print(json.dumps(line))
-    for c in ctxs:
+    for c in ctxs_all:
         c.close()
     return 0
 

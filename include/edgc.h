@@ -346,6 +346,21 @@ int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t coun
 int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
                           edgc_dtype dtype, uint32_t r, void* hip_stream);
 
+/* The entropy of a pipeline stage whose gradients are separate buffers (Sec.
+ * IV-C / Algorithm 1 work with one entropy per stage): `count` (1..32)
+ * buffers, grads[i] (host array of device pointers) of n_elems[i] elements
+ * each.  Every buffer is sampled by its own element index with the same
+ * (stride, chunk, seed, step), hence the same slot; the range, the histogram
+ * and the entropy are taken over the union of those samples, and n_sampled /
+ * n_nonfinite count over all buffers.  Other arguments, result and errors as
+ * for edgc_entropy_estimate, which is this call with count = 1. */
+int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* grads, const uint64_t* n_elems,
+                                uint32_t count, edgc_dtype dtype, uint64_t stride, uint32_t chunk,
+                                uint64_t seed, uint64_t step, uint32_t bins,
+                                const float* range_lo_hi_or_null, edgc_entropy_result* out,
+                                uint64_t* counts_out_or_null, void* hip_stream);
+
+
 #ifdef __cplusplus
 }
 #endif

@@ -83,6 +83,9 @@ def load_library() -> C.CDLL:
     L.edgc_profile_end.argtypes = [vp, C.POINTER(_KernelStat), u32, C.POINTER(u32)]
     L.edgc_entropy_estimate.restype = i32
     L.edgc_entropy_estimate.argtypes = [vp, vp, i32, u64, u64, u32, u64, u64, u32, vp, vp, vp, vp]
+    L.edgc_entropy_estimate_batch.restype = i32
+    L.edgc_entropy_estimate_batch.argtypes = [vp, C.POINTER(C.c_void_p), C.POINTER(u64), u32, i32, u64, u32,
+                                              u64, u64, u32, vp, vp, vp, vp]
     L.edgc_sample_indices.restype = i32
     L.edgc_sample_indices.argtypes = [vp, u64, u64, u32, u64, u64, vp, u64, C.POINTER(u64), vp]
     L.edgc_select_rank.restype = i32
@@ -357,11 +360,25 @@ class Context:
     # -- entropy -----------------------------------------------------------
     def entropy_estimate_async(self, grad, stride: int, chunk: int, seed: int, step: int, bins: int,
                                out_pinned, value_range=None, counts_out=None, stream=None) -> None:
-        """edgc_entropy_estimate.  ``out_pinned``: pinned uint8 CPU tensor of
-        ENTROPY_RESULT_BYTES bytes, valid after the stream is synchronised."""
+        """edgc_entropy_estimate, or edgc_entropy_estimate_batch when ``grad`` is a list of tensors
+        (one estimate over the union of their samples).  ``out_pinned``: pinned uint8 CPU tensor
+        of ENTROPY_RESULT_BYTES bytes, valid after the stream is synchronised."""
         rng = None
         if value_range is not None:
             rng = (C.c_float * 2)(float(value_range[0]), float(value_range[1]))
+        if isinstance(grad, (list, tuple)):
+            k = len(grad)
+            ptrs = (C.c_void_p * max(k, 1))(*[g.data_ptr() for g in grad])
+            sizes = (C.c_uint64 * max(k, 1))(*[g.numel() for g in grad])
+            codes = {_dtype_code(g) for g in grad}
+            if len(codes) > 1:
+                raise TypeError("all buffers of one estimate must have one dtype")
+            rc = self._L.edgc_entropy_estimate_batch(
+                self._h, ptrs, sizes, k, codes.pop() if codes else F32, stride, chunk, seed, step, bins,
+                C.cast(rng, C.c_void_p) if rng is not None else None, out_pinned.data_ptr(),
+                counts_out.data_ptr() if counts_out is not None else None, _stream_handle(stream))
+            self._check(rc, "edgc_entropy_estimate_batch")
+            return
         rc = self._L.edgc_entropy_estimate(
             self._h, grad.data_ptr(), _dtype_code(grad), grad.numel(), stride, chunk, seed, step, bins,
             C.cast(rng, C.c_void_p) if rng is not None else None, out_pinned.data_ptr(),

@@ -206,14 +206,47 @@ extern "C" int edgc_entropy_estimate(edgc_ctx* ctx, const void* grad, edgc_dtype
     if (int rc = check_sampler_args(ctx, stride, chunk)) return rc;
     if (bins == 0 || bins > ctx->max_bins) return fail(ctx, EDGC_EINVAL, "bins == 0 or bins > max_bins");
     if (range && !(range[0] <= range[1])) return fail(ctx, EDGC_EINVAL, "range needs lo <= hi");
-    if (!aligned_to(grad, dtype == EDGC_F32 ? 4 : 2)) return fail(ctx, EDGC_EINVAL, "grad misaligned");
+    return edgc_entropy_estimate_batch(ctx, &grad, &n_elems, 1, dtype, stride, chunk, seed, step, bins, range,
+                                       out, counts_out, hip_stream);
+}
+
+extern "C" int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* grads, const uint64_t* n_elems,
+                                           uint32_t count, edgc_dtype dtype, uint64_t stride, uint32_t chunk,
+                                           uint64_t seed, uint64_t step, uint32_t bins, const float* range,
+                                           edgc_entropy_result* out, uint64_t* counts_out, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!grads || !n_elems || !out) return fail(ctx, EDGC_EINVAL, "null grads, n_elems or out");
+    if (count == 0 || count > static_cast<uint32_t>(kMaxEntGroup))
+        return fail(ctx, EDGC_EINVAL, "an entropy estimate takes 1 to 32 buffers");
+    if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
+    if (int rc = check_sampler_args(ctx, stride, chunk)) return rc;
+    if (bins == 0 || bins > ctx->max_bins) return fail(ctx, EDGC_EINVAL, "bins == 0 or bins > max_bins");
+    if (range && !(range[0] <= range[1])) return fail(ctx, EDGC_EINVAL, "range needs lo <= hi");
     if (counts_out && !aligned_to(counts_out, 8)) return fail(ctx, EDGC_EINVAL, "counts misaligned");
-    if (n_elems > (1ull << 44)) return fail(ctx, EDGC_EINVAL, "n_elems too large");
-    const SampleGeom g = make_geom(grad, dtype, n_elems, stride, chunk, seed, step);
+    for (uint32_t i = 0; i < count; ++i) {
+        if (!grads[i]) return fail(ctx, EDGC_EINVAL, "null grad");
+        if (!aligned_to(grads[i], dtype == EDGC_F32 ? 4 : 2)) return fail(ctx, EDGC_EINVAL, "grad misaligned");
+        if (n_elems[i] > (1ull << 44)) return fail(ctx, EDGC_EINVAL, "n_elems too large");
+    }
+    EntGroup g{};
+    g.count = count;
+    // one vector width for the whole group: scalar loads as soon as one buffer needs them
+    for (int pass = 0; pass < 2; ++pass) {
+        bool uniform = true;
+        g.n_items = g.n_sampled = 0;
+        for (uint32_t i = 0; i < count; ++i) {
+            g.base[i] = grads[i];
+            g.geom[i] = make_geom(grads[i], dtype, n_elems[i], stride, chunk, seed, step, pass == 0);
+            g.n_items += g.geom[i].n_items;
+            g.n_sampled += g.geom[i].n_sampled;
+            uniform = uniform && (g.geom[i].vec > 1) == (g.geom[0].vec > 1);
+        }
+        if (uniform) break;
+    }
     if (g.n_sampled == 0) return fail(ctx, EDGC_ENONFINITE, "the sampling predicate selects no element");
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
-    return launch_entropy(ctx, grad, dtype, g, bins, range, out, counts_out,
-                          static_cast<hipStream_t>(hip_stream));
+    return launch_entropy(ctx, g, dtype, bins, range, out, counts_out, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int edgc_sample_indices(edgc_ctx* ctx, uint64_t n_elems, uint64_t stride, uint32_t chunk,

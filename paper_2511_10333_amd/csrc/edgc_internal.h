@@ -184,13 +184,24 @@ struct SampleGeom {
     uint32_t vec;       // elements per item: 1, 4 (fp32) or 8 (bf16)
 };
 
+// The buffers of one entropy estimate: the sample is the union of every buffer's own
+// chunk-strided sample, and range, histogram and entropy are taken over that union.
+constexpr int kMaxEntGroup = 32;
+struct EntGroup {
+    uint32_t count;
+    uint32_t _pad;
+    uint64_t n_items;       // over all buffers
+    uint64_t n_sampled;     // over all buffers
+    const void* base[kMaxEntGroup];
+    SampleGeom geom[kMaxEntGroup];
+};
+
 SampleGeom make_geom(const void* base, edgc_dtype dt, uint64_t n, uint64_t stride, uint32_t chunk,
-                     uint64_t seed, uint64_t step);
+                     uint64_t seed, uint64_t step, bool allow_vec = true);
 
 // launchers (entropy.hip)
-int launch_entropy(edgc_ctx* ctx, const void* grad, edgc_dtype dt, const SampleGeom& g,
-                   uint32_t bins, const float* range, edgc_entropy_result* out,
-                   uint64_t* counts_out, hipStream_t st);
+int launch_entropy(edgc_ctx* ctx, const EntGroup& grp, edgc_dtype dt, uint32_t bins,
+                   const float* range, edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st);
 int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uint64_t cap,
                           hipStream_t st);
 

@@ -148,7 +148,7 @@ __device__ __forceinline__ bool finite_f32(float x)
 // kernel 1: range of the finite sample
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>
-__global__ __launch_bounds__(kMMBlock) void k_minmax(const T* __restrict__ g, SampleGeom geom,
+__global__ __launch_bounds__(kMMBlock) void k_minmax(const EntGroup grp,
                                                      float* __restrict__ part,
                                                      unsigned int* done, RangeParams* rp,
                                                      float fbins, unsigned long long* counts,
@@ -161,9 +161,12 @@ __global__ __launch_bounds__(kMMBlock) void k_minmax(const T* __restrict__ g, Sa
     if (gtid == 0) *nonfinite = 0ull;
 
     float lo = INFINITY, hi = -INFINITY;
+    constexpr int U = 4;
+    for (uint32_t ti = 0; ti < grp.count; ++ti) {
+    const SampleGeom& geom = grp.geom[ti];
+    const T* __restrict__ g = static_cast<const T*>(grp.base[ti]);
     ItemCursor cur;
     cur.init(gtid, G, geom.ipc);
-    constexpr int U = 4;
     while (cur.item < geom.n_items) {
         float v[U][VEC];
         uint32_t mask[U];
@@ -184,6 +187,7 @@ __global__ __launch_bounds__(kMMBlock) void k_minmax(const T* __restrict__ g, Sa
                     lo = fminf(lo, v[u][p]);
                     hi = fmaxf(hi, v[u][p]);
                 }
+    }
     }
 
     __shared__ float s_lo[kMMBlock / 64], s_hi[kMMBlock / 64];
@@ -252,7 +256,7 @@ __global__ void k_set_range(RangeParams* rp, float lo, float hi, float fbins,
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>
 __global__ __launch_bounds__(kHistBlock) void k_hist(
-    const T* __restrict__ g, SampleGeom geom, const RangeParams* __restrict__ rp, uint32_t bins,
+    const EntGroup grp, const RangeParams* __restrict__ rp, uint32_t bins,
     uint32_t bins_local, uint32_t rep_shift, unsigned long long* counts,
     unsigned long long* nonfinite, unsigned int* done, edgc_entropy_result* res)
 {
@@ -270,9 +274,12 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
     unsigned long long nf = 0;
 
     const uint64_t G = static_cast<uint64_t>(gridDim.x) * kHistBlock;
+    constexpr int U = 4;
+    for (uint32_t ti = 0; ti < grp.count; ++ti) {
+    const SampleGeom& geom = grp.geom[ti];
+    const T* __restrict__ g = static_cast<const T*>(grp.base[ti]);
     ItemCursor cur;
     cur.init(static_cast<uint64_t>(blockIdx.x) * kHistBlock + threadIdx.x, G, geom.ipc);
-    constexpr int U = 4;
     while (cur.item < geom.n_items) {
         float v[U][VEC];
         uint32_t mask[U];
@@ -300,6 +307,7 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
                 const uint32_t rel = b - bin_base;
                 if (rel < local_n) atomicAdd(&h[(rel << rep_shift) | rep], 1u);
             }
+    }
     }
     __syncthreads();
 
@@ -344,7 +352,7 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
         for (int w = 0; w < kHistBlock / 64; ++w) { acc += s_a[w]; tot += s_b[w]; }
         edgc_entropy_result r;
         r.lo = rp->lo; r.hi = rp->hi;
-        r.n_sampled = geom.n_sampled;
+        r.n_sampled = grp.n_sampled;
         r.n_nonfinite = __hip_atomic_load(nonfinite, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         r._pad = 0;
         if (tot > 0.0) {
@@ -387,12 +395,12 @@ __global__ __launch_bounds__(256) void k_sample_indices(SampleGeom geom, uint64_
 // host side
 // ---------------------------------------------------------------------------
 SampleGeom make_geom(const void* base, edgc_dtype dt, uint64_t n, uint64_t stride, uint32_t chunk,
-                     uint64_t seed, uint64_t step)
+                     uint64_t seed, uint64_t step, bool allow_vec)
 {
     SampleGeom g{};
     const uint32_t elem = (dt == EDGC_F32) ? 4u : 2u;
     const uint32_t V = 16u / elem;
-    const bool aligned = (reinterpret_cast<uintptr_t>(base) % 16u) == 0;
+    const bool aligned = allow_vec && (reinterpret_cast<uintptr_t>(base) % 16u) == 0;
     g.n = n;
     g.stride = stride;
     g.slot = mix64(seed, step) % stride;
@@ -426,7 +434,7 @@ static uint32_t grid_for(uint64_t n_items, int block, int per_thread, int max_bl
 }
 
 template <typename T, int VEC>
-static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32_t bins,
+static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins,
                        const float* range, uint64_t* counts_out, hipStream_t st)
 {
     Scratch& s = ctx->s;
@@ -444,7 +452,7 @@ static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32
         // one unrolled round of four 16-byte loads per thread while the sample is small
         const uint32_t gx = grid_for(g.n_items, kMMBlock, 4, min(kMaxReduceBlocks, ctx->num_cu * 4));
         EDGC_LAUNCH(ctx, st, KID_MINMAX, sample_bytes, 0.0,
-                    k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(grad, g, s.mm_part, s.done_counter, rp, fbins,
+                    k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(g, s.mm_part, s.done_counter, rp, fbins,
                                                               counts, bins, s.nonfinite));
     }
 
@@ -466,7 +474,7 @@ static int run_entropy(edgc_ctx* ctx, const T* grad, const SampleGeom& g, uint32
     const int per_thread = small ? 4 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
     const uint32_t gx = grid_for(g.n_items, kHistBlock, per_thread, ctx->num_cu * 2);
     EDGC_LAUNCH(ctx, st, KID_HIST, sample_bytes * ny, 0.0,
-                k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(grad, g, rp, bins, bins_local, rep_shift,
+                k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(g, rp, bins, bins_local, rep_shift,
                                                                       counts, s.nonfinite, s.done_counter + 1, res));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
@@ -486,20 +494,19 @@ int prepare_entropy_kernels(edgc_ctx* ctx)
     return EDGC_OK;
 }
 
-int launch_entropy(edgc_ctx* ctx, const void* grad, edgc_dtype dt, const SampleGeom& g,
-                   uint32_t bins, const float* range, edgc_entropy_result* out,
-                   uint64_t* counts_out, hipStream_t st)
+int launch_entropy(edgc_ctx* ctx, const EntGroup& g, edgc_dtype dt, uint32_t bins,
+                   const float* range, edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st)
 {
+    // the kernels are compiled for one vector width: every buffer of the group was given the same
+    bool vec = true;
+    for (uint32_t i = 0; i < g.count; ++i) vec = vec && g.geom[i].vec > 1;
     int rc;
-    if (dt == EDGC_F32) {
-        const float* p = static_cast<const float*>(grad);
-        rc = (g.vec == 4) ? run_entropy<float, 4>(ctx, p, g, bins, range, counts_out, st)
-                          : run_entropy<float, 1>(ctx, p, g, bins, range, counts_out, st);
-    } else {
-        const uint16_t* p = static_cast<const uint16_t*>(grad);
-        rc = (g.vec == 8) ? run_entropy<uint16_t, 8>(ctx, p, g, bins, range, counts_out, st)
-                          : run_entropy<uint16_t, 1>(ctx, p, g, bins, range, counts_out, st);
-    }
+    if (dt == EDGC_F32)
+        rc = vec ? run_entropy<float, 4>(ctx, g, bins, range, counts_out, st)
+                 : run_entropy<float, 1>(ctx, g, bins, range, counts_out, st);
+    else
+        rc = vec ? run_entropy<uint16_t, 8>(ctx, g, bins, range, counts_out, st)
+                 : run_entropy<uint16_t, 1>(ctx, g, bins, range, counts_out, st);
     if (rc != EDGC_OK) return rc;
     EDGC_HIP_TRY(ctx, hipMemcpyAsync(out, ctx->s.result_dev, sizeof(edgc_entropy_result),
                                      hipMemcpyDeviceToHost, st));

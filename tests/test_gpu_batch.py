@@ -165,3 +165,48 @@ def test_batch_rejects_bad_descriptors_before_launching():
         st.ctx.compress_batch([st.t[0], edgc.Tensor(st.t[1].grad.bfloat16(), st.t[1].grad_out.bfloat16())], 8)
     st.ctx.compress_batch([], 8)                                   # empty batch: nothing to do
     st.ctx.decompress_batch([], 8)
+
+
+# ---------------------------------------------------------------------------
+# stage-level entropy over separate buffers: the union of the buffers' own samples
+# ---------------------------------------------------------------------------
+def _oracle_union_entropy(bufs, stride, chunk, seed, step, bins, value_range=None):
+    """Each buffer's sample by the oracle's sampler, gathered and concatenated; the oracle's
+    estimator then runs over that vector with every element sampled."""
+    parts = []
+    for b in bufs:
+        idx = orc.sample_indices(b.size, stride, chunk, seed, step)
+        parts.append(b.reshape(-1)[idx])
+    cat = np.concatenate(parts)
+    return orc.entropy(cat, 1, 1, 0, 0, bins, value_range), cat.size
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stride,chunk,bins", [(100, 64, 1024), (10, 1, 256), (1, 64, 4096), (7, 48, 65536)])
+def test_stage_entropy_over_separate_buffers(dtype, stride, chunk, bins):
+    sizes = [1 << 20, 300_007, 64, 1, 2_000_003, 4096]
+    bufs = [gen.laplace_mixture(n, 40 + i, dtype=dtype, scale=1e-3 * (1 + i)) for i, n in enumerate(sizes)]
+    dev = [to_dev(b) for b in bufs]
+    c = edgc.Context(0, max_bins=65536, max_rank=4, max_rows=64, max_cols=64)
+    counts = torch.zeros(bins, dtype=torch.int64, device="cuda")
+    for step in (0, 5):
+        got = c.entropy_estimate(dev, stride, chunk, 9, step, bins, counts_out=counts)
+        want, n_s = _oracle_union_entropy(bufs, stride, chunk, 9, step, bins)
+        assert got.n_sampled == n_s == want.n_sampled
+        assert (got.lo, got.hi) == (want.lo, want.hi)
+        assert np.array_equal(counts.cpu().numpy().astype(np.uint64), want.counts), "bin counts are bit-exact"
+        assert abs(got.H_bits - want.H_bits) <= 1e-5 and abs(got.h_diff_nats - want.h_diff_nats) <= 1e-5
+    # a caller's range, and one buffer that is not 16-byte aligned (the group falls back to scalar loads)
+    odd = [dev[0][1:], dev[1]]
+    odd_host = [bufs[0][1:], bufs[1]]
+    got = c.entropy_estimate(odd, stride, chunk, 9, 3, bins, value_range=(-2e-3, 2e-3))
+    want, n_s = _oracle_union_entropy(odd_host, stride, chunk, 9, 3, bins, (-2e-3, 2e-3))
+    assert got.n_sampled == n_s and abs(got.H_bits - want.H_bits) <= 1e-5
+    # one buffer through the batch call is the single call
+    a = c.entropy_estimate([dev[0]], stride, chunk, 9, 1, bins)
+    b = c.entropy_estimate(dev[0], stride, chunk, 9, 1, bins)
+    assert a == b
+    with pytest.raises(edgc.EdgcError):
+        c.entropy_estimate([dev[0]] * 33, stride, chunk, 9, 1, bins)
+    with pytest.raises(edgc.EdgcError):
+        c.entropy_estimate([], stride, chunk, 9, 1, bins)
