@@ -2,11 +2,17 @@
 """Benchmark of the EDGC hot path on one MI355X.
 
 One "step" = one pass of the whole hot path over one batch of synthetic layer
-gradients: for every 2-D gradient of the workload, the down-sampled entropy
-estimate (sample, range, histogram, entropy), the host rank rule on the
-step's entropies, and rank-r compress + decompress with the error-feedback
-residual carried from the previous step.  Inputs are resident in HBM before
-the timed region starts.  Prints ONE JSON line.
+gradients: the down-sampled entropy estimate (sample, range, histogram,
+entropy) of every 2-D gradient of the workload, the host rank rule on the
+step's entropies, and rank-r compress + decompress of every gradient with the
+error-feedback residual carried from the previous step.  Inputs are resident
+in HBM before the timed region starts.  Prints ONE JSON line.
+
+Default layout: the layers are split into two groups; each group goes through
+the batched entry points (one launch sequence per group, on a stream of its
+own, so that one group's small kernels run beside the other's streaming
+passes) and gets one stage-level entropy estimate over its gradient buffers on
+a third stream.  `--batch 0` runs one call chain and one estimate per layer.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
@@ -26,11 +32,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this command (see profiles/); None until such a run has been recorded.
+# runs of this command (see profiles/), keyed by (workload, kernel, batch groups); None for a
+# layout that has no such run recorded.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/k_pass_p_cfg2_traffic.md: (2 x FETCH_SIZE + WRITE_SIZE) KiB per launch, the factors
     # coming from the same counters on a plain 1 GiB device copy (FETCH_SIZE reads half the bytes)
-    ("cfg2_gpt_h2048_r16", "k_pass_p"): int((2 * 4.84e4 + 6.25e4) * 1024),
+    ("cfg2_gpt_h2048_r16", "k_pass_p", 2): int((2 * 9.764e4 + 1.125e5) * 1024),
 }
 
 
@@ -49,13 +56,19 @@ def parse_args():
                     help="replay the compress/decompress launches from a captured HIP graph instead of issuing "
                          "them eagerly (measured slower here: the graph's branches overlap less than the streams)")
     ap.add_argument("--no-graph", action="store_true", help="kept for compatibility: eager launches are the default")
-    ap.add_argument("--batch", type=int, default=0,
-                    help="N > 0: compress/decompress through the batched entry points, the layers split into N "
-                         "groups (balanced by size), each group one launch sequence on its own stream")
+    ap.add_argument("--batch", type=int, default=2,
+                    help="N > 0 (default 2): compress/decompress through the batched entry points, the layers split "
+                         "into N groups (balanced by size), each group one launch sequence on its own stream and one "
+                         "stage-level entropy estimate; 0: one call chain per layer")
     ap.add_argument("--ent-streams", type=int, default=0,
-                    help="streams the entropy estimates are spread over; 0 = one per compress stream")
+                    help="streams the entropy estimates are spread over; 0 = one in batched mode (compress streams "
+                         "+ entropy stream stay within the 4 hardware queues), else one per compress stream")
+    ap.add_argument("--serial", action="store_true",
+                    help="issue everything on ONE stream, also in the timed region (what the per-kernel second pass "
+                         "always does): the run to put under rocprofv3 --kernel-trace --stats, every kernel alone on the GPU")
     ap.add_argument("--streams", type=int, default=0,
-                    help="HIP streams (one library context each) the layers are spread over; 0 = one per layer")
+                    help="HIP streams (one library context each) the layers or groups are spread over; "
+                         "0 = one per group in batched mode, else one per layer")
     return ap.parse_args()
 
 
@@ -95,15 +108,18 @@ def main() -> int:
     mats = gen.workload_matrices(args.workload)
     max_m = max(s.m for s, _ in mats)
     max_n = max(s.n for s, _ in mats)
-    n_streams = args.streams or len(mats)
+    n_streams = args.streams or (min(args.batch, len(mats)) if args.batch > 0 else len(mats))
     # one context (scratch) per stream: independent layers overlap their small kernels
     ctxs = [edgc.Context(0, max_bins=w["bins"], max_rank=max(r, 4), max_rows=max_m, max_cols=max_n)
             for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     # the entropy estimate only reads the gradient and uses scratch of its own, so it runs on a
     # stream of its own beside the layer's compress/decompress chain
-    n_ent = args.ent_streams or n_streams
-    ent_streams = [torch.cuda.Stream() for _ in range(n_ent)] if (n_streams > 1 or args.ent_streams) else streams
+    n_ent = args.ent_streams or (1 if args.batch > 0 else n_streams)
+    ent_streams = [torch.cuda.Stream() for _ in range(n_ent)] if (n_streams > 1 or args.ent_streams or args.batch > 0) else streams
+    if args.serial:
+        streams = [streams[0]] * n_streams
+        ent_streams = [streams[0]] * n_ent
     n_ent = len(ent_streams)
     ctx = ctxs[0]
 
@@ -144,8 +160,12 @@ def main() -> int:
             gctx.reserve_batch([(layers[i]["spec"].m, layers[i]["spec"].n) for i in idx])
             tensors = [edgc.Tensor(layers[i]["G"], layers[i]["out"], layers[i]["E"], layers[i]["Q"],
                                    layers[i]["P"], True) for i in idx]
-            groups.append(dict(ctx=gctx, tensors=tensors, stream=streams[k % n_streams]))
-        ctxs_all = ctxs + [g["ctx"] for g in groups]
+            groups.append(dict(
+                ctx=gctx, tensors=tensors, stream=streams[k % n_streams],
+                ectx=edgc.Context(0, max_bins=w["bins"], max_rank=4, max_rows=64, max_cols=64),
+                estream=ent_streams[k % n_ent], flats=[layers[i]["G"].view(-1) for i in idx],
+                ent=[torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(NBUF)]))
+        ctxs_all = ctxs + [g["ctx"] for g in groups] + [g["ectx"] for g in groups]
     else:
         ctxs_all = ctxs
 
@@ -167,8 +187,8 @@ def main() -> int:
         if t > 1:
             for ev in step_events[(t - 2) % NBUF]:
                 ev.synchronize()
-            H = [edgc.EntropyResult.from_buffer(L["ent"][(t - 2) % NBUF].numpy().tobytes()).h_diff_nats
-                 for L in layers]
+            H = [edgc.EntropyResult.from_buffer(x["ent"][(t - 2) % NBUF].numpy().tobytes()).h_diff_nats
+                 for x in (groups or layers)]
             decisions.append(edgc.select_rank(state, H, 1, prm))
 
     def compress_all():
@@ -189,9 +209,15 @@ def main() -> int:
         t = counter["step"]
         rank_rule(t)
         if graph["g"] is None:
-            for L in layers:
-                L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t, w["bins"],
-                                                L["ent"][t % NBUF], stream=L["estream"])
+            if groups:
+                # one stage-level estimate over the group's separate gradient buffers
+                for g in groups:
+                    g["ectx"].entropy_estimate_async(g["flats"], w["stride"], w["chunk"], w["seed"], t,
+                                                     w["bins"], g["ent"][t % NBUF], stream=g["estream"])
+            else:
+                for L in layers:
+                    L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
+                                                    w["bins"], L["ent"][t % NBUF], stream=L["estream"])
             compress_all()
             for si, st in enumerate(streams):
                 step_events[t % NBUF][si].record(st)
@@ -265,7 +291,7 @@ def main() -> int:
     for L in layers:
         L["stream"] = L["estream"] = streams[0]
     for g in groups:
-        g["stream"] = streams[0]
+        g["stream"] = g["estream"] = streams[0]
     ent_streams = [streams[0]] * n_ent
     for c in ctxs_all:
         c.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)
@@ -289,7 +315,7 @@ def main() -> int:
     achieved = ds["bytes"] / (ds["total_ms"] * 1e-3) / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
+                    traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, dom, len(groups))),
                     avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
                     algorithmic_bytes_per_launch=round(ds["bytes"] / ds["launches"]),
                     timing="HIP events around every launch (minus %.2f us, what an empty event pair reads); "
@@ -327,7 +353,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": ["%dx%d" % (s.m, s.n) for s, _ in mats],
                    "rank": r, "stride": w["stride"], "chunk": w["chunk"], "bins": w["bins"],
-                   "streams": n_streams, "hip_graph": graphed, "batch_groups": len(groups),
+                   "streams": 1 if args.serial else n_streams, "entropy_streams": 0 if args.serial else n_ent,
+                   "hip_graph": graphed, "batch_groups": len(groups),
                    "gradient_bytes_per_step": grad_bytes},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "mfma": mfma,
         "last_rank_decision": decisions[-1].rank if decisions else None,
