@@ -21,7 +21,10 @@ def _widen(a):
 class Stage:
     """Host and device state of a list of gradient tensors that share one rank."""
 
-    def __init__(self, shapes, r, dtype, seed=0, ragged_ld=False):
+    def __init__(self, shapes, r, dtype, seed=0, ragged_ld=False, mats=None):
+        """``mats``: ready-made 2-D gradients (host arrays) instead of generated ones."""
+        if mats is not None:
+            shapes = [g.shape for g in mats]
         self.shapes, self.r, self.dtype = shapes, r, dtype
         self.ctx = edgc.Context(0, max_rank=128, max_rows=64, max_cols=64)    # own scratch unused here
         self.ctx.reserve_batch([s if len(s) == 2 else (1, s[0]) for s in shapes])
@@ -36,7 +39,8 @@ class Stage:
                 self.t.append(edgc.Tensor(to_dev(g), torch.zeros(s[0], dtype=tdt, device="cuda")))
                 continue
             m, n = s
-            g = gen.lowrank_plus_noise(m, n, min(m, n, 48), 0.9, 1e-4, seed + i, dtype=dtype)
+            g = mats[i] if mats is not None else \
+                gen.lowrank_plus_noise(m, n, min(m, n, 48), 0.9, 1e-4, seed + i, dtype=dtype)
             self.G.append(g)
             if edgc.tensor_bypassed(m, n, r):
                 self.Q.append(None); self.E.append(None)
@@ -101,6 +105,26 @@ def test_mixed_stage_matches_oracle_over_three_steps(dtype, r):
     for _ in range(3):                                            # residual carried from step to step
         st.step_device()
         st.step_oracle_and_compare()
+
+
+def test_benchmark_workload_full_size_in_the_bench_layout():
+    """The benchmark's matrices at full size, grouped as bench.py groups them (two groups balanced by
+    size, largest first into the lighter one), two steps so that the second carries a residual."""
+    name = "cfg2_gpt_h2048_r16"
+    w = gen.WORKLOADS[name]
+    mats = [g for _, g in gen.workload_matrices(name)]
+    order = sorted(range(len(mats)), key=lambda i: -mats[i].size)
+    members, load = [[], []], [0, 0]
+    for i in order:
+        k = load.index(min(load))
+        members[k].append(i)
+        load[k] += mats[i].size
+    assert sorted(members[0] + members[1]) == list(range(len(mats)))
+    for idx in members:
+        st = Stage(None, w["rank"], w["dtype"], seed=w["seed"], mats=[mats[i] for i in sorted(idx)])
+        for _ in range(2):
+            st.step_device()
+            st.step_oracle_and_compare()
 
 
 def test_ragged_leading_dimension_and_rank_48():
