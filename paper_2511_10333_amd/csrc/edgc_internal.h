@@ -66,6 +66,8 @@ struct TensorArgs {
 struct Group {
     uint32_t count;
     uint32_t r;             // rank, the same for every tensor of a group
+    uint32_t stream;        // Q-pass only.  1: D is too large to still be cached when the decompress
+                            //    reads it again, so the Q-pass reads it with non-temporal loads
     TensorArgs t[kMaxGroup];
 };
 
@@ -117,6 +119,7 @@ struct edgc_ctx {
     // launch-shape overrides for sweeps (blocks per CU aimed at by the P-pass, Q-pass and
     // decompress); 0 = the built-in choice
     uint32_t tune_p = 0, tune_q = 0, tune_d = 0;
+    int tune_stream = -1;   // -1: by size; 0 / 1: force cached / non-temporal reads of D in the Q-pass
     edgc::Scratch s;
     std::vector<edgc::BatchSlot> batch;
     edgc::Profiler prof;
