@@ -1257,8 +1257,8 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
 {
     constexpr uint32_t BK = 64, RP = RT * 32;
     using GT = typename GradElem<NP>::type;
-    // measured: bf16 gradients stream best with ~2 blocks per CU, fp32 with ~4
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : (NP == 1 ? 2u : 4u));
+    // measured: ~4 blocks per CU stream best (3 are resident; more splits only add partials)
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : 4u);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
     bool vec = true;
@@ -1493,7 +1493,7 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
     constexpr uint32_t RP = RT * 32;
     constexpr size_t lds = static_cast<size_t>(64) * (NP * RP * 2 + 16);
     constexpr uint32_t esz = (NP == 1) ? 2 : 4;          // one plane <=> bf16 gradient and output
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_d ? ctx->tune_d : (NP == 1 ? 2u : 4u));
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_d ? ctx->tune_d : 4u);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
     bool vec = true;
