@@ -234,3 +234,36 @@ def test_stage_entropy_over_separate_buffers(dtype, stride, chunk, bins):
         c.entropy_estimate([dev[0]] * 33, stride, chunk, 9, 1, bins)
     with pytest.raises(edgc.EdgcError):
         c.entropy_estimate([], stride, chunk, 9, 1, bins)
+
+
+# ---------------------------------------------------------------------------
+# the batched calls under HIP graph capture: no allocation, no synchronisation, no memset
+# node inside them, so a captured step replays like the eager one
+# ---------------------------------------------------------------------------
+def test_batched_step_replays_from_a_hip_graph():
+    shapes, r = [(384, 512), (256, 640), (100,)], 8
+    eager = Stage(shapes, r, "f32", seed=31)
+    graphed = Stage(shapes, r, "f32", seed=31)
+    for st in (eager, graphed):                       # first step eagerly: it starts from a zero residual
+        st.step_device()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    keep = [(t.residual.clone(), t.Q.clone()) if t.residual is not None else None for t in graphed.t]
+    with torch.cuda.graph(g, stream=side, capture_error_mode="thread_local"):
+        graphed.ctx.compress_batch(graphed.t, r, stream=side)
+        graphed.ctx.decompress_batch(graphed.t, r, stream=side)
+    torch.cuda.synchronize()
+    for t, k in zip(graphed.t, keep):                 # capture runs nothing, but make the state explicit
+        if k is not None:
+            t.residual.copy_(k[0]); t.Q.copy_(k[1])
+    for step in range(3):
+        eager.step_device()
+        g.replay()
+        # eager work and a synchronisation between replays
+        torch.cuda.synchronize()
+        _ = (eager.t[0].grad_out * 2).sum().item()
+        for a, b in zip(eager.t, graphed.t):
+            assert torch.equal(a.grad_out, b.grad_out), step
+            if a.residual is not None:
+                assert torch.equal(a.residual, b.residual) and torch.equal(a.Q, b.Q) and torch.equal(a.P, b.P), step
