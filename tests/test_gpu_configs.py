@@ -165,3 +165,34 @@ def test_dynamic_rank_run_free_running():
     assert ranks_seen[0] == 0                       # first window only fixes the reference
     assert len(set(r for r in ranks_seen if r)) >= 3, ranks_seen     # the rank really changed
     assert ranks_seen == sorted(ranks_seen)         # entropy rises with the flattening spectrum
+
+
+# ---------------------------------------------------------------------------
+# layers of the dynamic-rate configuration at their real size (hidden 4096: attention projection
+# and the two MLP matrices), across its rank range: step 0 from a zero residual, then one step
+# from the ORACLE's residual and warm-started Q (teacher-forced), as the 200-step run at
+# reduced size does at every check point
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n,r", [(4096, 4096, 4), (4096, 4096, 64), (4096, 16384, 64), (16384, 4096, 32)])
+def test_hidden4096_layer_full_size_teacher_forced(m, n, r):
+    c = ctx()
+    factors = gen.orthonormal_factors(m, n, 256, 77)
+    Q0 = np.zeros((n, 64), dtype=np.float32)
+    orc.init_q(Q0, 0, 64, 5)
+    E_prev, Q_prev = None, np.ascontiguousarray(Q0[:, :r])
+    for t, decay in enumerate((0.90, 0.99)):
+        G = gen.lowrank_plus_noise(m, n, 256, decay, 1e-4, 7, noise_seed=900 + t, factors=factors)
+        Po, Qn, Do = orc.compress(G, E_prev, Q_prev, r)
+        out_o, E_o = orc.decompress(Po, Qn, Do, orc.F32)
+        Gd = to_dev(G)
+        Ed = torch.empty((m, n), device="cuda") if E_prev is None else to_dev(E_prev)
+        Qd = torch.zeros((n, 64), device="cuda"); Qd[:, :r] = to_dev(Q_prev)
+        Pd = torch.empty((m, 64), device="cuda"); out = torch.empty((m, n), device="cuda")
+        c.compress(Gd, Ed, E_prev is None, Qd, Pd, r)
+        assert np.array_equal(to_host(Ed), Do)
+        c.decompress(Pd, Qd, r, Ed, out)
+        torch.cuda.synchronize()
+        assert rel_fro(to_host(Pd)[:, :r], Po) <= 1e-3 and rel_fro(to_host(Qd)[:, :r], Qn) <= 1e-3, (t, r)
+        assert rel_fro(to_host(out), out_o) <= 1e-3, (t, r)
+        assert np.linalg.norm(to_host(Ed).astype(np.float64) - E_o) <= 1e-3 * np.linalg.norm(Do.astype(np.float64))
+        E_prev, Q_prev = E_o, Qn
