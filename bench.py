@@ -11,8 +11,8 @@ in HBM before the timed region starts.  Prints ONE JSON line.
 Default layout: the layers are split into two groups; each group goes through
 the batched entry points (one launch sequence per group, on a stream of its
 own, so that one group's small kernels run beside the other's streaming
-passes) and gets one stage-level entropy estimate over its gradient buffers on
-a third stream.  `--batch 0` runs one call chain and one estimate per layer.
+passes); one stage-level entropy estimate over all the gradient buffers runs
+on a third stream.  `--batch 0` runs one call chain and one estimate per layer.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
@@ -160,12 +160,13 @@ def main() -> int:
             gctx.reserve_batch([(layers[i]["spec"].m, layers[i]["spec"].n) for i in idx])
             tensors = [edgc.Tensor(layers[i]["G"], layers[i]["out"], layers[i]["E"], layers[i]["Q"],
                                    layers[i]["P"], True) for i in idx]
-            groups.append(dict(
-                ctx=gctx, tensors=tensors, stream=streams[k % n_streams],
-                ectx=edgc.Context(0, max_bins=w["bins"], max_rank=4, max_rows=64, max_cols=64),
-                estream=ent_streams[k % n_ent], flats=[layers[i]["G"].view(-1) for i in idx],
-                ent=[torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(NBUF)]))
-        ctxs_all = ctxs + [g["ctx"] for g in groups] + [g["ectx"] for g in groups]
+            groups.append(dict(ctx=gctx, tensors=tensors, stream=streams[k % n_streams]))
+        # ONE stage-level entropy estimate per step over all gradient buffers of the workload
+        # (the paper's rank is per stage), on a stream of its own
+        stage = dict(ectx=edgc.Context(0, max_bins=w["bins"], max_rank=4, max_rows=64, max_cols=64),
+                     estream=ent_streams[0], flats=[L["G"].view(-1) for L in layers],
+                     ent=[torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(NBUF)])
+        ctxs_all = ctxs + [g["ctx"] for g in groups] + [stage["ectx"]]
     else:
         ctxs_all = ctxs
 
@@ -188,7 +189,7 @@ def main() -> int:
             for ev in step_events[(t - 2) % NBUF]:
                 ev.synchronize()
             H = [edgc.EntropyResult.from_buffer(x["ent"][(t - 2) % NBUF].numpy().tobytes()).h_diff_nats
-                 for x in (groups or layers)]
+                 for x in ([stage] if groups else layers)]
             decisions.append(edgc.select_rank(state, H, 1, prm))
 
     def compress_all():
@@ -210,10 +211,8 @@ def main() -> int:
         rank_rule(t)
         if graph["g"] is None:
             if groups:
-                # one stage-level estimate over the group's separate gradient buffers
-                for g in groups:
-                    g["ectx"].entropy_estimate_async(g["flats"], w["stride"], w["chunk"], w["seed"], t,
-                                                     w["bins"], g["ent"][t % NBUF], stream=g["estream"])
+                stage["ectx"].entropy_estimate_async(stage["flats"], w["stride"], w["chunk"], w["seed"], t,
+                                                     w["bins"], stage["ent"][t % NBUF], stream=stage["estream"])
             else:
                 for L in layers:
                     L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
@@ -291,7 +290,9 @@ def main() -> int:
     for L in layers:
         L["stream"] = L["estream"] = streams[0]
     for g in groups:
-        g["stream"] = g["estream"] = streams[0]
+        g["stream"] = streams[0]
+    if groups:
+        stage["estream"] = streams[0]
     ent_streams = [streams[0]] * n_ent
     for c in ctxs_all:
         c.profile_begin(max_launches=args.steps * len(layers) * 16 + 64)

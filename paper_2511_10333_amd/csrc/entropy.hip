@@ -368,6 +368,7 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
             r.status = EDGC_ENONFINITE;
         }
         *res = r;
+        __threadfence_system();       // `res` may be the caller's pinned host memory
         *done = 0u;
     }
 }
@@ -434,13 +435,12 @@ static uint32_t grid_for(uint64_t n_items, int block, int per_thread, int max_bl
 }
 
 template <typename T, int VEC>
-static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins,
-                       const float* range, uint64_t* counts_out, hipStream_t st)
+static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins, const float* range,
+                       uint64_t* counts_out, edgc_entropy_result* res, hipStream_t st)
 {
     Scratch& s = ctx->s;
     auto* counts = counts_out ? reinterpret_cast<unsigned long long*>(counts_out) : s.counts;
     auto* rp = static_cast<RangeParams*>(s.range);
-    auto* res = static_cast<edgc_entropy_result*>(s.result_dev);
     const float fbins = static_cast<float>(bins);
 
     const double sample_bytes = static_cast<double>(g.n_sampled) * sizeof(T);
@@ -449,8 +449,10 @@ static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins,
                     k_set_range<<<(bins + 255) / 256, 256, 0, st>>>(rp, range[0], range[1], fbins, counts,
                                                                      bins, s.nonfinite));
     } else {
-        // one unrolled round of four 16-byte loads per thread while the sample is small
-        const uint32_t gx = grid_for(g.n_items, kMMBlock, 4, min(kMaxReduceBlocks, ctx->num_cu * 4));
+        // few blocks of four rounds of four 16-byte loads: the estimate runs beside the compressor's
+        // streaming passes, and every block of it that takes a CU slot delays those (measured on the
+        // bench workload: 16 items per thread cost 12 us of step time less than 4)
+        const uint32_t gx = grid_for(g.n_items, kMMBlock, 16, min(kMaxReduceBlocks, ctx->num_cu * 4));
         EDGC_LAUNCH(ctx, st, KID_MINMAX, sample_bytes, 0.0,
                     k_minmax<T, VEC><<<gx, kMMBlock, 0, st>>>(g, s.mm_part, s.done_counter, rp, fbins,
                                                               counts, bins, s.nonfinite));
@@ -471,7 +473,7 @@ static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins,
     const uint32_t ny = (bins + bins_local - 1) / bins_local;
     const size_t lds = static_cast<size_t>(bins_local << rep_shift) * sizeof(uint32_t);
     // enough items per block that zeroing and flushing the LDS histogram stays small
-    const int per_thread = small ? 4 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
+    const int per_thread = small ? 8 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
     const uint32_t gx = grid_for(g.n_items, kHistBlock, per_thread, ctx->num_cu * 2);
     EDGC_LAUNCH(ctx, st, KID_HIST, sample_bytes * ny, 0.0,
                 k_hist<T, VEC><<<dim3(gx, ny), kHistBlock, lds, st>>>(g, rp, bins, bins_local, rep_shift,
@@ -500,14 +502,27 @@ int launch_entropy(edgc_ctx* ctx, const EntGroup& g, edgc_dtype dt, uint32_t bin
     // the kernels are compiled for one vector width: every buffer of the group was given the same
     bool vec = true;
     for (uint32_t i = 0; i < g.count; ++i) vec = vec && g.geom[i].vec > 1;
+    // Pinned (device-accessible) host memory takes the result straight from the kernel; any
+    // other host memory gets it through a copy on the stream.
+    auto* res = static_cast<edgc_entropy_result*>(ctx->s.result_dev);
+    bool direct = false;
+    hipPointerAttribute_t attr;
+    if (reinterpret_cast<uintptr_t>(out) % alignof(edgc_entropy_result) == 0 &&
+        hipPointerGetAttributes(&attr, out) == hipSuccess && attr.type == hipMemoryTypeHost &&
+        attr.devicePointer != nullptr) {
+        res = static_cast<edgc_entropy_result*>(attr.devicePointer);
+        direct = true;
+    } else {
+        (void)hipGetLastError();      // pageable memory is reported as an error: not one here
+    }
     int rc;
     if (dt == EDGC_F32)
-        rc = vec ? run_entropy<float, 4>(ctx, g, bins, range, counts_out, st)
-                 : run_entropy<float, 1>(ctx, g, bins, range, counts_out, st);
+        rc = vec ? run_entropy<float, 4>(ctx, g, bins, range, counts_out, res, st)
+                 : run_entropy<float, 1>(ctx, g, bins, range, counts_out, res, st);
     else
-        rc = vec ? run_entropy<uint16_t, 8>(ctx, g, bins, range, counts_out, st)
-                 : run_entropy<uint16_t, 1>(ctx, g, bins, range, counts_out, st);
-    if (rc != EDGC_OK) return rc;
+        rc = vec ? run_entropy<uint16_t, 8>(ctx, g, bins, range, counts_out, res, st)
+                 : run_entropy<uint16_t, 1>(ctx, g, bins, range, counts_out, res, st);
+    if (rc != EDGC_OK || direct) return rc;
     EDGC_HIP_TRY(ctx, hipMemcpyAsync(out, ctx->s.result_dev, sizeof(edgc_entropy_result),
                                      hipMemcpyDeviceToHost, st));
     return EDGC_OK;

@@ -145,3 +145,22 @@ def test_repeated_calls_are_deterministic():
     for _ in range(3):
         b = ctx().entropy_estimate(x, 10, 64, 5, 5, 4096)
         assert (a.H_bits, a.h_diff_nats, a.lo, a.hi) == (b.H_bits, b.h_diff_nats, b.lo, b.hi)
+
+
+def test_result_reaches_pageable_and_pinned_host_memory_alike():
+    """Pinned host memory takes the result straight from the kernel, pageable memory through a
+    copy on the stream: the caller sees the same bytes."""
+    x = gen.laplace_mixture(1 << 20, 12)
+    d = to_dev(x)
+    c = ctx()
+    pinned = torch.zeros(edgc.binding.ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True)
+    pageable = torch.zeros(edgc.binding.ENTROPY_RESULT_BYTES, dtype=torch.uint8)
+    odd = torch.zeros(edgc.binding.ENTROPY_RESULT_BYTES + 8, dtype=torch.uint8, pin_memory=True)[4:-4]   # misaligned view
+    for out in (pinned, pageable, odd):
+        c.entropy_estimate_async(d, 100, 64, 3, 7, 1024, out)
+    torch.cuda.synchronize()
+    a = edgc.EntropyResult.from_buffer(pinned.numpy().tobytes())
+    assert a == edgc.EntropyResult.from_buffer(pageable.numpy().tobytes())
+    assert a == edgc.EntropyResult.from_buffer(odd.numpy().tobytes())
+    want = orc.entropy(x, 100, 64, 3, 7, 1024)
+    assert a.n_sampled == want.n_sampled and abs(a.H_bits - want.H_bits) <= 1e-5
