@@ -961,21 +961,38 @@ __global__ __launch_bounds__(256) void k_reduce_q(const Group grp, uint32_t RP)
     const float* __restrict__ part = ta.part;
     float* __restrict__ Q = ta.Q;
     const uint32_t S = ta.sq, n = ta.n, r = grp.r, ldq = ta.ldq;
+    // one thread per four adjacent factor columns of one row of Q
+    const uint32_t q4 = RP / 4;
     const uint64_t t = static_cast<uint64_t>(blockIdx.x - ta.first) * 256 + threadIdx.x;
-    if (t >= static_cast<uint64_t>(n) * RP) return;
-    const uint32_t j = static_cast<uint32_t>(t / RP), c = static_cast<uint32_t>(t % RP);
+    if (t >= static_cast<uint64_t>(n) * q4) return;
+    const uint32_t j = static_cast<uint32_t>(t / q4), c = static_cast<uint32_t>(t % q4) * 4;
     if (c >= r) return;
     const size_t stride = static_cast<size_t>(n) * RP;
     const float* p = part + static_cast<size_t>(j) * RP + c;
-    float v = 0.0f;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     uint32_t s = 0;
     for (; s + 4 <= S; s += 4) {
-        const float x0 = p[(s + 0) * stride], x1 = p[(s + 1) * stride];
-        const float x2 = p[(s + 2) * stride], x3 = p[(s + 3) * stride];
-        v += x0; v += x1; v += x2; v += x3;
+        const float4 x0 = *reinterpret_cast<const float4*>(p + (s + 0) * stride);
+        const float4 x1 = *reinterpret_cast<const float4*>(p + (s + 1) * stride);
+        const float4 x2 = *reinterpret_cast<const float4*>(p + (s + 2) * stride);
+        const float4 x3 = *reinterpret_cast<const float4*>(p + (s + 3) * stride);
+        v.x += x0.x; v.y += x0.y; v.z += x0.z; v.w += x0.w;
+        v.x += x1.x; v.y += x1.y; v.z += x1.z; v.w += x1.w;
+        v.x += x2.x; v.y += x2.y; v.z += x2.z; v.w += x2.w;
+        v.x += x3.x; v.y += x3.y; v.z += x3.z; v.w += x3.w;
     }
-    for (; s < S; ++s) v += p[s * stride];
-    Q[static_cast<size_t>(j) * ldq + c] = v;
+    for (; s < S; ++s) {
+        const float4 x0 = *reinterpret_cast<const float4*>(p + s * stride);
+        v.x += x0.x; v.y += x0.y; v.z += x0.z; v.w += x0.w;
+    }
+    float* dst = Q + static_cast<size_t>(j) * ldq + c;
+    if (c + 4 <= r) {
+        *reinterpret_cast<float4*>(dst) = v;              // ldq is a multiple of 4, Q 16-byte aligned
+    } else {
+        dst[0] = v.x;
+        if (c + 1 < r) dst[1] = v.y;
+        if (c + 2 < r) dst[2] = v.z;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1441,7 +1458,7 @@ static int run_pass_q(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStre
     for (uint32_t i = 0; i < g.count; ++i) {
         TensorArgs& t = g.t[i];
         t.first = blocks;
-        blocks += cdiv(static_cast<uint64_t>(t.n) * RP, 256);
+        blocks += cdiv(static_cast<uint64_t>(t.n) * (RP / 4), 256);
         bytes += 4.0 * t.n * g.r * (t.sq + 1);
     }
     EDGC_LAUNCH(ctx, st, KID_REDUCE_Q, bytes, 0.0, k_reduce_q<<<blocks, 256, 0, st>>>(g, RP));
