@@ -334,8 +334,14 @@ def main() -> int:
             q0s.append(Q0)
         reps, tc0 = 0, time.perf_counter()
         while True:                      # whole steps until about 10 s of CPU work (at most 200 steps)
+            if groups:
+                # the stage-level estimate: every buffer's own sample, gathered, one histogram
+                parts = [g.reshape(-1)[orc.sample_indices(g.size, w["stride"], w["chunk"], w["seed"], reps)]
+                         for _, g in mats]
+                orc.entropy(np.concatenate(parts), 1, 1, 0, 0, w["bins"])
             for li, (spec, g) in enumerate(mats):
-                orc.entropy(g.reshape(-1), w["stride"], w["chunk"], w["seed"], reps, w["bins"])
+                if not groups:
+                    orc.entropy(g.reshape(-1), w["stride"], w["chunk"], w["seed"], reps, w["bins"])
                 P, Q1, D = orc.compress(g, None, q0s[li], r)
                 orc.decompress(P, Q1, D, orc.BF16 if bf16 else orc.F32)
             reps += 1
