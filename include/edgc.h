@@ -8,6 +8,11 @@
  *      Theorem 1 / Lemma 1; warm-up Sec. IV-D-2; Algorithm 1, Constraint 2)
  *   3. rank-r low-rank compress / decompress with an error-feedback residual
  *      (Sec. II-B, Sec. III-B, Sec. VII; PowerSGD-style subspace iteration)
+ *   4. rank bounds from measured compress / decompress times, the linear
+ *      communication-time model and stage-aligned ranks (Sec. IV-D-1,
+ *      Sec. IV-D-4, Algorithm 2), iteration sampling rate (Sec. IV-B)
+ *   5. the same entropy estimate and compressor over all gradient tensors of
+ *      a pipeline stage in one launch sequence (batched calls)
  *
  * Conventions
  *   - Every function returns an edgc_status (0 = OK, < 0 = error).  No C++
@@ -15,7 +20,8 @@
  *   - "device" pointers are HIP device memory on the context's GPU, owned by
  *     the caller; "host" pointers are ordinary process memory.  The library
  *     allocates device memory only in edgc_create (scratch) and frees it in
- *     edgc_destroy.  Hot calls never allocate, never free and never
+ *     edgc_destroy (and, for batches, in edgc_reserve_batch).  Hot calls
+ *     never allocate, never free and never
  *     synchronise the stream; they only enqueue work on `hip_stream`
  *     (a hipStream_t passed as void*, NULL = the default stream).
  *   - Matrices are row-major.  A gradient G is m x n with leading dimension
@@ -39,7 +45,7 @@ typedef enum { EDGC_F32 = 0, EDGC_BF16 = 1 } edgc_dtype;
 typedef enum {
     EDGC_OK         =  0,
     EDGC_EINVAL     = -1,   /* bad argument (null / misaligned pointer, size out of range)  */
-    EDGC_ENOMEM     = -2,   /* allocation failed in edgc_create                            */
+    EDGC_ENOMEM     = -2,   /* allocation failed (edgc_create, edgc_reserve_batch)         */
     EDGC_EHIP       = -3,   /* a HIP call failed; see edgc_last_error                      */
     EDGC_ENOTIMPL   = -4,
     EDGC_ENONFINITE = -5    /* empty sample, or no finite value in it                      */
@@ -105,9 +111,10 @@ typedef struct {
 } edgc_entropy_result;
 
 /* grad: device, n_elems of dtype.  range_lo_hi_or_null: host float[2] or NULL.
- * out: host; written by an asynchronous device-to-host copy on `hip_stream`,
- * valid once the stream has been synchronised (pinned memory keeps the call
- * fully asynchronous).  counts_out_or_null: device, `bins` uint64 counters.
+ * out: host, valid once the stream has been synchronised.  Pinned (device-
+ * accessible, 8-byte aligned) memory is written by the kernel itself; any
+ * other host memory by a device-to-host copy on `hip_stream`, which makes the
+ * call wait for the stream.  counts_out_or_null: device, `bins` uint64 counters.
  * Errors: EDGC_EINVAL for null ctx/grad/out, stride == 0, chunk == 0,
  * bins == 0 or > max_bins, lo > hi; EDGC_ENONFINITE when the predicate selects
  * no element (known on the host).  A sample with no finite value is reported
