@@ -250,10 +250,14 @@ def test_batched_step_replays_from_a_hip_graph():
     g = torch.cuda.CUDAGraph()
     torch.cuda.synchronize()
     keep = [(t.residual.clone(), t.Q.clone()) if t.residual is not None else None for t in graphed.t]
+    ent_out = torch.zeros(edgc.binding.ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True)
+    flats = [t.grad.view(-1) for t in graphed.t]
     with torch.cuda.graph(g, stream=side, capture_error_mode="thread_local"):
+        graphed.ctx.entropy_estimate_async(flats, 10, 64, 3, 0, 256, ent_out, stream=side)
         graphed.ctx.compress_batch(graphed.t, r, stream=side)
         graphed.ctx.decompress_batch(graphed.t, r, stream=side)
     torch.cuda.synchronize()
+    ent_want = graphed.ctx.entropy_estimate(flats, 10, 64, 3, 0, 256)
     for t, k in zip(graphed.t, keep):                 # capture runs nothing, but make the state explicit
         if k is not None:
             t.residual.copy_(k[0]); t.Q.copy_(k[1])
@@ -263,6 +267,8 @@ def test_batched_step_replays_from_a_hip_graph():
         # eager work and a synchronisation between replays
         torch.cuda.synchronize()
         _ = (eager.t[0].grad_out * 2).sum().item()
+        assert edgc.EntropyResult.from_buffer(ent_out.numpy().tobytes()) == ent_want, step
+        ent_out.zero_()
         for a, b in zip(eager.t, graphed.t):
             assert torch.equal(a.grad_out, b.grad_out), step
             if a.residual is not None:
