@@ -18,6 +18,10 @@
 // per byte), so the matrix is streamed exactly once per pass with 16-byte
 // accesses and everything else (factors, partials) stays in L2 / LDS.
 //
+// Every kernel works on a list of tensors (Group): its grid is the concatenation
+// of the tensors' block ranges, so all gradients of a pipeline stage go through
+// each pass in ONE launch; a single-tensor call is a list of one.
+//
 // MFMA 32x32x16 operand layout (64 lanes): lane l supplies A[i = l%32][k = 8*(l/32) .. +8]
 // and B[k = 8*(l/32) .. +8][j = l%32]; accumulator register v of lane l holds
 // D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].

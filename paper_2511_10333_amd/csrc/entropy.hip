@@ -11,6 +11,10 @@
 //             block reduces the counters to the Shannon entropy in fp64
 // The chunk-strided sample is read with 16-byte loads whenever chunks are a
 // multiple of the vector width, so a wavefront touches whole cache lines.
+// Both kernels take a list of buffers (EntGroup): the estimate is over the union
+// of the buffers' samples (one entropy for a pipeline stage whose gradients are
+// separate tensors); a single buffer is a list of one.  The result goes straight
+// into the caller's pinned host memory when it is device-accessible.
 #include "edgc_internal.h"
 
 #include <math.h>
