@@ -321,7 +321,12 @@ def main() -> int:
                     algorithmic_bytes_per_launch=round(ds["bytes"] / ds["launches"]),
                     timing="HIP events around every launch (minus %.2f us, what an empty event pair reads); "
                            "second pass of the same K steps, launches serialised on one stream" % event_overhead_us)
-    mfma = {k: dict(tflops=v["tflops"], frac_of_bf16_peak=round(v["tflops"] / BF16_MFMA_PEAK_TFLOPS, 4))
+    # MFMA utilisation of the instruction issued, beside the most an HBM-bound pass could reach:
+    # ceiling = min(1, arithmetic intensity / ridge), ridge = bf16 MFMA peak / HBM peak
+    ridge = BF16_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    mfma = {k: dict(tflops=v["tflops"], frac_of_bf16_peak=round(v["tflops"] / BF16_MFMA_PEAK_TFLOPS, 4),
+                    flop_per_byte=round(stats[k]["flops"] / stats[k]["bytes"], 2),
+                    ceiling=round(min(1.0, stats[k]["flops"] / stats[k]["bytes"] / ridge), 4))
             for k, v in kernels.items() if k in ("k_pass_p", "k_pass_q", "k_decompress") and v["tflops"]}
 
     cpu_baseline = None
