@@ -258,7 +258,15 @@ __global__ __launch_bounds__(256) void k_pass_p(const Group grp)
             float g[4] = {0.f, 0.f, 0.f, 0.f}, e[4] = {0.f, 0.f, 0.f, 0.f};
             if constexpr (FULL) {
                 if (G) ld_stream4(G + static_cast<uint64_t>(row) * ldg + col, g);
-                if (!e_zero) ld_stream4(E + static_cast<uint64_t>(row) * n + col, e);
+                if (!e_zero) {
+                    const float* pe = E + static_cast<uint64_t>(row) * n + col;
+                    if (grp.stream) {
+                        ld_stream4(pe, e);
+                    } else {                                  // the residual may still be cached: keep it so
+                        const float4 q4 = *reinterpret_cast<const float4*>(pe);
+                        e[0] = q4.x; e[1] = q4.y; e[2] = q4.z; e[3] = q4.w;
+                    }
+                }
             } else {
                 load_grad4<NP, VECOK>(G, ldg, row, col, m, k_end, g);
                 if (!e_zero) load_f32x4<VECOK>(E, n, row, col, m, k_end, e);
@@ -1120,9 +1128,9 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
                 const __bf16 h0 = static_cast<__bf16>(w0), h1 = static_cast<__bf16>(w1);
                 w0 = static_cast<float>(h0); w1 = static_cast<float>(h1);
                 __bf16* o = static_cast<__bf16*>(out_) + static_cast<size_t>(row) * ldo + col;
-                if constexpr (FULL) {
+                if constexpr (FULL) {             // the reconstruction is not read again here: past the caches
                     bf16x2 hh = {h0, h1};
-                    *reinterpret_cast<bf16x2*>(o) = hh;
+                    __builtin_nontemporal_store(hh, reinterpret_cast<bf16x2*>(o));
                 } else if (row < m) {
                     if (col < n) o[0] = h0;
                     if (col + 1 < n) o[1] = h1;
@@ -1130,7 +1138,8 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
             } else {
                 float* o = static_cast<float*>(out_) + static_cast<size_t>(row) * ldo + col;
                 if constexpr (FULL) {
-                    *reinterpret_cast<float2*>(o) = make_float2(w0, w1);
+                    const vf2 q2 = {w0, w1};
+                    __builtin_nontemporal_store(q2, reinterpret_cast<vf2*>(o));
                 } else if (row < m) {
                     if (col < n) o[0] = w0;
                     if (col + 1 < n) o[1] = w1;
@@ -1263,6 +1272,19 @@ int launch_copy_rows(edgc_ctx* ctx, const void* src, uint64_t ld_src, void* dst,
 
 // The blocks a pass aims at are shared among the tensors of a group in proportion to their
 // size (at least one each).
+// A group whose residual (= D) takes more than half of the 256 MB last-level cache streams it
+// (measured on 400 MB groups: the Q-pass reads D at 4.7 instead of 3.7 TB/s with non-temporal
+// loads); a smaller one is left cached: the decompress then finds D, and the next step's P-pass
+// E_new, largely still there (bench workload: 0.262 instead of 0.283 ms per step, together with
+// the non-temporal store of the reconstruction).
+static uint32_t group_streams(const edgc_ctx* ctx, const Group& g)
+{
+    if (ctx->tune_stream >= 0) return ctx->tune_stream != 0 ? 1u : 0u;
+    double bytes = 0.0;
+    for (uint32_t i = 0; i < g.count; ++i) bytes += 4.0 * g.t[i].m * g.t[i].n;
+    return bytes > 128.0 * 1024 * 1024 ? 1u : 0u;
+}
+
 static void share_targets(const Group& g, uint32_t target, uint32_t (&out)[kMaxGroup])
 {
     double total = 0.0;
@@ -1419,14 +1441,6 @@ static int run_pass_q(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStre
     const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_q ? ctx->tune_q : 2u);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
-    // D of a group that takes more than half of the 256 MB last-level cache is not there any more
-    // when the decompress comes back for it: reading it past the caches is then faster (measured
-    // 4.7 against 3.7 TB/s on 400 MB groups), while a smaller D is better left cached (the
-    // decompress of the bench workload loses 10 % when the Q-pass reads past the caches).
-    double d_bytes = 0.0;
-    for (uint32_t i = 0; i < g.count; ++i) d_bytes += 4.0 * g.t[i].m * g.t[i].n;
-    g.stream = ctx->tune_stream >= 0 ? static_cast<uint32_t>(ctx->tune_stream != 0)
-                                     : (d_bytes > 128.0 * 1024 * 1024 ? 1u : 0u);
     bool vec = true;
     uint32_t blocks = 0;
     double bytes = 0.0, flops = 0.0;
@@ -1475,6 +1489,7 @@ static int compress_impl(edgc_ctx* ctx, Group& g, const TensorScratch* cap, uint
                          hipStream_t st)
 {
     for (uint32_t i = 0; i < g.count; ++i) g.t[i].m_pad = cdiv(g.t[i].m, 64) * 64;
+    g.stream = group_streams(ctx, g);
     // After the first P-pass the residual buffer holds D; later iterations re-read it
     // with a null gradient (D + 0).
     for (uint32_t it = 0; it < power_iters; ++it) {

@@ -66,8 +66,10 @@ struct TensorArgs {
 struct Group {
     uint32_t count;
     uint32_t r;             // rank, the same for every tensor of a group
-    uint32_t stream;        // Q-pass only.  1: D is too large to still be cached when the decompress
-                            //    reads it again, so the Q-pass reads it with non-temporal loads
+    uint32_t stream;        // 1: the group's residual is too large to stay in the last-level cache:
+                            //    the Q-pass reads D, and the P-pass E_old, with non-temporal loads.
+                            //    0: both are ordinary loads, so that D is still cached when the
+                            //    decompress reads it again and E_new when the next step's P-pass does
     TensorArgs t[kMaxGroup];
 };
 
