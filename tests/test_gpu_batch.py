@@ -107,10 +107,11 @@ def test_mixed_stage_matches_oracle_over_three_steps(dtype, r):
         st.step_oracle_and_compare()
 
 
-def test_benchmark_workload_full_size_in_the_bench_layout():
+@pytest.mark.parametrize("name,steps", [("cfg2_gpt_h2048_r16", 2), ("cfg4_gpt_h5120_bf16", 1)])
+def test_benchmark_workload_full_size_in_the_bench_layout(name, steps):
     """The benchmark's matrices at full size, grouped as bench.py groups them (two groups balanced by
-    size, largest first into the lighter one), two steps so that the second carries a residual."""
-    name = "cfg2_gpt_h2048_r16"
+    size, largest first into the lighter one); two steps of the default workload so that the second
+    carries a residual, one step of the hidden-5120 bf16 block."""
     w = gen.WORKLOADS[name]
     mats = [g for _, g in gen.workload_matrices(name)]
     order = sorted(range(len(mats)), key=lambda i: -mats[i].size)
@@ -122,9 +123,11 @@ def test_benchmark_workload_full_size_in_the_bench_layout():
     assert sorted(members[0] + members[1]) == list(range(len(mats)))
     for idx in members:
         st = Stage(None, w["rank"], w["dtype"], seed=w["seed"], mats=[mats[i] for i in sorted(idx)])
-        for _ in range(2):
+        for _ in range(steps):
             st.step_device()
             st.step_oracle_and_compare()
+        del st
+        torch.cuda.empty_cache()
 
 
 def test_ragged_leading_dimension_and_rank_48():
