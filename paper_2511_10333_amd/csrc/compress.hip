@@ -733,9 +733,24 @@ __global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
     const uint32_t ldp = ta.ldp, m = ta.m, r = grp.r, m_pad = ta.m_pad;
     constexpr int CW = 16 * T16;
     constexpr int LD = CW + 4;             // floats; 16 rows x 4 columns per read: 2-way at worst
+    constexpr int NTILE = T16 * (T16 + 1) / 2;       // upper-triangle 16x16 tiles of R^-1
     __shared__ __attribute__((aligned(16))) float Ps[64 * LD];
+    __shared__ double Rs[NTILE * 256];               // tile (tk <= tc), [k][c] row-major
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t row0 = (blockIdx.x - ta.first) * 64;
+    // R^-1 goes to LDS once per block (all loads in flight together): the multiply below then
+    // runs without a round trip to L2 per k step
+    {
+        const uint32_t kl = tid >> 4, cc = tid & 15;
+        int t = 0;
+#pragma unroll
+        for (int tk = 0; tk < T16; ++tk)
+#pragma unroll
+            for (int tc = tk; tc < T16; ++tc, ++t) {
+                const uint32_t k = 16 * tk + kl, c = 16 * tc + cc;
+                Rs[t * 256 + tid] = (k < r && c < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
+            }
+    }
 #pragma unroll
     for (int it = 0; it < T16; ++it) {
         const int idx = tid + 256 * it;
@@ -762,16 +777,19 @@ __global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
     const float* pa = Ps + (16 * wave + (lane & 15)) * LD + (lane >> 4);
     const uint32_t kq = lane >> 4, cl = lane & 15;
     const uint32_t ksteps = (r + 3) / 4;
-    for (uint32_t kk = 0; kk < ksteps; ++kk) {
-        const double a = static_cast<double>(pa[4 * kk]);
-        const uint32_t k = 4 * kk + kq;
 #pragma unroll
-        for (int tc = 0; tc < T16; ++tc) {
-            // R^-1 is upper triangular: column tile tc needs k <= 16*tc + 15
-            if (4 * kk <= static_cast<uint32_t>(16 * tc + 15)) {
-                const uint32_t c = 16 * tc + cl;
-                const double b = (k < r && c < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
-                acc[tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[tc], 0, 0, 0);
+    for (int kk = 0; kk < 4 * T16; ++kk) {
+        if (static_cast<uint32_t>(kk) < ksteps) {
+            const double a = static_cast<double>(pa[4 * kk]);
+            const int tk = kk >> 2;
+            // R^-1 is upper triangular: row tile tk only reaches column tiles tc >= tk
+#pragma unroll
+            for (int tc = 0; tc < T16; ++tc) {
+                if (tc >= tk) {
+                    const int t = tk * T16 - tk * (tk - 1) / 2 + (tc - tk);
+                    const double b = Rs[t * 256 + ((kk & 3) * 4 + kq) * 16 + cl];
+                    acc[tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[tc], 0, 0, 0);
+                }
             }
         }
     }
