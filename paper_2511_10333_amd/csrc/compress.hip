@@ -418,40 +418,61 @@ __global__ __launch_bounds__(256) void k_reduce_gram(const Group grp, uint32_t R
     for (uint32_t ch = ch_begin; ch < ch_end; ++ch) {
         const uint32_t row0 = ch * 64;
         __syncthreads();                             // previous chunk's Gram reads are done
+        // the sums of all T16 items of a thread advance together, DEP splits at a time, so that
+        // DEP * T16 independent 16-byte loads are in flight (the order of the additions per element
+        // is the split order, whatever the grouping)
+        float4 v[T16];
+        const float* src[T16];
+#pragma unroll
+        for (int it = 0; it < T16; ++it) {
+            const int idx = tid + 256 * it;
+            const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
+            const uint32_t row = min(row0 + i, m - 1);       // rows past the end are loaded but not used
+            v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            src[it] = part + static_cast<size_t>(row) * RP + c4;
+        }
+        constexpr int DEP = T16 >= 4 ? 2 : 4;            // splits per round
+        uint32_t sp = 0;
+        for (; sp + DEP <= S; sp += DEP) {
+            float4 x[DEP][T16];
+#pragma unroll
+            for (int u = 0; u < DEP; ++u)
+#pragma unroll
+                for (int it = 0; it < T16; ++it)
+                    x[u][it] = *reinterpret_cast<const float4*>(src[it] + (sp + u) * sstride);
+#pragma unroll
+            for (int u = 0; u < DEP; ++u)
+#pragma unroll
+                for (int it = 0; it < T16; ++it) {
+                    v[it].x += x[u][it].x; v[it].y += x[u][it].y; v[it].z += x[u][it].z; v[it].w += x[u][it].w;
+                }
+        }
+        for (; sp < S; ++sp) {
+#pragma unroll
+            for (int it = 0; it < T16; ++it) {
+                const float4 x0 = *reinterpret_cast<const float4*>(src[it] + sp * sstride);
+                v[it].x += x0.x; v[it].y += x0.y; v[it].z += x0.z; v[it].w += x0.w;
+            }
+        }
 #pragma unroll
         for (int it = 0; it < T16; ++it) {
             const int idx = tid + 256 * it;
             const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
             const uint32_t row = row0 + i;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (row < m) {
-                const float* src = part + static_cast<size_t>(row) * RP + c4;
-                uint32_t sp = 0;
-                for (; sp + 4 <= S; sp += 4) {
-                    const float4 x0 = *reinterpret_cast<const float4*>(src + (sp + 0) * sstride);
-                    const float4 x1 = *reinterpret_cast<const float4*>(src + (sp + 1) * sstride);
-                    const float4 x2 = *reinterpret_cast<const float4*>(src + (sp + 2) * sstride);
-                    const float4 x3 = *reinterpret_cast<const float4*>(src + (sp + 3) * sstride);
-                    v.x += x0.x; v.y += x0.y; v.z += x0.z; v.w += x0.w;
-                    v.x += x1.x; v.y += x1.y; v.z += x1.z; v.w += x1.w;
-                    v.x += x2.x; v.y += x2.y; v.z += x2.z; v.w += x2.w;
-                    v.x += x3.x; v.y += x3.y; v.z += x3.z; v.w += x3.w;
-                }
-                for (; sp < S; ++sp) {
-                    const float4 x0 = *reinterpret_cast<const float4*>(src + sp * sstride);
-                    v.x += x0.x; v.y += x0.y; v.z += x0.z; v.w += x0.w;
-                }
                 // partial columns >= r are exact zeros (the Q tile is masked in the P-pass)
                 float* dst = P + static_cast<size_t>(row) * ldp + c4;
                 if (static_cast<uint32_t>(c4) + 4 <= r) {
-                    *reinterpret_cast<float4*>(dst) = v;
+                    *reinterpret_cast<float4*>(dst) = v[it];
                 } else {
-                    if (static_cast<uint32_t>(c4) < r) dst[0] = v.x;
-                    if (static_cast<uint32_t>(c4) + 1 < r) dst[1] = v.y;
-                    if (static_cast<uint32_t>(c4) + 2 < r) dst[2] = v.z;
+                    if (static_cast<uint32_t>(c4) < r) dst[0] = v[it].x;
+                    if (static_cast<uint32_t>(c4) + 1 < r) dst[1] = v[it].y;
+                    if (static_cast<uint32_t>(c4) + 2 < r) dst[2] = v[it].z;
                 }
+            } else {
+                v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            *reinterpret_cast<float4*>(Ps + i * LD + c4) = v;
+            *reinterpret_cast<float4*>(Ps + i * LD + c4) = v[it];
         }
         __syncthreads();
         const float* pk = Ps + (lane >> 4) * LD + (lane & 15);
