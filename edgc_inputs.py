@@ -103,6 +103,10 @@ WORKLOADS: Dict[str, dict] = {
                                 stride=100, chunk=64, bins=1024, rank=64, seed=0),
     "cfg5_stage_h4096": dict(layers=gpt_block(4096), dtype="f32", k=1024, decay=0.90, noise=1e-4,
                              stride=100, chunk=64, bins=1024, rank=64, seed=0),
+    # the whole pipeline stage of that configuration: 8 layers, 32 tensors, 1.61e9 elements; the
+    # 8 layers carry the same four seeded gradients (generating 32 distinct ones takes minutes)
+    "cfg5_stage8_h4096": dict(layers=gpt_block(4096), repeat=8, dtype="f32", k=1024, decay=0.90, noise=1e-4,
+                              stride=100, chunk=64, bins=1024, rank=64, seed=0),
 }
 
 
@@ -118,4 +122,8 @@ def workload_matrices(name: str, scale_hidden: int | None = None) -> List[Tuple[
         k = min(w["k"], m, n)
         g = lowrank_plus_noise(m, n, k, w["decay"], w["noise"], w["seed"] + 17 * li, w["dtype"])
         out.append((LayerSpec(spec.name, m, n), g))
+    rep = w.get("repeat", 1)
+    if rep > 1:
+        out = [(LayerSpec("L%d.%s" % (layer, spec.name), spec.m, spec.n), g)
+               for layer in range(rep) for spec, g in out]
     return out
