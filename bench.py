@@ -133,7 +133,10 @@ def main() -> int:
             G = torch.from_numpy(g).cuda()
         ldf = (r + 3) // 4 * 4
         Q = torch.zeros((spec.n, ldf), dtype=torch.float32, device="cuda")
-        ctx.init_q(Q, 0, r, w["seed"] + li)
+        torch.cuda.synchronize()
+        # on the stream that will own the layer: the runtime sets a stream's hardware queue up at its
+        # first submission (milliseconds), which belongs to the set-up, not to a step
+        ctx.init_q(Q, 0, r, w["seed"] + li, stream=streams[li % n_streams])
         layers.append(dict(
             spec=spec, G=G, Q=Q, ctx=ctxs[li % n_streams], stream=streams[li % n_streams],
             estream=ent_streams[li % n_ent],
@@ -142,6 +145,9 @@ def main() -> int:
             out=torch.empty_like(G), fresh=True,
             ent=[torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True) for _ in range(NBUF)],
         ))
+    for st in ent_streams:
+        with torch.cuda.stream(st):
+            torch.zeros(1, device="cuda")     # first submission on the entropy stream, as above
     torch.cuda.synchronize()
 
     # batched mode: groups of layers, each with a context whose batch slots fit the group

@@ -39,16 +39,30 @@ public:
         if (gm_ > 0.0) bracket -= 2.0 * gm_ * std::atan2(std::sqrt(b_ * up), std::sqrt(a_ * dn));
         return bracket / (2.0 * M_PI * static_cast<double>(mm_));
     }
-    // inverse CDF on [from, b]; `from` must satisfy cdf(from) <= p
+    // density of the same law: dF/dl = sqrt((l-a)(b-l)) / (2 pi mm l)
+    double pdf(double l) const
+    {
+        if (l <= a_ || l >= b_) return 0.0;
+        return std::sqrt((l - a_) * (b_ - l)) / (2.0 * M_PI * static_cast<double>(mm_) * l);
+    }
+    // inverse CDF on [from, b]; `from` must satisfy cdf(from) <= p.  Newton steps from `from`,
+    // kept inside a bracket that every evaluation tightens; a step that leaves the bracket
+    // (the density vanishes at both ends of the support) is replaced by its mid-point.
     double quantile(double p, double from) const
     {
         double lo = std::max(from, a_), hi = b_;
-        for (int it = 0; it < 128; ++it) {
-            const double mid = lo + 0.5 * (hi - lo);
-            if (!(mid > lo && mid < hi)) break;
-            (cdf(mid) < p ? lo : hi) = mid;
+        double x = lo;
+        for (int it = 0; it < 200; ++it) {
+            const double f = cdf(x) - p;
+            (f < 0.0 ? lo : hi) = x;
+            const double d = pdf(x);
+            double nx = d > 0.0 ? x - f / d : lo + 0.5 * (hi - lo);
+            if (!(nx > lo && nx < hi)) nx = lo + 0.5 * (hi - lo);
+            if (!(nx > lo && nx < hi)) break;             // the bracket is one rounding step wide
+            if (std::fabs(nx - x) <= 4e-16 * std::fabs(nx)) { x = nx; break; }
+            x = nx;
         }
-        return lo + 0.5 * (hi - lo);
+        return x;
     }
     uint32_t small() const { return mm_; }
     double a() const { return a_; }
