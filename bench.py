@@ -12,7 +12,10 @@ Default layout: the layers are split into two groups; each group goes through
 the batched entry points (one launch sequence per group, on a stream of its
 own, so that one group's small kernels run beside the other's streaming
 passes); one stage-level entropy estimate over all the gradient buffers runs
-on a third stream.  `--batch 0` runs one call chain and one estimate per layer.
+on a third stream; the error-feedback residual is kept in the deferred form
+(the buffer holds D = G + E, the next step's P-pass subtracts P^ Q^T on the
+way; `--explicit-residual` stores E instead).  `--batch 0` runs one call chain
+and one estimate per layer.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
@@ -63,6 +66,10 @@ def parse_args():
     ap.add_argument("--ent-streams", type=int, default=0,
                     help="streams the entropy estimates are spread over; 0 = one in batched mode (compress streams "
                          "+ entropy stream stay within the 4 hardware queues), else one per compress stream")
+    ap.add_argument("--explicit-residual", action="store_true",
+                    help="batched mode: keep E = D - M^ in the residual buffer between steps (the decompress reads D "
+                         "and writes E) instead of the default deferred subtraction, where the buffer keeps D, the "
+                         "decompress only writes the reconstruction and the next P-pass subtracts P^ Q^T on the way")
     ap.add_argument("--serial", action="store_true",
                     help="issue everything on ONE stream, also in the timed region (what the per-kernel second pass "
                          "always does): the run to put under rocprofv3 --kernel-trace --stats, every kernel alone on the GPU")
@@ -198,11 +205,14 @@ def main() -> int:
                  for x in ([stage] if groups else layers)]
             decisions.append(edgc.select_rank(state, H, 1, prm))
 
+    deferred = bool(groups) and not args.explicit_residual
+
     def compress_all():
         if groups:
             for g in groups:
-                g["ctx"].compress_batch(g["tensors"], r, stream=g["stream"])
-                g["ctx"].decompress_batch(g["tensors"], r, stream=g["stream"])
+                first = g["tensors"][0].residual_is_zero     # nothing to subtract yet
+                g["ctx"].compress_batch(g["tensors"], r, stream=g["stream"], deferred=deferred and not first)
+                g["ctx"].decompress_batch(g["tensors"], r, stream=g["stream"], deferred=deferred)
                 for t in g["tensors"]:
                     t.residual_is_zero = False
             return
@@ -373,6 +383,7 @@ def main() -> int:
                    "rank": r, "stride": w["stride"], "chunk": w["chunk"], "bins": w["bins"],
                    "streams": 1 if args.serial else n_streams, "entropy_streams": 0 if args.serial else n_ent,
                    "hip_graph": graphed, "batch_groups": len(groups),
+                   "residual": "deferred" if deferred else "explicit",
                    "gradient_bytes_per_step": grad_bytes},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "mfma": mfma,
         "last_rank_decision": decisions[-1].rank if decisions else None,

@@ -325,7 +325,7 @@ typedef struct {
     uint64_t    ld, ld_out;
     uint32_t    m, n, ldq, ldp;
     int32_t     residual_is_zero;
-    uint32_t    _pad;
+    uint32_t    deferred;       /* 0 or 1, the same for every tensor of a call: see below  */
 } edgc_tensor;
 
 int edgc_tensor_bypassed(uint32_t m, uint32_t n, uint32_t r);
@@ -346,12 +346,41 @@ int edgc_reserve_batch(edgc_ctx* ctx, const uint32_t* rows, const uint32_t* cols
  * edgc_decompress_batch reads P, Q, residual, grad_out, ld_out (and grad, ld
  * of tensors sent as they stand).
  * Errors: as for the single-tensor calls, EDGC_EINVAL also for count above the
- * reservation or a tensor larger than its slot.  Nothing is launched when a
- * descriptor is rejected. */
+ * reservation, a tensor larger than its slot, or descriptors that disagree in
+ * `deferred`.  Nothing is launched when a descriptor is rejected.
+ *
+ * Deferred subtraction (deferred = 1).  The error feedback of Sec. III-B / VII
+ * is E_t = D_t - M^_t with D_t = G_t + E_(t-1).  With deferred = 0 the
+ * residual buffer holds E_t between steps, as for the single-tensor calls.
+ * With deferred = 1 it holds D_t and E_t stays in factored form: the P and Q
+ * buffers, which after the step hold P^_t and Q_t, stand in for M^_t.
+ *   edgc_decompress_batch, deferred = 1: writes grad_out only; the residual
+ *     buffer is neither read nor written and keeps D_t.
+ *   edgc_compress_batch, deferred = 1: the residual buffer holds D_(t-1) and
+ *     P, Q the factors of that step (unless residual_is_zero); the call forms
+ *     D_t = G_t + D_(t-1) - P^_(t-1) Q_(t-1)^T on the way, M^_(t-1) computed
+ *     and rounded exactly as the decompress wrote it, so the results equal
+ *     the deferred = 0 chain bit for bit where the launch shapes agree.
+ * This saves one read and one write of the fp32 residual per step.  The flag
+ * of a compress call says what the buffer holds on entry, that of a
+ * decompress call what it holds on return, so a chain may change over: after
+ * decompress with 1, compress with 1; after decompress with 0 (or
+ * edgc_residual_materialize_batch), compress with 0.  Between a deferred
+ * decompress and the next compress the caller leaves P and Q untouched and
+ * keeps r and dtype; before anything else that needs E_t itself (another
+ * rank, a checkpoint of the residual, the single-tensor calls)
+ * edgc_residual_materialize_batch carries the subtraction out:
+ * residual <- residual - round_dtype(P Q^T).  With power_iters > 1 the
+ * subtraction is part of the first iteration.  Tensors sent as they stand
+ * ignore the flag. */
 int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count, edgc_dtype dtype,
                         uint32_t r, uint32_t power_iters, void* hip_stream);
 int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
                           edgc_dtype dtype, uint32_t r, void* hip_stream);
+/* reads residual, P, Q of every compressed tensor; writes residual; `deferred` and the gradient
+ * pointers of the descriptors are ignored.  r and dtype: those of the step that left P and Q. */
+int edgc_residual_materialize_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                    edgc_dtype dtype, uint32_t r, void* hip_stream);
 
 /* The entropy of a pipeline stage whose gradients are separate buffers (Sec.
  * IV-C / Algorithm 1 work with one entropy per stage): `count` (1..32)

@@ -113,6 +113,8 @@ def load_library() -> C.CDLL:
     L.edgc_compress_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, u32, vp]
     L.edgc_decompress_batch.restype = i32
     L.edgc_decompress_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
+    L.edgc_residual_materialize_batch.restype = i32
+    L.edgc_residual_materialize_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
     L.edgc_init_q.restype = i32
     L.edgc_init_q.argtypes = [vp, vp, u32, u32, u32, u32, u64, vp]
     L.edgc_compress.restype = i32
@@ -127,7 +129,7 @@ class _Tensor(C.Structure):
     _fields_ = [("grad", C.c_void_p), ("grad_out", C.c_void_p), ("residual", C.c_void_p),
                 ("Q", C.c_void_p), ("P", C.c_void_p), ("ld", C.c_uint64), ("ld_out", C.c_uint64),
                 ("m", C.c_uint32), ("n", C.c_uint32), ("ldq", C.c_uint32), ("ldp", C.c_uint32),
-                ("residual_is_zero", C.c_int32), ("_pad", C.c_uint32)]
+                ("residual_is_zero", C.c_int32), ("deferred", C.c_uint32)]
 
 
 @dataclass
@@ -456,7 +458,7 @@ class Context:
         self._check(self._L.edgc_reserve_batch(self._h, rows, cols, n), "edgc_reserve_batch")
 
     @staticmethod
-    def _marshal(tensors: Sequence[Tensor]):
+    def _marshal(tensors: Sequence[Tensor], deferred: bool = False):
         arr = (_Tensor * max(len(tensors), 1))()
         code = None
         for i, t in enumerate(tensors):
@@ -468,22 +470,32 @@ class Context:
                              ld(t.grad), ld(t.grad_out), m, n,
                              t.Q.shape[1] if t.Q is not None else 0,
                              t.P.shape[1] if t.P is not None else 0,
-                             1 if t.residual_is_zero else 0, 0)
+                             1 if t.residual_is_zero else 0, 1 if deferred else 0)
             c = _dtype_code(g)
             if code is not None and c != code:
                 raise TypeError("all gradients of a batch must have one dtype")
             code = c
         return arr, (code if code is not None else F32)
 
-    def compress_batch(self, tensors: Sequence[Tensor], r: int, power_iters: int = 1, stream=None) -> None:
-        """edgc_compress_batch over a list of :class:`Tensor`."""
-        arr, code = self._marshal(tensors)
+    def compress_batch(self, tensors: Sequence[Tensor], r: int, power_iters: int = 1, stream=None,
+                       deferred: bool = False) -> None:
+        """edgc_compress_batch over a list of :class:`Tensor`; ``deferred``: the residual buffers
+        hold D of the previous step and P, Q its factors (edgc_tensor.deferred of every entry)."""
+        arr, code = self._marshal(tensors, deferred)
         rc = self._L.edgc_compress_batch(self._h, arr, len(tensors), code, r, power_iters,
                                          _stream_handle(stream))
         self._check(rc, "edgc_compress_batch")
 
-    def decompress_batch(self, tensors: Sequence[Tensor], r: int, stream=None) -> None:
-        """edgc_decompress_batch over a list of :class:`Tensor`."""
-        arr, code = self._marshal(tensors)
+    def decompress_batch(self, tensors: Sequence[Tensor], r: int, stream=None, deferred: bool = False) -> None:
+        """edgc_decompress_batch over a list of :class:`Tensor`; ``deferred``: only the
+        reconstruction is written and the residual buffers keep D."""
+        arr, code = self._marshal(tensors, deferred)
         rc = self._L.edgc_decompress_batch(self._h, arr, len(tensors), code, r, _stream_handle(stream))
         self._check(rc, "edgc_decompress_batch")
+
+    def residual_materialize_batch(self, tensors: Sequence[Tensor], r: int, stream=None) -> None:
+        """edgc_residual_materialize_batch: residual <- residual - round(P Q^T)."""
+        arr, code = self._marshal(tensors)
+        rc = self._L.edgc_residual_materialize_batch(self._h, arr, len(tensors), code, r,
+                                                     _stream_handle(stream))
+        self._check(rc, "edgc_residual_materialize_batch")

@@ -1054,8 +1054,11 @@ __global__ __launch_bounds__(256) void k_reduce_q(const Group grp, uint32_t RP)
 // accesses, 256 B contiguous per half wave).  Q rows and D of the next stage are
 // fetched while the current stage is multiplied and written.
 // One bf16 plane <=> bf16 gradient and output; two planes <=> fp32.
+// DEFER: only M^ is written; the residual buffer keeps D and the next step's P-pass subtracts
+// M^ itself (k_pass_p_deferred).  Without DEFER a null `out` leaves the reconstruction unwritten
+// (E_new alone: the deferred subtraction carried out after all).
 // ---------------------------------------------------------------------------
-template <int NP, int RT, bool VECOK>
+template <int NP, int RT, bool VECOK, bool DEFER>
 __global__ __launch_bounds__(256) void k_decompress(const Group grp)
 {
     const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
@@ -1107,7 +1110,7 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
     const uint32_t st_end = min(total_stages, st_begin + stages_per_split);
 
     float qv[PQ][4];
-    float dv[2][16][2];
+    float dv[DEFER ? 1 : 2][16][2];
     auto fetch_q = [&](uint32_t st) {
 #pragma unroll
         for (int p = 0; p < PQ; ++p) {
@@ -1141,6 +1144,7 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
     // D of this lane's 16 rows x 2 adjacent columns
     auto fetch_d = [&](uint32_t st, float (&d)[16][2], auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
+        if constexpr (DEFER) return;
         const uint32_t col = st * 64 + 2 * jl;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -1167,7 +1171,8 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
                 const __bf16 h0 = static_cast<__bf16>(w0), h1 = static_cast<__bf16>(w1);
                 w0 = static_cast<float>(h0); w1 = static_cast<float>(h1);
                 __bf16* o = static_cast<__bf16*>(out_) + static_cast<size_t>(row) * ldo + col;
-                if constexpr (FULL) {             // the reconstruction is not read again here: past the caches
+                if (!DEFER && out_ == nullptr) {
+                } else if constexpr (FULL) {      // the reconstruction is not read again here: past the caches
                     bf16x2 hh = {h0, h1};
                     __builtin_nontemporal_store(hh, reinterpret_cast<bf16x2*>(o));
                 } else if (row < m) {
@@ -1176,7 +1181,8 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
                 }
             } else {
                 float* o = static_cast<float*>(out_) + static_cast<size_t>(row) * ldo + col;
-                if constexpr (FULL) {
+                if (!DEFER && out_ == nullptr) {
+                } else if constexpr (FULL) {
                     const vf2 q2 = {w0, w1};
                     __builtin_nontemporal_store(q2, reinterpret_cast<vf2*>(o));
                 } else if (row < m) {
@@ -1184,6 +1190,7 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
                     if (col + 1 < n) o[1] = w1;
                 }
             }
+            if constexpr (DEFER) continue;
             const float e0 = d[v][0] - w0, e1 = d[v][1] - w1;
             if constexpr (FULL) {
                 *reinterpret_cast<float2*>(e) = make_float2(e0, e1);
@@ -1226,9 +1233,298 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
         if (stage_full(st_begin)) fetch_d(st_begin, dv[0], T{}); else fetch_d(st_begin, dv[0], F{});
     }
     for (uint32_t st = st_begin; st < st_end; st += 2) {
-        run_stage(st, dv[0], dv[1]);
-        if (st + 1 < st_end) run_stage(st + 1, dv[1], dv[0]);
+        run_stage(st, dv[0], dv[DEFER ? 0 : 1]);
+        if (st + 1 < st_end) run_stage(st + 1, dv[DEFER ? 0 : 1], dv[0]);
     }
+}
+
+// ---------------------------------------------------------------------------
+// P-pass with the deferred subtraction.  The residual buffer holds D_prev = G_prev + E_prev of
+// the previous step and P, Q hold that step's factors; the residual itself is only formed here:
+//   E = D_prev - M^_prev,  M^_prev = P^_prev Q_prev^T  (rounded as it was transmitted)
+//   D = G + E  (written back),  P_partial[s] = D[:, k-range s] Q_prev[k-range s, :]
+// so that the decompress neither reads D nor writes E: 8 bytes per element less traffic per
+// step for two small MFMA products more.  M^_prev is computed exactly as k_decompress computed
+// it (same fragments, same order), hence E is bit-identical to what that kernel would have
+// stored.
+// Block: 4 waves x 32 rows over 64-column stages, the lane layout of k_decompress (lane (jl, g)
+// holds columns 2jl, 2jl+1 of 16 rows).  A stage's Q rows are staged twice: [column][rank]
+// (B operand of M^) and [rank][column] (B operand of D Q); D goes through a wave-private LDS
+// tile to become the A operand.
+// ---------------------------------------------------------------------------
+template <int NP, int RT, bool VECOK>
+__global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const Group grp)
+{
+    // Up to rank 64 two blocks share a CU and each keeps one stage of G and D_prev in flight;
+    // above, LDS leaves room for one block, which then prefetches into a second register set.
+    constexpr bool DB = RT > 2;
+    const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
+    using GT = typename GradElem<NP>::type;
+    const GT* __restrict__ G = static_cast<const GT*>(ta.G);
+    float* __restrict__ E = ta.E;
+    const float* __restrict__ Q = ta.Q;
+    const float* __restrict__ P = ta.P;
+    float* __restrict__ part = ta.part;
+    const uint64_t ldg = ta.ldg;
+    const uint32_t ldq = ta.ldq, ldp = ta.ldp, m = ta.m, n = ta.n, r = grp.r, kper = ta.d0, S = ta.d1;
+    const bool e_zero = ta.e_zero != 0;
+    constexpr bool ROUND_BF16 = (NP == 1);
+    constexpr int KT = RT * 2, RP = RT * 32;
+    constexpr int ROWQ = NP * RP * 2 + 16;            // LDS bytes per Q row, [column][rank]
+    constexpr int ROWB = NP * 128 + 16;               // LDS bytes per row of 64 columns
+    constexpr int PQ = 32 * (RP / 4) / 256;           // Q-stage items per thread: 2 rows x 4 ranks each
+    extern __shared__ __attribute__((aligned(16))) unsigned char plds[];
+    unsigned char* ldsQ = plds;                       // 64 x ROWQ
+    unsigned char* ldsT = ldsQ + 64 * ROWQ;           // RP x ROWB: Q^T
+    unsigned char* ldsA = ldsT + RP * ROWB;           // 128 x ROWB: D
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: row addresses then are scalar base + one per-lane offset
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int jl = lane & 31, g = lane >> 5;
+    const uint32_t lid = blockIdx.x - ta.first;
+    const uint32_t s = lid % S, rb = lid / S;
+    const uint32_t row0 = rb * 128 + wave * 32;
+    const uint32_t k_begin = s * kper;
+    const uint32_t k_end = min(n, k_begin + kper);
+    const uint32_t n_st = k_begin < k_end ? (k_end - k_begin + 63) / 64 : 0;
+    const bool rows_full = row0 + 32 <= m;
+    // per-lane element offsets inside a 32-row x 64-column stage (vector path: both fit 32 bits)
+    const uint32_t off_d = 4u * g * n + 2u * jl;
+    const uint32_t off_g = 4u * g * static_cast<uint32_t>(ldg) + 2u * jl;
+
+    // A-fragments of P^_prev: row row0 + jl, k = kb*16 + 8g .. +8
+    bf16x8 a[KT][NP];
+#pragma unroll
+    for (int kb = 0; kb < KT; ++kb) {
+        float v[8];
+        const uint32_t row = row0 + jl, c0 = kb * 16 + 8 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+        if (!e_zero && row < m) {
+            if (c0 + 8 <= r) {
+                const float4 x = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0);
+                const float4 y = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0 + 4);
+                v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (c0 + e < r) v[e] = P[static_cast<size_t>(row) * ldp + c0 + e];
+            }
+        }
+        pack8<NP>(v, a[kb]);
+    }
+
+    float qv[PQ][2][4];
+    float dv[DB ? 2 : 1][16][2], gv[DB ? 2 : 1][16][2];
+    auto stage_full = [&](uint32_t st) __attribute__((always_inline)) { return VECOK && rows_full && k_begin + st * 64 + 64 <= k_end; };
+    // Q rows of a stage: item (jp, c4) holds rows 2jp and 2jp+1 (two adjacent columns of the
+    // matrix), ranks c4 .. c4+3; lanes run along jp
+    auto fetch_q = [&](uint32_t st) __attribute__((always_inline)) {
+        const uint32_t col0 = k_begin + st * 64;
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jp = idx & 31, c4 = (idx >> 5) * 4;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t j = col0 + 2 * jp + h;
+                qv[p][h][0] = qv[p][h][1] = qv[p][h][2] = qv[p][h][3] = 0.0f;
+                if (j < n && static_cast<uint32_t>(c4) < ldq) {
+                    const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(j) * ldq + c4);
+                    qv[p][h][0] = q.x; qv[p][h][1] = q.y; qv[p][h][2] = q.z; qv[p][h][3] = q.w;
+                }
+            }
+        }
+    };
+    // G and D_prev of this lane's 16 rows x 2 adjacent columns
+    auto fetch_dg = [&](uint32_t st, auto buf_tag, auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int B = decltype(buf_tag)::value;
+        const uint32_t col0 = k_begin + st * 64;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rowu = row0 + 8 * (v / 4) + (v % 4);        // scalar part of the row
+            dv[B][v][0] = dv[B][v][1] = 0.0f;
+            if constexpr (FULL) {
+                const GT* pg = G + (static_cast<uint64_t>(rowu) * ldg + col0) + off_g;
+                const float* pd = E + (static_cast<uint64_t>(rowu) * n + col0) + off_d;
+                if constexpr (NP == 2) {
+                    const vf2 x = __builtin_nontemporal_load(reinterpret_cast<const vf2*>(pg));
+                    gv[B][v][0] = x.x; gv[B][v][1] = x.y;
+                } else {
+                    const uint32_t x = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(pg));
+                    gv[B][v][0] = __uint_as_float(x << 16); gv[B][v][1] = __uint_as_float(x & 0xffff0000u);
+                }
+                if (!e_zero) {
+                    if (grp.stream) {
+                        const vf2 x = __builtin_nontemporal_load(reinterpret_cast<const vf2*>(pd));
+                        dv[B][v][0] = x.x; dv[B][v][1] = x.y;
+                    } else {
+                        const float2 x = *reinterpret_cast<const float2*>(pd);
+                        dv[B][v][0] = x.x; dv[B][v][1] = x.y;
+                    }
+                }
+            } else {
+                const uint32_t row = rowu + 4 * g, col = col0 + 2 * jl;
+                const GT* pg = G + static_cast<uint64_t>(row) * ldg + col;
+                const float* pd = E + static_cast<uint64_t>(row) * n + col;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const bool in = row < m && col + e < k_end;
+                    if constexpr (NP == 2) gv[B][v][e] = in ? pg[e] : 0.0f;
+                    else gv[B][v][e] = in ? bf16_bits_widen(pg[e]) : 0.0f;
+                    if (in && !e_zero) dv[B][v][e] = pd[e];
+                }
+            }
+        }
+    };
+    // ... into LDS twice: [column][rank] (row 2jp + h at LDS row h*32 + jp, so that a lane of the
+    // first product ends up with two adjacent columns) and [rank][column], there as 32-bit words
+    // of two adjacent columns: 128 contiguous bytes per half wave, no 16-bit scatter
+    auto stage_q = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jp = idx & 31, c4 = (idx >> 5) * 4;
+            uint32_t w[2][2][NP];                      // [row h][rank pair][plane]
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float m4[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) m4[e] = (static_cast<uint32_t>(c4 + e) < r) ? qv[p][h][e] : 0.0f;
+                pack_pair<NP>(m4[0], m4[1], w[h][0]);
+                pack_pair<NP>(m4[2], m4[3], w[h][1]);
+            }
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const u32x2 two = {w[h][0][q], w[h][1][q]};
+                    *reinterpret_cast<u32x2*>(ldsQ + (h * 32 + jp) * ROWQ + q * (RP * 2) + c4 * 2) = two;
+                }
+#pragma unroll
+                for (int e2 = 0; e2 < 2; ++e2) {
+                    // ranks c4 + 2 e2 (low halves) and c4 + 2 e2 + 1 (high halves) of the two rows
+                    const uint32_t lo = __builtin_amdgcn_perm(w[1][e2][q], w[0][e2][q], 0x05040100u);
+                    const uint32_t hi = __builtin_amdgcn_perm(w[1][e2][q], w[0][e2][q], 0x07060302u);
+                    *reinterpret_cast<uint32_t*>(ldsT + (c4 + 2 * e2) * ROWB + q * 128 + jp * 4) = lo;
+                    *reinterpret_cast<uint32_t*>(ldsT + (c4 + 2 * e2 + 1) * ROWB + q * 128 + jp * 4) = hi;
+                }
+            }
+        }
+    };
+
+    f32x16 accp[RT];
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accp[ct][v] = 0.0f;
+
+    using T = std::true_type;
+    using F = std::false_type;
+    auto fetch_next = [&](uint32_t st, auto buf_tag) __attribute__((always_inline)) {
+        if (st < n_st) { if (stage_full(st)) fetch_dg(st, buf_tag, T{}); else fetch_dg(st, buf_tag, F{}); }
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, DB ? 1 : 0>;
+
+    // The stage body is spelled out once per register set (a macro, not a lambda: with the
+    // D / G / accumulator arrays handed to a lambda the compiler spills).
+    //   M^_prev of the stage from LDS, as the decompress formed it;
+    //   E = D_prev - M^_prev, D = G + E: to the residual buffer and, as bf16 planes, to the wave's LDS rows.
+#define EDGC_DEFERRED_COMBINE(ST, CUR, FULL)                                                              \
+    {                                                                                                     \
+        const uint32_t col0 = k_begin + (ST) * 64;                                                        \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                  \
+            const int rl = 8 * (v / 4) + (v % 4);                                                         \
+            float w0 = acc[0][v], w1 = acc[1][v];                                                         \
+            if constexpr (ROUND_BF16) {                                                                   \
+                w0 = static_cast<float>(static_cast<__bf16>(w0));                                         \
+                w1 = static_cast<float>(static_cast<__bf16>(w1));                                         \
+            }                                                                                             \
+            const float d0 = gv[CUR][v][0] + (dv[CUR][v][0] - w0), d1 = gv[CUR][v][1] + (dv[CUR][v][1] - w1); \
+            if constexpr (FULL) {                                                                         \
+                float* pd = E + (static_cast<uint64_t>(row0 + rl) * n + col0) + off_d;                    \
+                *reinterpret_cast<float2*>(pd) = make_float2(d0, d1);                                     \
+            } else {                                                                                      \
+                const uint32_t row = row0 + rl + 4 * g, col = col0 + 2 * jl;                              \
+                float* pd = E + static_cast<uint64_t>(row) * n + col;                                     \
+                if (row < m) {                                                                            \
+                    if (col < k_end) pd[0] = d0;                                                          \
+                    if (col + 1 < k_end) pd[1] = d1;                                                      \
+                }                                                                                         \
+            }                                                                                             \
+            uint32_t w[NP];                                                                               \
+            pack_pair<NP>(d0, d1, w);                                                                     \
+            _Pragma("unroll") for (int q = 0; q < NP; ++q)                                                \
+                *reinterpret_cast<uint32_t*>(ldsA + (wave * 32 + rl + 4 * g) * ROWB + q * 128 + jl * 4) = w[q]; \
+        }                                                                                                 \
+    }
+    // CUR / NXT: register sets of this stage and of the prefetch.  With one set (CUR = NXT) the next
+    // stage's loads are issued as soon as this stage has used it and fly during its second product
+    // and the next stage's first one.
+#define EDGC_DEFERRED_STAGE(ST, CUR, NXT)                                                                 \
+    {                                                                                                     \
+        __syncthreads(); /* previous stage's LDS reads are done */                                        \
+        stage_q();                                                                                        \
+        __syncthreads();                                                                                  \
+        if ((ST) + 1 < n_st) fetch_q((ST) + 1);                                                           \
+        if constexpr (DB) fetch_next((ST) + 1, NXT{});                                                    \
+        f32x16 acc[2];                                                                                    \
+        _Pragma("unroll") for (int ct = 0; ct < 2; ++ct)                                                  \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;                             \
+        if (!e_zero) {                                                                                    \
+            _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                            \
+                _Pragma("unroll") for (int kb = 0; kb < KT; ++kb) {                                       \
+                    bf16x8 b[NP];                                                                         \
+                    _Pragma("unroll") for (int p = 0; p < NP; ++p)                                        \
+                        b[p] = *reinterpret_cast<const bf16x8*>(ldsQ + (ct * 32 + jl) * ROWQ + p * (RP * 2) + kb * 32 + g * 16); \
+                    acc[ct] = mma<NP>(a[kb], b, acc[ct]);                                                 \
+                }                                                                                         \
+            }                                                                                             \
+        }                                                                                                 \
+        if (stage_full(ST)) EDGC_DEFERRED_COMBINE(ST, CUR::value, true)                                   \
+        else EDGC_DEFERRED_COMBINE(ST, CUR::value, false)                                                 \
+        if constexpr (!DB) fetch_next((ST) + 1, NXT{});                                                   \
+        __syncthreads(); /* D tile and Q^T are in LDS */                                                  \
+        const unsigned char* pa = ldsA + (wave * 32 + jl) * ROWB + g * 16;                                \
+        const unsigned char* pb = ldsT + jl * ROWB + g * 16;                                              \
+        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) {                                                \
+            bf16x8 af[NP];                                                                                \
+            _Pragma("unroll") for (int q = 0; q < NP; ++q)                                                \
+                af[q] = *reinterpret_cast<const bf16x8*>(pa + q * 128 + kb * 32);                         \
+            _Pragma("unroll") for (int ct = 0; ct < RT; ++ct) {                                           \
+                bf16x8 b[NP];                                                                             \
+                _Pragma("unroll") for (int q = 0; q < NP; ++q)                                            \
+                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + q * 128 + kb * 32);     \
+                accp[ct] = mma<NP>(af, b, accp[ct]);                                                      \
+            }                                                                                             \
+        }                                                                                                 \
+    }
+
+    if (n_st) fetch_q(0);
+    fetch_next(0, B0{});
+    if constexpr (DB) {
+        for (uint32_t st = 0; st < n_st; st += 2) {
+            EDGC_DEFERRED_STAGE(st, B0, B1)
+            if (st + 1 < n_st) EDGC_DEFERRED_STAGE(st + 1, B1, B0)
+        }
+    } else {
+        for (uint32_t st = 0; st < n_st; ++st) EDGC_DEFERRED_STAGE(st, B0, B0)
+    }
+#undef EDGC_DEFERRED_STAGE
+#undef EDGC_DEFERRED_COMBINE
+
+    // partial P of this k-range: part[s][row][c], c over the padded rank
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
+            if (row < m)
+                part[(static_cast<size_t>(s) * m + row) * RP + ct * 32 + jl] = accp[ct][v];
+        }
 }
 
 // Strided row copy (a tensor that is sent as it stands: decompress hands the gradient on).
@@ -1274,6 +1570,22 @@ static hipError_t allow_lds_pass_q()
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
+template <int NP, int RT>
+static constexpr size_t deferred_lds()
+{
+    return static_cast<size_t>(64) * (NP * RT * 32 * 2 + 16) + static_cast<size_t>(RT * 32 + 128) * (NP * 128 + 16);
+}
+template <int NP, int RT>
+static hipError_t allow_lds_pass_p_deferred()
+{
+    constexpr int lds = static_cast<int>(deferred_lds<NP, RT>());
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_pass_p_deferred<NP, RT, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_pass_p_deferred<NP, RT, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+
 int prepare_compress_kernels(edgc_ctx* ctx)
 {
     constexpr int chol_max = (128 * 129 + 8 * 16 * 17 + 128 + kCholThreads) * 8 + 64;
@@ -1282,6 +1594,8 @@ int prepare_compress_kernels(edgc_ctx* ctx)
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<1, 4, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 4, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 2>()));
+    EDGC_HIP_TRY(ctx, (allow_lds_pass_p_deferred<2, 2>()));
+    EDGC_HIP_TRY(ctx, (allow_lds_pass_p_deferred<2, 4>()));
     return EDGC_OK;
 }
 
@@ -1360,15 +1674,25 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         t.sp = S;
         t.first = blocks;
         blocks += RB * S;
-        vec = vec && (t.n % 4 == 0) && (t.ldg % 4 == 0) &&
-              (reinterpret_cast<uintptr_t>(t.G) % (4 * sizeof(GT)) == 0) &&
-              (reinterpret_cast<uintptr_t>(t.E) % 16 == 0);
+        // 16-byte accesses; the deferred form reads and writes two columns per lane
+        const uint32_t w = (g.defer && with_grad) ? 2u : 4u;
+        if (w == 2u) vec = vec && t.ldg < (1ull << 28);       // its per-lane offsets are 32-bit
+        vec = vec && (t.n % w == 0) && (t.ldg % w == 0) &&
+              (reinterpret_cast<uintptr_t>(t.G) % (w * sizeof(GT)) == 0) &&
+              (reinterpret_cast<uintptr_t>(t.E) % (4 * w) == 0);
         // algorithmic traffic: read G (if any) and E_old (if any), write D
         const double mn = static_cast<double>(t.m) * t.n;
         bytes += mn * ((with_grad ? sizeof(GT) : 0) + (t.e_zero ? 0 : 4) + 4);
         flops += 2.0 * mn * g.r;
     }
-    if (vec)
+    if (g.defer && with_grad) {
+        // D_prev is read where the other form reads E_old: the same bytes; two products per element
+        constexpr size_t lds = deferred_lds<NP, RT>();
+        if (vec)
+            EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+        else
+            EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+    } else if (vec)
         EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops, (k_pass_p<NP, RT, true><<<blocks, 256, 0, st>>>(g)));
     else
         EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops, (k_pass_p<NP, RT, false><<<blocks, 256, 0, st>>>(g)));
@@ -1586,14 +1910,19 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
         blocks += RB * JS;
         vec = vec && (t.n % 2 == 0) && (t.ldo % 2 == 0) && (reinterpret_cast<uintptr_t>(t.E) % 8 == 0) &&
               (reinterpret_cast<uintptr_t>(t.out) % (2 * esz) == 0);
-        // algorithmic traffic: read D, write E_new, write M^
-        bytes += static_cast<double>(t.m) * t.n * (8 + esz);
+        // algorithmic traffic: write M^ (if asked for); read D and write E_new unless deferred
+        bytes += static_cast<double>(t.m) * t.n * ((g.defer ? 0 : 8) + (t.out ? esz : 0));
         flops += 2.0 * t.m * t.n * g.r;
     }
-    if (vec)
-        EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops, (k_decompress<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+    if (g.defer) {
+        if (vec)
+            EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops, (k_decompress<NP, RT, true, true><<<blocks, 256, lds, st>>>(g)));
+        else
+            EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops, (k_decompress<NP, RT, false, true><<<blocks, 256, lds, st>>>(g)));
+    } else if (vec)
+        EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops, (k_decompress<NP, RT, true, false><<<blocks, 256, lds, st>>>(g)));
     else
-        EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops, (k_decompress<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+        EDGC_LAUNCH(ctx, st, KID_DECOMPRESS, bytes, flops, (k_decompress<NP, RT, false, false><<<blocks, 256, lds, st>>>(g)));
     EDGC_HIP_TRY(ctx, hipGetLastError());
     return EDGC_OK;
 }

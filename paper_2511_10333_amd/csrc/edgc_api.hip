@@ -406,6 +406,22 @@ int check_batch_tensor(edgc_ctx* ctx, const edgc_tensor& d, uint32_t i, edgc_dty
     return 0;
 }
 
+// The deferred flag of a call: every compressed tensor must carry the same one.
+// Returns 0 / 1, or < 0 when the descriptors disagree or the flag is neither.
+int batch_deferred(edgc_ctx* ctx, const edgc_tensor* tensors, const std::vector<int>& kind)
+{
+    int flag = -1;
+    for (size_t i = 0; i < kind.size(); ++i) {
+        if (kind[i] == 1) continue;
+        if (tensors[i].deferred > 1) return fail(ctx, EDGC_EINVAL, "edgc_tensor.deferred must be 0 or 1");
+        const int f = static_cast<int>(tensors[i].deferred);
+        if (flag >= 0 && f != flag)
+            return fail(ctx, EDGC_EINVAL, "the tensors of one batch call must agree in `deferred`");
+        flag = f;
+    }
+    return flag < 0 ? 0 : flag;
+}
+
 }  // namespace
 
 extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
@@ -423,16 +439,20 @@ extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, ui
         kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, true, false);
         if (kind[i] < 0) return kind[i];
     }
+    const int defer = batch_deferred(ctx, tensors, kind);
+    if (defer < 0) return defer;
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Group g{};
     TensorScratch cap[kMaxGroup];
     g.r = r;
+    g.defer = static_cast<uint32_t>(defer);
     auto flush = [&]() -> int {
         if (g.count == 0) return EDGC_OK;
         const int rc = launch_compress(ctx, g, cap, dtype, power_iters, st);
         g = Group{};
         g.r = r;
+        g.defer = static_cast<uint32_t>(defer);
         return rc;
     };
     for (uint32_t i = 0; i < count; ++i) {
@@ -450,8 +470,12 @@ extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, ui
     return flush();
 }
 
-extern "C" int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
-                                     edgc_dtype dtype, uint32_t r, void* hip_stream)
+namespace {
+
+// Shared by edgc_decompress_batch and edgc_residual_materialize_batch (with_out = false: the
+// reconstruction is not written, E = D - M^ alone).
+int decompress_batch_impl(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count, edgc_dtype dtype,
+                          uint32_t r, bool with_out, void* hip_stream)
 {
     if (!ctx) return EDGC_EINVAL;
     if (count == 0) return EDGC_OK;
@@ -461,35 +485,57 @@ extern "C" int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, 
     if (count > ctx->batch.size()) return fail(ctx, EDGC_EINVAL, "more tensors than reserved batch slots");
     std::vector<int> kind(count);
     for (uint32_t i = 0; i < count; ++i) {
-        kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, false, true);
+        kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, false, with_out);
         if (kind[i] < 0) return kind[i];
-        if (kind[i] == 1 && !tensors[i].grad) return fail(ctx, EDGC_EINVAL, "null gradient pointer in batch");
+        if (with_out && kind[i] == 1 && !tensors[i].grad) return fail(ctx, EDGC_EINVAL, "null gradient pointer in batch");
+    }
+    int defer = 0;
+    if (with_out) {
+        defer = batch_deferred(ctx, tensors, kind);
+        if (defer < 0) return defer;
     }
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Group g{};
     g.r = r;
+    g.defer = static_cast<uint32_t>(defer);
     auto flush = [&]() -> int {
         if (g.count == 0) return EDGC_OK;
         const int rc = launch_decompress(ctx, g, dtype, st);
         g = Group{};
         g.r = r;
+        g.defer = static_cast<uint32_t>(defer);
         return rc;
     };
     const uint32_t esz = dtype == EDGC_F32 ? 4 : 2;
     for (uint32_t i = 0; i < count; ++i) {
         const edgc_tensor& d = tensors[i];
         if (kind[i] == 1) {                      // sent as it stands: hand the gradient on
-            if (int rc = launch_copy_rows(ctx, d.grad, d.ld, d.grad_out, d.ld_out, d.m, d.n, esz, st)) return rc;
+            if (with_out)
+                if (int rc = launch_copy_rows(ctx, d.grad, d.ld, d.grad_out, d.ld_out, d.m, d.n, esz, st)) return rc;
             continue;
         }
         TensorArgs& t = g.t[g.count];
         t.E = d.residual; t.Q = d.Q; t.ldq = d.ldq; t.P = d.P; t.ldp = d.ldp;
-        t.out = d.grad_out; t.ldo = d.ld_out; t.m = d.m; t.n = d.n;
+        t.out = with_out ? d.grad_out : nullptr; t.ldo = with_out ? d.ld_out : 0; t.m = d.m; t.n = d.n;
         if (++g.count == kMaxGroup)
             if (int rc = flush()) return rc;
     }
     return flush();
+}
+
+}  // namespace
+
+extern "C" int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                     edgc_dtype dtype, uint32_t r, void* hip_stream)
+{
+    return decompress_batch_impl(ctx, tensors, count, dtype, r, true, hip_stream);
+}
+
+extern "C" int edgc_residual_materialize_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                               edgc_dtype dtype, uint32_t r, void* hip_stream)
+{
+    return decompress_batch_impl(ctx, tensors, count, dtype, r, false, hip_stream);
 }
 
 // Sec. IV-D-1 asks for T_compress and T_decompress measured on the system at hand: time this

@@ -70,6 +70,8 @@ struct Group {
                             //    the Q-pass reads D, and the P-pass E_old, with non-temporal loads.
                             //    0: both are ordinary loads, so that D is still cached when the
                             //    decompress reads it again and E_new when the next step's P-pass does
+    uint32_t defer;         // 1: deferred subtraction: the residual buffer holds D between steps and the
+                            //    next P-pass subtracts M^ = P^ Q^T itself; the decompress only writes M^
     TensorArgs t[kMaxGroup];
 };
 

@@ -21,11 +21,14 @@ def _widen(a):
 class Stage:
     """Host and device state of a list of gradient tensors that share one rank."""
 
-    def __init__(self, shapes, r, dtype, seed=0, ragged_ld=False, mats=None):
-        """``mats``: ready-made 2-D gradients (host arrays) instead of generated ones."""
+    def __init__(self, shapes, r, dtype, seed=0, ragged_ld=False, mats=None, deferred=False, power_iters=1,
+                 signal_rank=48, decay=0.9):
+        """``mats``: ready-made 2-D gradients (host arrays) instead of generated ones.
+        ``deferred``: the residual buffers keep D between steps (edgc_tensor.deferred)."""
         if mats is not None:
             shapes = [g.shape for g in mats]
         self.shapes, self.r, self.dtype = shapes, r, dtype
+        self.deferred, self.power_iters, self.steps = deferred, power_iters, 0
         self.ctx = edgc.Context(0, max_rank=128, max_rows=64, max_cols=64)    # own scratch unused here
         self.ctx.reserve_batch([s if len(s) == 2 else (1, s[0]) for s in shapes])
         tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -40,7 +43,7 @@ class Stage:
                 continue
             m, n = s
             g = mats[i] if mats is not None else \
-                gen.lowrank_plus_noise(m, n, min(m, n, 48), 0.9, 1e-4, seed + i, dtype=dtype)
+                gen.lowrank_plus_noise(m, n, min(m, n, signal_rank), decay, 1e-4, seed + i, dtype=dtype)
             self.G.append(g)
             if edgc.tensor_bypassed(m, n, r):
                 self.Q.append(None); self.E.append(None)
@@ -64,9 +67,12 @@ class Stage:
         return self.Q[i] is not None
 
     def step_device(self):
-        self.ctx.compress_batch(self.t, self.r)
-        self.ctx.decompress_batch(self.t, self.r)
+        # a deferred compress expects D and the factors of the step before: not on the first step
+        self.ctx.compress_batch(self.t, self.r, power_iters=self.power_iters,
+                                deferred=self.deferred and self.steps > 0)
+        self.ctx.decompress_batch(self.t, self.r, deferred=self.deferred)
         torch.cuda.synchronize()
+        self.steps += 1
         for t in self.t:
             t.residual_is_zero = False
 
@@ -87,6 +93,11 @@ class Stage:
             assert rel_fro(to_host(t.P)[:, :r], Po) <= tol, i
             assert rel_fro(to_host(t.Q)[:, :r], Qo) <= tol, i
             assert rel_fro(_widen(to_host(t.grad_out)), _widen(out_o)) <= tol, i
+            if self.deferred:                                 # the buffer keeps D; E stays in factored form
+                assert np.linalg.norm(to_host(t.residual).astype(np.float64) - Do) <= tol * nD, i
+                if first:
+                    assert np.array_equal(to_host(t.residual), Do.astype(np.float32)), i
+                continue
             assert np.linalg.norm(to_host(t.residual).astype(np.float64) - E_o) <= tol * nD, i
             # D = M^ + E_new on the device (first step: its D is the oracle's D bit for bit)
             if first:
