@@ -35,12 +35,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this command (see profiles/), keyed by (workload, kernel, batch groups); None for a
+# runs of this command (see profiles/), keyed by (workload, kernel, batch groups, form of the residual); None for a
 # layout that has no such run recorded.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_pass_p_cfg2_traffic.md: (2 x FETCH_SIZE + WRITE_SIZE) KiB per launch, the factors
+    # profiles/k_pass_p_cfg2_explicit_residual_traffic.md: (2 x FETCH_SIZE + WRITE_SIZE) KiB per launch, the factors
     # coming from the same counters on a plain 1 GiB device copy (FETCH_SIZE reads half the bytes)
-    ("cfg2_gpt_h2048_r16", "k_pass_p", 2): int((2 * 9.764e4 + 1.125e5) * 1024),
+    ("cfg2_gpt_h2048_r16", "k_pass_p", 2, "explicit"): int((2 * 9.764e4 + 1.125e5) * 1024),
 }
 
 
@@ -332,7 +332,8 @@ def main() -> int:
     achieved = ds["bytes"] / (ds["total_ms"] * 1e-3) / 1e9
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, dom, len(groups))),
+                    traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, dom, len(groups),
+                                                        "deferred" if deferred else "explicit")),
                     avg_launch_us=round(ds["total_ms"] * 1e3 / ds["launches"], 2),
                     algorithmic_bytes_per_launch=round(ds["bytes"] / ds["launches"]),
                     timing="HIP events around every launch (minus %.2f us, what an empty event pair reads); "
