@@ -9,6 +9,9 @@
 //   k_pass_q        Q_partial = D^T P^                                (split over rows)
 //   k_reduce_q      Q = sum of partials
 //   k_decompress    M^ = P^ Q^T -> grad_out, E_new = D - M^
+//   k_pass_p_deferred   the P-pass when the residual buffer kept D of the step before instead of E
+//                   (batched calls, deferred = 1): E = D_prev - P^_prev Q_prev^T is formed on the
+//                   way and k_decompress then only writes M^
 //
 // All contractions run on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.
 // bf16 gradients use one bf16 plane per operand (operands rounded to nearest
