@@ -290,15 +290,18 @@ int edgc_entropy_due(uint64_t iter_in_window, uint32_t period);
  * call bracketed by HIP events on hip_stream.  costs_out[i] (host) receives
  * the rank, the mean time of either call in seconds, and bytes_compressed =
  * (m + n) * rank * 4 (P and Q in fp32, what the two exchanges of a data-
- * parallel step would carry).  Overwrites residual, Q, P and grad_out;
- * synchronises the stream; not a hot-path call.
- * Errors: those of edgc_compress / edgc_decompress, EDGC_EINVAL for reps == 0
- * or n_ranks == 0. */
+ * parallel step would carry).  deferred = 1 times the deferred form of the
+ * residual instead (section 5: the timed compress subtracts P Q^T of the round
+ * before on the way, the decompress only writes grad_out), which is what a
+ * caller of the batched calls with deferred = 1 runs.  Overwrites residual, Q,
+ * P and grad_out; synchronises the stream; not a hot-path call.
+ * Errors: those of edgc_compress / edgc_decompress, EDGC_EINVAL for reps == 0,
+ * n_ranks == 0 or deferred not 0 or 1. */
 int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m,
                             uint32_t n, uint64_t ld, float* residual, float* Q, uint32_t ldq,
                             float* P, uint32_t ldp, void* grad_out, const uint32_t* ranks,
-                            uint32_t n_ranks, uint32_t reps, edgc_rank_cost* costs_out,
-                            void* hip_stream);
+                            uint32_t n_ranks, uint32_t reps, int deferred,
+                            edgc_rank_cost* costs_out, void* hip_stream);
 
 /* ------------------------------------------------------------------------
  * 5. Batched calls: every gradient tensor of a pipeline stage in one launch

@@ -104,7 +104,7 @@ def load_library() -> C.CDLL:
     L.edgc_entropy_due.argtypes = [u64, u32]
     L.edgc_measure_rank_costs.restype = i32
     L.edgc_measure_rank_costs.argtypes = [vp, vp, i32, u32, u32, u64, vp, vp, u32, vp, u32, vp,
-                                          C.POINTER(u32), u32, u32, C.POINTER(_RankCost), vp]
+                                          C.POINTER(u32), u32, u32, i32, C.POINTER(_RankCost), vp]
     L.edgc_tensor_bypassed.restype = i32
     L.edgc_tensor_bypassed.argtypes = [u32, u32, u32]
     L.edgc_reserve_batch.restype = i32
@@ -435,16 +435,17 @@ class Context:
         self._check(rc, "edgc_decompress")
 
     def measure_rank_costs(self, grad, residual, Q, P, grad_out, ranks: Sequence[int], reps: int = 5,
-                           stream=None) -> List[RankCost]:
+                           stream=None, deferred: bool = False) -> List[RankCost]:
         """edgc_measure_rank_costs: times compress and decompress at each rank on these buffers
-        (all overwritten except grad); synchronises the stream."""
+        (all overwritten except grad); synchronises the stream.  ``deferred``: time the deferred
+        form of the residual."""
         m, n = grad.shape
         rk = (C.c_uint32 * max(len(ranks), 1))(*[int(r) for r in ranks])
         out = (_RankCost * max(len(ranks), 1))()
         rc = self._L.edgc_measure_rank_costs(
             self._h, grad.data_ptr(), _dtype_code(grad), m, n, grad.stride(0), residual.data_ptr(),
             Q.data_ptr(), Q.shape[1], P.data_ptr(), P.shape[1], grad_out.data_ptr(), rk, len(ranks),
-            reps, out, _stream_handle(stream))
+            reps, 1 if deferred else 0, out, _stream_handle(stream))
         self._check(rc, "edgc_measure_rank_costs")
         return [RankCost(int(c.rank), c.t_compress, c.t_decompress, c.bytes_compressed)
                 for c in list(out)[:len(ranks)]]

@@ -23,7 +23,7 @@ def block_shapes(hidden: int):
     return [(hidden, 3 * hidden), (hidden, hidden), (hidden, 4 * hidden), (4 * hidden, hidden)]
 
 
-def measure_block(hidden: int, dtype: torch.dtype, ranks, reps: int, seed: int = 0):
+def measure_block(hidden: int, dtype: torch.dtype, ranks, reps: int, seed: int = 0, deferred: bool = True):
     """Sum of the per-matrix costs over the four matrices of a block, per rank."""
     r_cap = max(ranks)
     total = [RankCost(r, 0.0, 0.0, 0.0) for r in ranks]
@@ -35,7 +35,7 @@ def measure_block(hidden: int, dtype: torch.dtype, ranks, reps: int, seed: int =
         out = torch.empty((m, n), device="cuda", dtype=dtype)
         Q = torch.empty((n, r_cap), device="cuda")
         P = torch.empty((m, r_cap), device="cuda")
-        for acc, c in zip(total, ctx.measure_rank_costs(g, res, Q, P, out, ranks, reps)):
+        for acc, c in zip(total, ctx.measure_rank_costs(g, res, Q, P, out, ranks, reps, deferred=deferred)):
             acc.t_compress += c.t_compress
             acc.t_decompress += c.t_decompress
             acc.bytes_compressed += c.bytes_compressed
@@ -51,13 +51,15 @@ def main(argv=None):
     ap.add_argument("--gbps", type=float, nargs="+", default=[32.0, 100.0, 400.0, 8568.0],
                     help="network bandwidths in Gbit/s (8568 = seven xGMI links of 153 GB/s)")
     ap.add_argument("--reps", type=int, default=10)
+    ap.add_argument("--explicit-residual", action="store_true",
+                    help="time the form that stores E between steps instead of the deferred one")
     ap.add_argument("--divisor", type=float, default=4.0, help="r_min = ceil(r_max / divisor), 4..6")
     a = ap.parse_args(argv)
     dtype = torch.float32 if a.dtype == "f32" else torch.bfloat16
-    costs = measure_block(a.hidden, dtype, sorted(a.ranks), a.reps)
+    costs = measure_block(a.hidden, dtype, sorted(a.ranks), a.reps, deferred=not a.explicit_residual)
     elem = 4 if a.dtype == "f32" else 2
     d_orig = float(sum(m * n for m, n in block_shapes(a.hidden)) * elem)
-    report = {"hidden": a.hidden, "dtype": a.dtype, "bytes_original": d_orig, "reps": a.reps,
+    report = {"hidden": a.hidden, "dtype": a.dtype, "residual": "explicit" if a.explicit_residual else "deferred", "bytes_original": d_orig, "reps": a.reps,
               "costs": [{"rank": c.rank, "t_compress_us": 1e6 * c.t_compress,
                          "t_decompress_us": 1e6 * c.t_decompress,
                          "bytes_compressed": c.bytes_compressed} for c in costs],

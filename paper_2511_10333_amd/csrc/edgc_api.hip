@@ -299,9 +299,13 @@ static void own_scratch(edgc_ctx* ctx, TensorArgs& t, TensorScratch& cap)
     cap.gram_part_elems = s.gram_part_elems;
 }
 
-extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
-                             uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
-                             float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, void* hip_stream)
+namespace {
+
+// The single-tensor calls with the deferred flag of the batched ones (a group of one on the
+// context's own scratch); the public single-tensor entry points pass 0.
+int compress_one(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
+                 uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
+                 float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, uint32_t defer, void* hip_stream)
 {
     if (!ctx) return EDGC_EINVAL;
     if (!grad || !residual) return fail(ctx, EDGC_EINVAL, "null grad or residual");
@@ -314,6 +318,7 @@ extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, 
     Group g{};
     g.count = 1;
     g.r = r;
+    g.defer = defer;
     TensorArgs& t = g.t[0];
     t.G = grad; t.ldg = ld; t.E = residual; t.e_zero = residual_is_zero ? 1 : 0;
     t.Q = Q; t.ldq = ldq; t.P = P; t.ldp = ldp; t.m = m; t.n = n;
@@ -322,9 +327,9 @@ extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, 
     return launch_compress(ctx, g, &cap, dtype, power_iters, static_cast<hipStream_t>(hip_stream));
 }
 
-extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
-                               uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
-                               edgc_dtype dtype, uint64_t ld, void* hip_stream)
+int decompress_one(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                   uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
+                   edgc_dtype dtype, uint64_t ld, uint32_t defer, void* hip_stream)
 {
     if (!ctx) return EDGC_EINVAL;
     if (!residual || !grad_out) return fail(ctx, EDGC_EINVAL, "null residual or grad_out");
@@ -336,10 +341,28 @@ extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, cons
     Group g{};
     g.count = 1;
     g.r = r;
+    g.defer = defer;
     TensorArgs& t = g.t[0];
     t.E = residual; t.Q = const_cast<float*>(Q); t.ldq = ldq; t.P = const_cast<float*>(P); t.ldp = ldp;
     t.out = grad_out; t.ldo = ld; t.m = m; t.n = n;
     return launch_decompress(ctx, g, dtype, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // namespace
+
+extern "C" int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
+                             uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
+                             float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, void* hip_stream)
+{
+    return compress_one(ctx, grad, dtype, m, n, ld, residual, residual_is_zero, Q, ldq, P, ldp, r, power_iters, 0,
+                        hip_stream);
+}
+
+extern "C" int edgc_decompress(edgc_ctx* ctx, const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
+                               uint32_t m, uint32_t n, uint32_t r, float* residual, void* grad_out,
+                               edgc_dtype dtype, uint64_t ld, void* hip_stream)
+{
+    return decompress_one(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld, 0, hip_stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -543,10 +566,12 @@ extern "C" int edgc_residual_materialize_batch(edgc_ctx* ctx, const edgc_tensor*
 extern "C" int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m,
                                        uint32_t n, uint64_t ld, float* residual, float* Q, uint32_t ldq,
                                        float* P, uint32_t ldp, void* grad_out, const uint32_t* ranks,
-                                       uint32_t n_ranks, uint32_t reps, edgc_rank_cost* costs_out,
-                                       void* hip_stream)
+                                       uint32_t n_ranks, uint32_t reps, int deferred,
+                                       edgc_rank_cost* costs_out, void* hip_stream)
 {
     if (!ctx) return EDGC_EINVAL;
+    if (deferred != 0 && deferred != 1) return fail(ctx, EDGC_EINVAL, "deferred must be 0 or 1");
+    const uint32_t defer = static_cast<uint32_t>(deferred);
     if (!ranks || !costs_out || n_ranks == 0 || reps == 0)
         return fail(ctx, EDGC_EINVAL, "null ranks/costs_out, n_ranks == 0 or reps == 0");
     if (grad_out == grad) return fail(ctx, EDGC_EINVAL, "grad_out must not alias grad while measuring");
@@ -570,10 +595,12 @@ extern "C" int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dty
         rc = edgc_init_q(ctx, Q, n, ldq, 0, r, 0x5eedULL + r, hip_stream);
         for (uint32_t rep = 0; rc == EDGC_OK && rep <= reps; ++rep) {
             if (!hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) break;
-            rc = edgc_compress(ctx, grad, dtype, m, n, ld, residual, rep == 0, Q, ldq, P, ldp, r, 1, hip_stream);
+            // a deferred compress needs D and the factors of a step before it: not in round 0
+            rc = compress_one(ctx, grad, dtype, m, n, ld, residual, rep == 0, Q, ldq, P, ldp, r, 1,
+                              rep == 0 ? 0u : defer, hip_stream);
             if (rc != EDGC_OK) break;
             if (!hip_ok(hipEventRecord(ev[1], st), "hipEventRecord")) break;
-            rc = edgc_decompress(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld, hip_stream);
+            rc = decompress_one(ctx, P, ldp, Q, ldq, m, n, r, residual, grad_out, dtype, ld, defer, hip_stream);
             if (rc != EDGC_OK) break;
             if (!hip_ok(hipEventRecord(ev[2], st), "hipEventRecord")) break;
             if (!hip_ok(hipEventSynchronize(ev[2]), "hipEventSynchronize")) break;

@@ -254,27 +254,28 @@ def test_stage_entropy_over_separate_buffers(dtype, stride, chunk, bins):
 # the batched calls under HIP graph capture: no allocation, no synchronisation, no memset
 # node inside them, so a captured step replays like the eager one
 # ---------------------------------------------------------------------------
-def test_batched_step_replays_from_a_hip_graph():
+@pytest.mark.parametrize("deferred", [False, True])
+def test_batched_step_replays_from_a_hip_graph(deferred):
     shapes, r = [(384, 512), (256, 640), (100,)], 8
-    eager = Stage(shapes, r, "f32", seed=31)
-    graphed = Stage(shapes, r, "f32", seed=31)
+    eager = Stage(shapes, r, "f32", seed=31, deferred=deferred)
+    graphed = Stage(shapes, r, "f32", seed=31, deferred=deferred)
     for st in (eager, graphed):                       # first step eagerly: it starts from a zero residual
         st.step_device()
     side = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
     torch.cuda.synchronize()
-    keep = [(t.residual.clone(), t.Q.clone()) if t.residual is not None else None for t in graphed.t]
+    keep = [(t.residual.clone(), t.Q.clone(), t.P.clone()) if t.residual is not None else None for t in graphed.t]
     ent_out = torch.zeros(edgc.binding.ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True)
     flats = [t.grad.view(-1) for t in graphed.t]
     with torch.cuda.graph(g, stream=side, capture_error_mode="thread_local"):
         graphed.ctx.entropy_estimate_async(flats, 10, 64, 3, 0, 256, ent_out, stream=side)
-        graphed.ctx.compress_batch(graphed.t, r, stream=side)
-        graphed.ctx.decompress_batch(graphed.t, r, stream=side)
+        graphed.ctx.compress_batch(graphed.t, r, stream=side, deferred=deferred)
+        graphed.ctx.decompress_batch(graphed.t, r, stream=side, deferred=deferred)
     torch.cuda.synchronize()
     ent_want = graphed.ctx.entropy_estimate(flats, 10, 64, 3, 0, 256)
     for t, k in zip(graphed.t, keep):                 # capture runs nothing, but make the state explicit
         if k is not None:
-            t.residual.copy_(k[0]); t.Q.copy_(k[1])
+            t.residual.copy_(k[0]); t.Q.copy_(k[1]); t.P.copy_(k[2])
     for step in range(3):
         eager.step_device()
         g.replay()

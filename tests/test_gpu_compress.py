@@ -251,6 +251,15 @@ def test_measure_rank_costs_runs_the_two_calls_and_reports_bytes():
         c.decompress(P2, Q2, 32, res2, out2)
     torch.cuda.synchronize()
     assert torch.equal(res, res2) and torch.equal(out, out2) and torch.equal(P, P2) and torch.equal(Q, Q2)
+    # the deferred form leaves the same factors and reconstruction, and D where the other leaves E;
+    # its decompress only writes, so it is the cheaper of the two
+    res3, out3 = torch.empty_like(res), torch.empty_like(out)
+    Q3, P3 = torch.empty_like(Q), torch.empty_like(P)
+    costs_d = c.measure_rank_costs(gd, res3, Q3, P3, out3, ranks, reps=3, deferred=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out3, out) and torch.equal(P3, P) and torch.equal(Q3, Q)
+    assert torch.equal(res3 - out3, res)
+    assert all(1e-6 < k.t_decompress < 5e-3 and 1e-6 < k.t_compress < 5e-3 for k in costs_d)
     with pytest.raises(edgc.EdgcError):
         c.measure_rank_costs(gd, res, Q, P, gd, ranks, reps=3)           # aliasing refused
     with pytest.raises(edgc.EdgcError):
