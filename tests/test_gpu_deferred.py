@@ -153,3 +153,38 @@ def test_descriptors_of_one_call_must_agree():
     arr[1].deferred = 2
     arr[0].deferred = 2
     assert L.edgc_compress_batch(st.ctx._h, arr, 2, code, 8, 1, None) == edgc.binding.EINVAL
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_deferred_with_strided_gradient_rows_and_more_tensors_than_one_launch_holds(dtype):
+    """Gradient rows embedded in wider buffers (ld > n), and 21 tensors, which go through the
+    kernels as a launch of 16 and one of 5."""
+    st = Stage([(200, 328), (192, 192), (333, 100)], 24, dtype, seed=9, ragged_ld=True, deferred=True)
+    for _ in range(3):
+        st.step_device()
+        st.step_oracle_and_compare()
+    many = Stage([(64 + 8 * i, 96 + 4 * i) for i in range(21)], 8, dtype, seed=11, deferred=True)
+    for _ in range(2):
+        many.step_device()
+        many.step_oracle_and_compare()
+
+
+def test_deferred_hidden_5120_bf16_block_full_size():
+    """The hidden-5120 bf16 block at rank 64 in the bench's two-group layout, deferred form:
+    two steps, the second of which subtracts the first one's reconstruction on the way."""
+    name = "cfg4_gpt_h5120_bf16"
+    w = gen.WORKLOADS[name]
+    mats = [g for _, g in gen.workload_matrices(name)]
+    order = sorted(range(len(mats)), key=lambda i: -mats[i].size)
+    members, load = [[], []], [0, 0]
+    for i in order:
+        k = load.index(min(load))
+        members[k].append(i)
+        load[k] += mats[i].size
+    for idx in members:
+        st = Stage(None, w["rank"], w["dtype"], seed=w["seed"], mats=[mats[i] for i in sorted(idx)], deferred=True)
+        for _ in range(2):
+            st.step_device()
+            st.step_oracle_and_compare()
+        del st
+        torch.cuda.empty_cache()
