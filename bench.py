@@ -42,7 +42,7 @@ MEASURED_TRAFFIC_BYTES = {
     # coming from the same counters on a plain 1 GiB device copy (FETCH_SIZE reads half the bytes)
     ("cfg2_gpt_h2048_r16", "k_pass_p", 2, "explicit"): int((2 * 9.764e4 + 1.125e5) * 1024),
     # profiles/k_pass_p_deferred_cfg2_traffic.md, the same way
-    ("cfg2_gpt_h2048_r16", "k_pass_p", 2, "deferred"): int((2 * 1.0134e5 + 1.1251e5) * 1024),
+    ("cfg2_gpt_h2048_r16", "k_pass_p_deferred", 2, "deferred"): int((2 * 1.0134e5 + 1.1251e5) * 1024),
 }
 
 
@@ -346,7 +346,8 @@ def main() -> int:
     mfma = {k: dict(tflops=v["tflops"], frac_of_bf16_peak=round(v["tflops"] / BF16_MFMA_PEAK_TFLOPS, 4),
                     flop_per_byte=round(stats[k]["flops"] / stats[k]["bytes"], 2),
                     ceiling=round(min(1.0, stats[k]["flops"] / stats[k]["bytes"] / ridge), 4))
-            for k, v in kernels.items() if k in ("k_pass_p", "k_pass_q", "k_decompress") and v["tflops"]}
+            for k, v in kernels.items()
+            if k in ("k_pass_p", "k_pass_p_deferred", "k_pass_q", "k_decompress") and v["tflops"]}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

@@ -1679,7 +1679,7 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         blocks += RB * S;
         // 16-byte accesses; the deferred form reads and writes two columns per lane
         const uint32_t w = (g.defer && with_grad) ? 2u : 4u;
-        if (w == 2u) vec = vec && t.ldg < (1ull << 28);       // its per-lane offsets are 32-bit
+        if (w == 2u) vec = vec && t.ldg < (1ull << 28) && t.n < (1u << 28);   // its per-lane offsets are 32-bit
         vec = vec && (t.n % w == 0) && (t.ldg % w == 0) &&
               (reinterpret_cast<uintptr_t>(t.G) % (w * sizeof(GT)) == 0) &&
               (reinterpret_cast<uintptr_t>(t.E) % (4 * w) == 0);
@@ -1692,9 +1692,9 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         // D_prev is read where the other form reads E_old: the same bytes; two products per element
         constexpr size_t lds = deferred_lds<NP, RT>();
         if (vec)
-            EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+            EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
         else
-            EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+            EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
     } else if (vec)
         EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops, (k_pass_p<NP, RT, true><<<blocks, 256, 0, st>>>(g)));
     else

@@ -11,7 +11,8 @@ using namespace edgc;
 namespace edgc {
 const char* const kKernelNames[KID_COUNT] = {
     "k_set_range", "k_minmax", "k_hist", "k_sample_indices", "k_init_q", "k_pass_p",
-    "k_reduce_gram", "k_gram_sum", "k_chol", "k_apply", "k_pass_q", "k_reduce_q", "k_decompress"};
+    "k_reduce_gram", "k_gram_sum", "k_chol", "k_apply", "k_pass_q", "k_reduce_q", "k_decompress",
+    "k_pass_p_deferred"};
 }
 
 namespace {

@@ -95,7 +95,7 @@ struct BatchSlot {
 enum KernelId {
     KID_SET_RANGE = 0, KID_MINMAX, KID_HIST, KID_SAMPLE_IDX, KID_INIT_Q, KID_PASS_P,
     KID_REDUCE_GRAM, KID_GRAM_SUM, KID_CHOL, KID_APPLY, KID_PASS_Q, KID_REDUCE_Q, KID_DECOMPRESS,
-    KID_COUNT
+    KID_PASS_P_DEFERRED, KID_COUNT
 };
 extern const char* const kKernelNames[KID_COUNT];
 
