@@ -380,6 +380,22 @@ int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t coun
                         uint32_t r, uint32_t power_iters, void* hip_stream);
 int edgc_decompress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
                           edgc_dtype dtype, uint32_t r, void* hip_stream);
+/* The compress in two phases, for a data-parallel step that exchanges the factors between them
+ * (PowerSGD's two all-reduces, Sec. II-B; the inequality of Sec. IV-D-1 prices exactly these
+ * two messages):
+ *   edgc_compress_p_batch: error-feedback add and P-pass.  residual <- D, P <- D Q, NOT
+ *     orthonormalised (what the ranks average).  Reads what edgc_compress_batch reads.
+ *   edgc_compress_q_batch: orthonormalises P as it stands in the caller's buffer, then the
+ *     Q-pass: P <- P^, Q <- D^T P^ (what the ranks average next).  Reads residual (D), P; grad,
+ *     residual_is_zero and deferred are ignored.
+ * The first followed by the second, with P untouched in between, is edgc_compress_batch with
+ * power_iters = 1, bit for bit.  With deferred = 1 the caller stores the averaged Q back before
+ * the decompress, so that the buffers hold the factors the reconstruction was formed from.
+ * Errors: as for edgc_compress_batch. */
+int edgc_compress_p_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count, edgc_dtype dtype,
+                          uint32_t r, void* hip_stream);
+int edgc_compress_q_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count, edgc_dtype dtype,
+                          uint32_t r, void* hip_stream);
 /* reads residual, P, Q of every compressed tensor; writes residual; `deferred` and the gradient
  * pointers of the descriptors are ignored.  r and dtype: those of the step that left P and Q. */
 int edgc_residual_materialize_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,

@@ -113,6 +113,10 @@ def load_library() -> C.CDLL:
     L.edgc_compress_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, u32, vp]
     L.edgc_decompress_batch.restype = i32
     L.edgc_decompress_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
+    L.edgc_compress_p_batch.restype = i32
+    L.edgc_compress_p_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
+    L.edgc_compress_q_batch.restype = i32
+    L.edgc_compress_q_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
     L.edgc_residual_materialize_batch.restype = i32
     L.edgc_residual_materialize_batch.argtypes = [vp, C.POINTER(_Tensor), u32, i32, u32, vp]
     L.edgc_init_q.restype = i32
@@ -486,6 +490,18 @@ class Context:
         rc = self._L.edgc_compress_batch(self._h, arr, len(tensors), code, r, power_iters,
                                          _stream_handle(stream))
         self._check(rc, "edgc_compress_batch")
+
+    def compress_p_batch(self, tensors: Sequence[Tensor], r: int, stream=None, deferred: bool = False) -> None:
+        """edgc_compress_p_batch: error-feedback add and P-pass; P is left un-orthonormalised."""
+        arr, code = self._marshal(tensors, deferred)
+        rc = self._L.edgc_compress_p_batch(self._h, arr, len(tensors), code, r, _stream_handle(stream))
+        self._check(rc, "edgc_compress_p_batch")
+
+    def compress_q_batch(self, tensors: Sequence[Tensor], r: int, stream=None) -> None:
+        """edgc_compress_q_batch: orthonormalise P as it stands, then the Q-pass."""
+        arr, code = self._marshal(tensors)
+        rc = self._L.edgc_compress_q_batch(self._h, arr, len(tensors), code, r, _stream_handle(stream))
+        self._check(rc, "edgc_compress_q_batch")
 
     def decompress_batch(self, tensors: Sequence[Tensor], r: int, stream=None, deferred: bool = False) -> None:
         """edgc_decompress_batch over a list of :class:`Tensor`; ``deferred``: only the

@@ -501,6 +501,23 @@ __global__ __launch_bounds__(256) void k_reduce_gram(const Group grp, uint32_t R
     }
 }
 
+// The factor P as the caller holds it (m x ldp) in the layout of ONE column split of the
+// P-pass, [row][RP] with zeros from column r on: what the orthonormalisation starts from when
+// P comes from outside (the second phase of a split call: P after an exchange between ranks).
+__global__ __launch_bounds__(256) void k_p_to_part(const Group grp, uint32_t RP)
+{
+    const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
+    const uint32_t q4 = RP / 4;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x - ta.first) * 256 + threadIdx.x;
+    if (i >= static_cast<uint64_t>(ta.m) * q4) return;
+    const uint32_t row = static_cast<uint32_t>(i / q4), c4 = static_cast<uint32_t>(i % q4) * 4;
+    const float* src = ta.P + static_cast<size_t>(row) * ta.ldp + c4;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (c4 + e < grp.r) ? src[e] : 0.0f;
+    *reinterpret_cast<float4*>(ta.part + static_cast<size_t>(row) * RP + c4) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
 // out[e] = sum over blocks of gp[b][e], in block order within each of four interleaved
 // groups and then over the groups: a fixed tree, so the result is reproducible.
 __global__ __launch_bounds__(256) void k_gram_sum(const Group grps, uint32_t ne)
@@ -1703,8 +1720,10 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     return EDGC_OK;
 }
 
+// sums_only: stop after P = sum of the partials (the first phase of a split call)
 template <int NP>
-static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStream_t st)
+static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStream_t st,
+                              bool sums_only = false)
 {
     const uint32_t r = g.r;
     const uint32_t RP = rank_tiles(r) * 32;
@@ -1741,6 +1760,7 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
         }
     }
     EDGC_HIP_TRY(ctx, hipGetLastError());
+    if (sums_only) return EDGC_OK;
 
     // Gram = sum of the per-block tiles; the Cholesky block only sums a single tile itself
     blocks = 0;
@@ -1850,12 +1870,37 @@ static int run_pass_q(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStre
     return EDGC_OK;
 }
 
+// phase 0: the whole step.  1: error-feedback add, P-pass and the sum of its partials: P = D Q,
+// not orthonormalised.  2: P as it stands in the caller's buffer (after an exchange between
+// ranks, say) is orthonormalised, then the Q-pass.  1 followed by 2 is 0 bit for bit.
 template <int NP, int RT>
 static int compress_impl(edgc_ctx* ctx, Group& g, const TensorScratch* cap, uint32_t power_iters,
-                         hipStream_t st)
+                         int phase, hipStream_t st)
 {
     for (uint32_t i = 0; i < g.count; ++i) g.t[i].m_pad = cdiv(g.t[i].m, 64) * 64;
     g.stream = group_streams(ctx, g);
+    if (phase == 1) {
+        int rc = run_pass_p<NP, RT>(ctx, g, cap, true, st);
+        if (rc != EDGC_OK) return rc;
+        return run_orthonormalise<NP>(ctx, g, cap, st, true);
+    }
+    if (phase == 2) {
+        constexpr uint32_t RP = RT * 32;
+        uint32_t blocks = 0;
+        for (uint32_t i = 0; i < g.count; ++i) {
+            TensorArgs& t = g.t[i];
+            if (cap[i].part_elems < static_cast<uint64_t>(t.m) * RP)
+                return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
+            t.sp = 1;
+            t.first = blocks;
+            blocks += cdiv(static_cast<uint64_t>(t.m) * (RP / 4), 256);
+        }
+        k_p_to_part<<<blocks, 256, 0, st>>>(g, RP);
+        EDGC_HIP_TRY(ctx, hipGetLastError());
+        int rc = run_orthonormalise<NP>(ctx, g, cap, st);
+        if (rc != EDGC_OK) return rc;
+        return run_pass_q<NP, RT, 2>(ctx, g, cap, st);
+    }
     // After the first P-pass the residual buffer holds D; later iterations re-read it
     // with a null gradient (D + 0).
     for (uint32_t it = 0; it < power_iters; ++it) {
@@ -1875,14 +1920,14 @@ static int compress_impl(edgc_ctx* ctx, Group& g, const TensorScratch* cap, uint
 }
 
 int launch_compress(edgc_ctx* ctx, Group& g, const TensorScratch* cap, edgc_dtype dt,
-                    uint32_t power_iters, hipStream_t st)
+                    uint32_t power_iters, hipStream_t st, int phase)
 {
     const int rt = rank_tiles(g.r);
 #define EDGC_DISPATCH(NP_)                                                        \
     switch (rt) {                                                                 \
-    case 1: return compress_impl<NP_, 1>(ctx, g, cap, power_iters, st);           \
-    case 2: return compress_impl<NP_, 2>(ctx, g, cap, power_iters, st);           \
-    default: return compress_impl<NP_, 4>(ctx, g, cap, power_iters, st);          \
+    case 1: return compress_impl<NP_, 1>(ctx, g, cap, power_iters, phase, st);    \
+    case 2: return compress_impl<NP_, 2>(ctx, g, cap, power_iters, phase, st);    \
+    default: return compress_impl<NP_, 4>(ctx, g, cap, power_iters, phase, st);   \
     }
     if (dt == EDGC_BF16) { EDGC_DISPATCH(1) }
     EDGC_DISPATCH(2)

@@ -448,8 +448,11 @@ int batch_deferred(edgc_ctx* ctx, const edgc_tensor* tensors, const std::vector<
 
 }  // namespace
 
-extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
-                                   edgc_dtype dtype, uint32_t r, uint32_t power_iters, void* hip_stream)
+namespace {
+
+// phase: 0 the whole compress, 1 up to P = D Q, 2 from P as it stands (launch_compress)
+int compress_batch_impl(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count, edgc_dtype dtype,
+                        uint32_t r, uint32_t power_iters, int phase, void* hip_stream)
 {
     if (!ctx) return EDGC_EINVAL;
     if (count == 0) return EDGC_OK;
@@ -460,10 +463,10 @@ extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, ui
     if (count > ctx->batch.size()) return fail(ctx, EDGC_EINVAL, "more tensors than reserved batch slots");
     std::vector<int> kind(count);
     for (uint32_t i = 0; i < count; ++i) {
-        kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, true, false);
+        kind[i] = check_batch_tensor(ctx, tensors[i], i, dtype, r, phase != 2, false);
         if (kind[i] < 0) return kind[i];
     }
-    const int defer = batch_deferred(ctx, tensors, kind);
+    const int defer = phase == 2 ? 0 : batch_deferred(ctx, tensors, kind);   // the second phase reads D as it stands
     if (defer < 0) return defer;
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -473,7 +476,7 @@ extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, ui
     g.defer = static_cast<uint32_t>(defer);
     auto flush = [&]() -> int {
         if (g.count == 0) return EDGC_OK;
-        const int rc = launch_compress(ctx, g, cap, dtype, power_iters, st);
+        const int rc = launch_compress(ctx, g, cap, dtype, power_iters, st, phase);
         g = Group{};
         g.r = r;
         g.defer = static_cast<uint32_t>(defer);
@@ -492,6 +495,26 @@ extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, ui
             if (int rc = flush()) return rc;
     }
     return flush();
+}
+
+}  // namespace
+
+extern "C" int edgc_compress_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                   edgc_dtype dtype, uint32_t r, uint32_t power_iters, void* hip_stream)
+{
+    return compress_batch_impl(ctx, tensors, count, dtype, r, power_iters, 0, hip_stream);
+}
+
+extern "C" int edgc_compress_p_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                     edgc_dtype dtype, uint32_t r, void* hip_stream)
+{
+    return compress_batch_impl(ctx, tensors, count, dtype, r, 1, 1, hip_stream);
+}
+
+extern "C" int edgc_compress_q_batch(edgc_ctx* ctx, const edgc_tensor* tensors, uint32_t count,
+                                     edgc_dtype dtype, uint32_t r, void* hip_stream)
+{
+    return compress_batch_impl(ctx, tensors, count, dtype, r, 1, 2, hip_stream);
 }
 
 namespace {

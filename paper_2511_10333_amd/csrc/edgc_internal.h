@@ -216,8 +216,9 @@ int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uin
 int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1,
                   uint64_t seed, hipStream_t st);
 // `g` holds the tensors' pointers, shapes and scratch; the launchers fill in the rest.
+// phase 0: whole step; 1: up to P = D Q (not orthonormalised); 2: orthonormalise P as it stands, Q-pass
 int launch_compress(edgc_ctx* ctx, Group& g, const TensorScratch* cap, edgc_dtype dt,
-                    uint32_t power_iters, hipStream_t st);
+                    uint32_t power_iters, hipStream_t st, int phase = 0);
 int launch_decompress(edgc_ctx* ctx, Group& g, edgc_dtype dt, hipStream_t st);
 int launch_copy_rows(edgc_ctx* ctx, const void* src, uint64_t ld_src, void* dst, uint64_t ld_dst,
                      uint32_t m, uint32_t n, uint32_t elem_bytes, hipStream_t st);
