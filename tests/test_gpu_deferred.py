@@ -188,3 +188,26 @@ def test_deferred_hidden_5120_bf16_block_full_size():
             st.step_oracle_and_compare()
         del st
         torch.cuda.empty_cache()
+
+
+def test_seeded_sweep_of_small_and_ragged_shapes_deferred_equals_explicit():
+    """Forty seeded shapes between 2 and 700 per side (odd sizes, fewer columns than one stage,
+    fewer rows than one wave, ranks that are no multiple of 4), both dtypes: two steps through
+    either form must agree bit for bit, and the first step's D is G."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        m, n = int(rng.integers(2, 700)), int(rng.integers(2, 700))
+        r = int(rng.integers(1, min(m, n, 128) + 1))
+        dtype = "bf16" if case % 2 else "f32"
+        if edgc.tensor_bypassed(m, n, r):
+            continue
+        a = Stage([(m, n)], r, dtype, seed=case)
+        b = Stage([(m, n)], r, dtype, seed=case, deferred=True)
+        for step in range(2):
+            a.step_device()
+            b.step_device()
+            x, y = a.t[0], b.t[0]
+            assert torch.equal(x.grad_out, y.grad_out), (case, m, n, r, dtype, step)
+            assert torch.equal(x.P[:, :r], y.P[:, :r]) and torch.equal(x.Q[:, :r], y.Q[:, :r]), (case, m, n, r, dtype, step)
+            assert torch.equal(x.residual, y.residual - y.grad_out.float()), (case, m, n, r, dtype, step)
+        del a, b
