@@ -135,6 +135,33 @@ def test_error_feedback_telescopes():
     assert _fro(acc_out + E - acc_g) / _fro(acc_g) < 1e-6
 
 
+@pytest.mark.parametrize("code", ["f32", "bf16"])
+def test_residual_in_factored_form_is_the_stored_residual(code):
+    """What the deferred form of the library relies on: the residual the chain stores is exactly
+    D - widen(M^ as transmitted), so a chain that keeps D and the factors and forms
+    D_next = G + (D - M^) on the way walks through the same bits."""
+    m, n, r, T = 48, 80, 4, 4
+    rng = np.random.default_rng(12)
+    dt = orc.BF16 if code == "bf16" else orc.F32
+    Q, E, D_prev, out_prev = _q0(n, r), None, None, None
+    for t in range(T):
+        G = rng.standard_normal((m, n)).astype(np.float32)
+        if code == "bf16":
+            G = gen.to_bf16_bits(G)
+        P, Q, D = orc.compress(G, E, Q, r)
+        if D_prev is not None:                      # the same D from the factored form of E
+            wide = gen.bf16_bits_to_f32(out_prev) if code == "bf16" else out_prev
+            g32 = gen.bf16_bits_to_f32(G) if code == "bf16" else G
+            assert np.array_equal(D, g32 + (D_prev - wide))
+        out, E = orc.decompress(P, Q, D, dt)
+        wide = gen.bf16_bits_to_f32(out) if code == "bf16" else out
+        assert np.array_equal(E, D - wide)
+        # and M^ is a function of the factors alone: recomputing it from (P, Q) gives the same bits
+        out2, _ = orc.decompress(P, Q, np.zeros_like(D), dt)
+        assert np.array_equal(out2, out)
+        D_prev, out_prev = D, out
+
+
 def test_zero_matrix_gives_zero_factors():
     Z = np.zeros((32, 48), dtype=np.float32)
     P, Q, D = orc.compress(Z, None, _q0(48, 4), 4)
