@@ -12,7 +12,10 @@
  *      communication-time model and stage-aligned ranks (Sec. IV-D-1,
  *      Sec. IV-D-4, Algorithm 2), iteration sampling rate (Sec. IV-B)
  *   5. the same entropy estimate and compressor over all gradient tensors of
- *      a pipeline stage in one launch sequence (batched calls)
+ *      a pipeline stage in one launch sequence (batched calls), with the
+ *      error-feedback residual stored as E or kept as D plus the factors
+ *      ("deferred"), and the compress as one call or in the two phases between
+ *      which a data-parallel step exchanges P
  *
  * Conventions
  *   - Every function returns an edgc_status (0 = OK, < 0 = error).  No C++
