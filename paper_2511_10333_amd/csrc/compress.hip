@@ -1273,11 +1273,12 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
 // tile to become the A operand.
 // ---------------------------------------------------------------------------
 template <int NP, int RT, bool VECOK>
-__global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const Group grp)
+__global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
 {
-    // Up to rank 64 two blocks share a CU and each keeps one stage of G and D_prev in flight;
-    // above, LDS leaves room for one block, which then prefetches into a second register set.
-    constexpr bool DB = RT > 2;
+    // Two blocks share a CU and each keeps one stage of G and D_prev in flight.  Above rank 64
+    // the Q tiles of a 64-column stage would leave LDS for one block only (a version with a
+    // second register set for the prefetch ran at 2.7 TB/s): k_pass_p_deferred_narrow.
+    static_assert(RT <= 2, "above rank 64: k_pass_p_deferred_narrow");
     const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
     using GT = typename GradElem<NP>::type;
     const GT* __restrict__ G = static_cast<const GT*>(ta.G);
@@ -1336,7 +1337,7 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const 
     }
 
     float qv[PQ][2][4];
-    float dv[DB ? 2 : 1][16][2], gv[DB ? 2 : 1][16][2];
+    float dv[1][16][2], gv[1][16][2];
     auto stage_full = [&](uint32_t st) __attribute__((always_inline)) { return VECOK && rows_full && k_begin + st * 64 + 64 <= k_end; };
     // Q rows of a stage: item (jp, c4) holds rows 2jp and 2jp+1 (two adjacent columns of the
     // matrix), ranks c4 .. c4+3; lanes run along jp
@@ -1447,7 +1448,6 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const 
         if (st < n_st) { if (stage_full(st)) fetch_dg(st, buf_tag, T{}); else fetch_dg(st, buf_tag, F{}); }
     };
     using B0 = std::integral_constant<int, 0>;
-    using B1 = std::integral_constant<int, DB ? 1 : 0>;
 
     // The stage body is spelled out once per register set (a macro, not a lambda: with the
     // D / G / accumulator arrays handed to a lambda the compiler spills).
@@ -1481,16 +1481,14 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const 
                 *reinterpret_cast<uint32_t*>(ldsA + (wave * 32 + rl + 4 * g) * ROWB + q * 128 + jl * 4) = w[q]; \
         }                                                                                                 \
     }
-    // CUR / NXT: register sets of this stage and of the prefetch.  With one set (CUR = NXT) the next
-    // stage's loads are issued as soon as this stage has used it and fly during its second product
-    // and the next stage's first one.
+    // One register set for G and D_prev: the next stage's loads are issued as soon as this stage
+    // has used it and fly during its second product and the next stage's first one.
 #define EDGC_DEFERRED_STAGE(ST, CUR, NXT)                                                                 \
     {                                                                                                     \
         __syncthreads(); /* previous stage's LDS reads are done */                                        \
         stage_q();                                                                                        \
         __syncthreads();                                                                                  \
         if ((ST) + 1 < n_st) fetch_q((ST) + 1);                                                           \
-        if constexpr (DB) fetch_next((ST) + 1, NXT{});                                                    \
         f32x16 acc[2];                                                                                    \
         _Pragma("unroll") for (int ct = 0; ct < 2; ++ct)                                                  \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;                             \
@@ -1506,7 +1504,7 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const 
         }                                                                                                 \
         if (stage_full(ST)) EDGC_DEFERRED_COMBINE(ST, CUR::value, true)                                   \
         else EDGC_DEFERRED_COMBINE(ST, CUR::value, false)                                                 \
-        if constexpr (!DB) fetch_next((ST) + 1, NXT{});                                                   \
+        fetch_next((ST) + 1, NXT{});                                                                      \
         __syncthreads(); /* D tile and Q^T are in LDS */                                                  \
         const unsigned char* pa = ldsA + (wave * 32 + jl) * ROWB + g * 16;                                \
         const unsigned char* pb = ldsT + jl * ROWB + g * 16;                                              \
@@ -1525,16 +1523,244 @@ __global__ __launch_bounds__(256, RT <= 2 ? 2 : 1) void k_pass_p_deferred(const 
 
     if (n_st) fetch_q(0);
     fetch_next(0, B0{});
-    if constexpr (DB) {
-        for (uint32_t st = 0; st < n_st; st += 2) {
-            EDGC_DEFERRED_STAGE(st, B0, B1)
-            if (st + 1 < n_st) EDGC_DEFERRED_STAGE(st + 1, B1, B0)
-        }
-    } else {
-        for (uint32_t st = 0; st < n_st; ++st) EDGC_DEFERRED_STAGE(st, B0, B0)
-    }
+    for (uint32_t st = 0; st < n_st; ++st) EDGC_DEFERRED_STAGE(st, B0, B0)
 #undef EDGC_DEFERRED_STAGE
 #undef EDGC_DEFERRED_COMBINE
+
+    // partial P of this k-range: part[s][row][c], c over the padded rank
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = row0 + 8 * (v / 4) + 4 * g + (v % 4);
+            if (row < m)
+                part[(static_cast<size_t>(s) * m + row) * RP + ct * 32 + jl] = accp[ct][v];
+        }
+}
+
+// ---------------------------------------------------------------------------
+// The same pass above rank 64, where the Q tiles of a 64-column stage leave LDS for one block
+// per CU only: stages of 32 columns (54 KB of LDS with fp32 gradients), so that two blocks
+// share a CU again and each SIMD has two waves to overlap.  One MFMA tile per wave and stage:
+// lane (jl, g) holds column jl of 16 rows, 4-byte accesses (128 contiguous bytes per half wave
+// and row); neighbouring lanes swap their values (DPP) to write D into LDS as 32-bit pairs.
+// Same products in the same order as k_pass_p_deferred, hence the same bits.
+// ---------------------------------------------------------------------------
+template <int NP, int RT, bool VECOK>
+__global__ __launch_bounds__(256, 2) void k_pass_p_deferred_narrow(const Group grp)
+{
+    static_assert(RT == 4, "built for ranks above 64");
+    const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
+    using GT = typename GradElem<NP>::type;
+    const GT* __restrict__ G = static_cast<const GT*>(ta.G);
+    float* __restrict__ E = ta.E;
+    const float* __restrict__ Q = ta.Q;
+    const float* __restrict__ P = ta.P;
+    float* __restrict__ part = ta.part;
+    const uint64_t ldg = ta.ldg;
+    const uint32_t ldq = ta.ldq, ldp = ta.ldp, m = ta.m, n = ta.n, r = grp.r, kper = ta.d0, S = ta.d1;
+    const bool e_zero = ta.e_zero != 0;
+    constexpr bool ROUND_BF16 = (NP == 1);
+    constexpr int KT = RT * 2, RP = RT * 32;
+    constexpr int ROWQ = NP * RP * 2 + 16;            // LDS bytes per Q row, [column][rank]
+    constexpr int ROWB = NP * 64 + 16;                // LDS bytes per row of 32 columns
+    constexpr int PQ = 16 * (RP / 4) / 256;           // Q-stage items per thread: 2 rows x 4 ranks each
+    extern __shared__ __attribute__((aligned(16))) unsigned char plds[];
+    unsigned char* ldsQ = plds;                       // 32 x ROWQ
+    unsigned char* ldsT = ldsQ + 32 * ROWQ;           // RP x ROWB: Q^T
+    unsigned char* ldsA = ldsT + RP * ROWB;           // 128 x ROWB: D
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int jl = lane & 31, g = lane >> 5;
+    const uint32_t lid = blockIdx.x - ta.first;
+    const uint32_t s = lid % S, rb = lid / S;
+    const uint32_t row0 = rb * 128 + wave * 32;
+    const uint32_t k_begin = s * kper;
+    const uint32_t k_end = min(n, k_begin + kper);
+    const uint32_t n_st = k_begin < k_end ? (k_end - k_begin + 31) / 32 : 0;
+    const bool rows_full = row0 + 32 <= m;
+    const uint32_t off_d = 4u * g * n + jl;
+    const uint32_t off_g = 4u * g * static_cast<uint32_t>(ldg) + jl;
+
+    // A-fragments of P^_prev: row row0 + jl, k = kb*16 + 8g .. +8
+    bf16x8 a[KT][NP];
+#pragma unroll
+    for (int kb = 0; kb < KT; ++kb) {
+        float v[8];
+        const uint32_t row = row0 + jl, c0 = kb * 16 + 8 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+        if (!e_zero && row < m) {
+            if (c0 + 8 <= r) {
+                const float4 x = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0);
+                const float4 y = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0 + 4);
+                v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (c0 + e < r) v[e] = P[static_cast<size_t>(row) * ldp + c0 + e];
+            }
+        }
+        pack8<NP>(v, a[kb]);
+    }
+
+    float qv[PQ][2][4];
+    float dv[16], gv[16];
+    // VECOK here: n and ldg are below 2^28, so that the 32-bit lane offsets hold
+    auto stage_full = [&](uint32_t st) __attribute__((always_inline)) {
+        return VECOK && rows_full && k_begin + st * 32 + 32 <= k_end;
+    };
+    auto fetch_q = [&](uint32_t st) __attribute__((always_inline)) {
+        const uint32_t col0 = k_begin + st * 32;
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jp = idx & 15, c4 = (idx >> 4) * 4;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t j = col0 + 2 * jp + h;
+                qv[p][h][0] = qv[p][h][1] = qv[p][h][2] = qv[p][h][3] = 0.0f;
+                if (j < n && static_cast<uint32_t>(c4) < ldq) {
+                    const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(j) * ldq + c4);
+                    qv[p][h][0] = q.x; qv[p][h][1] = q.y; qv[p][h][2] = q.z; qv[p][h][3] = q.w;
+                }
+            }
+        }
+    };
+    auto fetch_dg = [&](uint32_t st, auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const uint32_t col0 = k_begin + st * 32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rowu = row0 + 8 * (v / 4) + (v % 4);
+            dv[v] = 0.0f;
+            if constexpr (FULL) {
+                const GT* pg = G + (static_cast<uint64_t>(rowu) * ldg + col0) + off_g;
+                const float* pd = E + (static_cast<uint64_t>(rowu) * n + col0) + off_d;
+                if constexpr (NP == 2) gv[v] = __builtin_nontemporal_load(pg);
+                else gv[v] = bf16_bits_widen(__builtin_nontemporal_load(pg));
+                if (!e_zero) dv[v] = grp.stream ? __builtin_nontemporal_load(pd) : *pd;
+            } else {
+                const uint32_t row = rowu + 4 * g, col = col0 + jl;
+                const bool in = row < m && col < k_end;
+                const GT* pg = G + static_cast<uint64_t>(row) * ldg + col;
+                if constexpr (NP == 2) gv[v] = in ? *pg : 0.0f;
+                else gv[v] = in ? bf16_bits_widen(*pg) : 0.0f;
+                if (in && !e_zero) dv[v] = E[static_cast<uint64_t>(row) * n + col];
+            }
+        }
+    };
+    auto stage_q = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jp = idx & 15, c4 = (idx >> 4) * 4;
+            uint32_t w[2][2][NP];                      // [row h][rank pair][plane]
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float m4[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) m4[e] = (static_cast<uint32_t>(c4 + e) < r) ? qv[p][h][e] : 0.0f;
+                pack_pair<NP>(m4[0], m4[1], w[h][0]);
+                pack_pair<NP>(m4[2], m4[3], w[h][1]);
+            }
+#pragma unroll
+            for (int q = 0; q < NP; ++q) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const u32x2 two = {w[h][0][q], w[h][1][q]};
+                    *reinterpret_cast<u32x2*>(ldsQ + (2 * jp + h) * ROWQ + q * (RP * 2) + c4 * 2) = two;
+                }
+#pragma unroll
+                for (int e2 = 0; e2 < 2; ++e2) {
+                    const uint32_t lo = __builtin_amdgcn_perm(w[1][e2][q], w[0][e2][q], 0x05040100u);
+                    const uint32_t hi = __builtin_amdgcn_perm(w[1][e2][q], w[0][e2][q], 0x07060302u);
+                    *reinterpret_cast<uint32_t*>(ldsT + (c4 + 2 * e2) * ROWB + q * 64 + jp * 4) = lo;
+                    *reinterpret_cast<uint32_t*>(ldsT + (c4 + 2 * e2 + 1) * ROWB + q * 64 + jp * 4) = hi;
+                }
+            }
+        }
+    };
+
+    f32x16 accp[RT];
+#pragma unroll
+    for (int ct = 0; ct < RT; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accp[ct][v] = 0.0f;
+
+    using T = std::true_type;
+    using F = std::false_type;
+    const int odd = jl & 1;
+#define EDGC_NARROW_COMBINE(ST, FULL)                                                                     \
+    {                                                                                                     \
+        const uint32_t col0 = k_begin + (ST) * 32;                                                        \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                  \
+            const int rl = 8 * (v / 4) + (v % 4);                                                         \
+            float w0 = acc[v];                                                                            \
+            if constexpr (ROUND_BF16) w0 = static_cast<float>(static_cast<__bf16>(w0));                   \
+            const float d0 = gv[v] + (dv[v] - w0);                                                        \
+            if constexpr (FULL) {                                                                         \
+                E[(static_cast<uint64_t>(row0 + rl) * n + col0) + off_d] = d0;                            \
+            } else {                                                                                      \
+                const uint32_t row = row0 + rl + 4 * g, col = col0 + jl;                                  \
+                if (row < m && col < k_end) E[static_cast<uint64_t>(row) * n + col] = d0;                 \
+            }                                                                                             \
+            /* the neighbouring column's value of the same row; even lanes write even v, odd lanes odd v */ \
+            const float dn = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(d0), 0xB1, 0xF, 0xF, true)); \
+            if ((v & 1) == odd) {                                                                         \
+                uint32_t w[NP];                                                                           \
+                pack_pair<NP>(odd ? dn : d0, odd ? d0 : dn, w);                                           \
+                _Pragma("unroll") for (int q = 0; q < NP; ++q)                                            \
+                    *reinterpret_cast<uint32_t*>(ldsA + (wave * 32 + rl + 4 * g) * ROWB + q * 64 + (jl >> 1) * 4) = w[q]; \
+            }                                                                                             \
+        }                                                                                                 \
+    }
+
+    if (n_st) {
+        fetch_q(0);
+        if (stage_full(0)) fetch_dg(0, T{}); else fetch_dg(0, F{});
+    }
+    for (uint32_t st = 0; st < n_st; ++st) {
+        __syncthreads();                     // previous stage's LDS reads are done
+        stage_q();
+        __syncthreads();
+        if (st + 1 < n_st) fetch_q(st + 1);
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        if (!e_zero) {                       // M^_prev of the stage's 32 columns, as the decompress formed it
+#pragma unroll
+            for (int kb = 0; kb < KT; ++kb) {
+                bf16x8 b[NP];
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+                    b[p] = *reinterpret_cast<const bf16x8*>(ldsQ + jl * ROWQ + p * (RP * 2) + kb * 32 + g * 16);
+                acc = mma<NP>(a[kb], b, acc);
+            }
+        }
+        if (stage_full(st)) EDGC_NARROW_COMBINE(st, true)
+        else EDGC_NARROW_COMBINE(st, false)
+        if (st + 1 < n_st) { if (stage_full(st + 1)) fetch_dg(st + 1, T{}); else fetch_dg(st + 1, F{}); }
+        __syncthreads();                     // D tile and Q^T are in LDS
+        const unsigned char* pa = ldsA + (wave * 32 + jl) * ROWB + g * 16;
+        const unsigned char* pb = ldsT + jl * ROWB + g * 16;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            bf16x8 af[NP];
+#pragma unroll
+            for (int q = 0; q < NP; ++q) af[q] = *reinterpret_cast<const bf16x8*>(pa + q * 64 + kb * 32);
+#pragma unroll
+            for (int ct = 0; ct < RT; ++ct) {
+                bf16x8 b[NP];
+#pragma unroll
+                for (int q = 0; q < NP; ++q)
+                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + q * 64 + kb * 32);
+                accp[ct] = mma<NP>(af, b, accp[ct]);
+            }
+        }
+    }
+#undef EDGC_NARROW_COMBINE
 
     // partial P of this k-range: part[s][row][c], c over the padded rank
 #pragma unroll
@@ -1606,6 +1832,12 @@ static hipError_t allow_lds_pass_p_deferred()
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
+template <int NP>
+static constexpr size_t deferred_narrow_lds()
+{
+    return static_cast<size_t>(32) * (NP * 128 * 2 + 16) + static_cast<size_t>(128 + 128) * (NP * 64 + 16);
+}
+
 int prepare_compress_kernels(edgc_ctx* ctx)
 {
     constexpr int chol_max = (128 * 129 + 8 * 16 * 17 + 128 + kCholThreads) * 8 + 64;
@@ -1615,7 +1847,6 @@ int prepare_compress_kernels(edgc_ctx* ctx)
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 4, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_p_deferred<2, 2>()));
-    EDGC_HIP_TRY(ctx, (allow_lds_pass_p_deferred<2, 4>()));
     return EDGC_OK;
 }
 
@@ -1707,11 +1938,24 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     }
     if (g.defer && with_grad) {
         // D_prev is read where the other form reads E_old: the same bytes; two products per element
-        constexpr size_t lds = deferred_lds<NP, RT>();
-        if (vec)
-            EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
-        else
-            EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+        if constexpr (RT == 4) {
+            // above rank 64: 32-column stages, 4-byte accesses (no alignment beyond the element's);
+            // `vec` here: the kernel's 32-bit lane offsets hold
+            constexpr size_t lds = deferred_narrow_lds<NP>();
+            bool off32 = true;
+            for (uint32_t i = 0; i < g.count; ++i)
+                off32 = off32 && g.t[i].ldg < (1ull << 28) && g.t[i].n < (1u << 28);
+            if (off32)
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred_narrow<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+            else
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred_narrow<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+        } else {
+            constexpr size_t lds = deferred_lds<NP, RT>();
+            if (vec)
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+            else
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+        }
     } else if (vec)
         EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops, (k_pass_p<NP, RT, true><<<blocks, 256, 0, st>>>(g)));
     else
