@@ -12,6 +12,7 @@
 //   k_pass_p_deferred   the P-pass when the residual buffer kept D of the step before instead of E
 //                   (batched calls, deferred = 1): E = D_prev - P^_prev Q_prev^T is formed on the
 //                   way and k_decompress then only writes M^
+//   k_pass_p_deferred_narrow   the same above rank 64 (32-column stages)
 //
 // All contractions run on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.
 // bf16 gradients use one bf16 plane per operand (operands rounded to nearest
@@ -1904,8 +1905,11 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
 {
     constexpr uint32_t BK = 64, RP = RT * 32;
     using GT = typename GradElem<NP>::type;
-    // measured: ~4 blocks per CU stream best (3 are resident; more splits only add partials)
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : 4u);
+    // measured: ~4 blocks per CU stream best (3 are resident; more splits only add partials).
+    // The deferred kernel above rank 64 starts every block with 64 KB of P^ fragments: there
+    // exactly the two blocks per CU that are resident (0 to 7 % faster per step than four).
+    const uint32_t per_cu = (g.defer && with_grad && RT == 4) ? 2u : 4u;
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : per_cu);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
     bool vec = true;
