@@ -914,7 +914,7 @@ __device__ __forceinline__ void load_d_rows(const float* __restrict__ D, uint32_
 }
 
 template <int NP, int RT, int NT, bool VECOK>
-__global__ __launch_bounds__(256) void k_pass_q(const Group grp)
+__global__ __launch_bounds__(256, (NP == 2 && RT == 4) ? 2 : 1) void k_pass_q(const Group grp)
 {
     const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
     const float* __restrict__ D = ta.E;
@@ -979,35 +979,43 @@ __global__ __launch_bounds__(256) void k_pass_q(const Group grp)
         const uint32_t i0 = st * 64;
         const bool full = cols_full && (i0 + 64 <= m);
         const unsigned char* tile = qlds + buf * TILE;
-        // all of the stage's D loads are issued at once (the other waves of the SIMD compute meanwhile)
-        float dv[4][8][NT];
+        // The stage's D loads are issued at once (the other waves of the SIMD compute meanwhile);
+        // fp32 above rank 64 issues them in two halves: with all 64 registers of a stage in
+        // flight the kernel is 12 registers over what lets two waves share a SIMD.
+        constexpr int UH = (NP == 2 && RT == 4) ? 2 : 4;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (full) {
-                if (grp.stream) load_d_rows<NT, true, true>(D, n, m, i0 + 16 * u + 8 * g, col, dv[u]);
-                else            load_d_rows<NT, true, false>(D, n, m, i0 + 16 * u + 8 * g, col, dv[u]);
-            } else {
-                load_d_rows<NT, false, false>(D, n, m, i0 + 16 * u + 8 * g, col, dv[u]);
-            }
-        }
+        for (int h = 0; h < 4 / UH; ++h) {
+            float dv[UH][8][NT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            bf16x8 a[NT][NP];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                float col8[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) col8[q] = dv[u][q][t];
-                pack8<NP>(col8, a[t]);
+            for (int uu = 0; uu < UH; ++uu) {
+                const int u = h * UH + uu;
+                if (full) {
+                    if (grp.stream) load_d_rows<NT, true, true>(D, n, m, i0 + 16 * u + 8 * g, col, dv[uu]);
+                    else            load_d_rows<NT, true, false>(D, n, m, i0 + 16 * u + 8 * g, col, dv[uu]);
+                } else {
+                    load_d_rows<NT, false, false>(D, n, m, i0 + 16 * u + 8 * g, col, dv[uu]);
+                }
             }
 #pragma unroll
-            for (int ct = 0; ct < RT; ++ct) {
-                bf16x8 b[NP];
+            for (int uu = 0; uu < UH; ++uu) {
+                const int u = h * UH + uu;
+                bf16x8 a[NT][NP];
 #pragma unroll
-                for (int p = 0; p < NP; ++p)
-                    b[p] = *reinterpret_cast<const bf16x8*>(tile + (ct * 32 + jl) * ROWB + p * 128 + u * 32 + g * 16);
+                for (int t = 0; t < NT; ++t) {
+                    float col8[8];
 #pragma unroll
-                for (int t = 0; t < NT; ++t) acc[ct][t] = mma<NP>(a[t], b, acc[ct][t]);
+                    for (int q = 0; q < 8; ++q) col8[q] = dv[uu][q][t];
+                    pack8<NP>(col8, a[t]);
+                }
+#pragma unroll
+                for (int ct = 0; ct < RT; ++ct) {
+                    bf16x8 b[NP];
+#pragma unroll
+                    for (int p = 0; p < NP; ++p)
+                        b[p] = *reinterpret_cast<const bf16x8*>(tile + (ct * 32 + jl) * ROWB + p * 128 + u * 32 + g * 16);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[ct][t] = mma<NP>(a[t], b, acc[ct][t]);
+                }
             }
         }
         buf ^= 1;
