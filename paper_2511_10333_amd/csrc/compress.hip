@@ -1384,7 +1384,8 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
                     gv[B][v][0] = x.x; gv[B][v][1] = x.y;
                 } else {
                     const uint32_t x = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(pg));
-                    gv[B][v][0] = __uint_as_float(x << 16); gv[B][v][1] = __uint_as_float(x & 0xffff0000u);
+                    gv[B][v][0] = __uint_as_float(x);    // the pair as loaded: widened where it is used, so
+                    gv[B][v][1] = 0.0f;                  // that nothing here waits for the load
                 }
                 if (!e_zero) {
                     if (grp.stream) {
@@ -1403,7 +1404,8 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
                 for (int e = 0; e < 2; ++e) {
                     const bool in = row < m && col + e < k_end;
                     if constexpr (NP == 2) gv[B][v][e] = in ? pg[e] : 0.0f;
-                    else gv[B][v][e] = in ? bf16_bits_widen(pg[e]) : 0.0f;
+                    else if (e == 0) gv[B][v][0] = __uint_as_float(in ? static_cast<uint32_t>(pg[0]) : 0u);
+                    else gv[B][v][0] = __uint_as_float(__float_as_uint(gv[B][v][0]) | (in ? static_cast<uint32_t>(pg[1]) << 16 : 0u));
                     if (in && !e_zero) dv[B][v][e] = pd[e];
                 }
             }
@@ -1472,7 +1474,12 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
                 w0 = static_cast<float>(static_cast<__bf16>(w0));                                         \
                 w1 = static_cast<float>(static_cast<__bf16>(w1));                                         \
             }                                                                                             \
-            const float d0 = gv[CUR][v][0] + (dv[CUR][v][0] - w0), d1 = gv[CUR][v][1] + (dv[CUR][v][1] - w1); \
+            float g0 = gv[CUR][v][0], g1 = gv[CUR][v][1];                                                 \
+            if constexpr (NP == 1) {                                                                      \
+                const uint32_t bits = __float_as_uint(g0);                                                \
+                g0 = __uint_as_float(bits << 16); g1 = __uint_as_float(bits & 0xffff0000u);               \
+            }                                                                                             \
+            const float d0 = g0 + (dv[CUR][v][0] - w0), d1 = g1 + (dv[CUR][v][1] - w1);                   \
             if constexpr (FULL) {                                                                         \
                 float* pd = E + (static_cast<uint64_t>(row0 + rl) * n + col0) + off_d;                    \
                 *reinterpret_cast<float2*>(pd) = make_float2(d0, d1);                                     \
@@ -1648,14 +1655,14 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_narrow(const Group g
                 const GT* pg = G + (static_cast<uint64_t>(rowu) * ldg + col0) + off_g;
                 const float* pd = E + (static_cast<uint64_t>(rowu) * n + col0) + off_d;
                 if constexpr (NP == 2) gv[v] = __builtin_nontemporal_load(pg);
-                else gv[v] = bf16_bits_widen(__builtin_nontemporal_load(pg));
+                else gv[v] = __uint_as_float(static_cast<uint32_t>(__builtin_nontemporal_load(pg)));   // widened where used
                 if (!e_zero) dv[v] = grp.stream ? __builtin_nontemporal_load(pd) : *pd;
             } else {
                 const uint32_t row = rowu + 4 * g, col = col0 + jl;
                 const bool in = row < m && col < k_end;
                 const GT* pg = G + static_cast<uint64_t>(row) * ldg + col;
                 if constexpr (NP == 2) gv[v] = in ? *pg : 0.0f;
-                else gv[v] = in ? bf16_bits_widen(*pg) : 0.0f;
+                else gv[v] = __uint_as_float(in ? static_cast<uint32_t>(*pg) : 0u);
                 if (in && !e_zero) dv[v] = E[static_cast<uint64_t>(row) * n + col];
             }
         }
@@ -1708,7 +1715,8 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_narrow(const Group g
             const int rl = 8 * (v / 4) + (v % 4);                                                         \
             float w0 = acc[v];                                                                            \
             if constexpr (ROUND_BF16) w0 = static_cast<float>(static_cast<__bf16>(w0));                   \
-            const float d0 = gv[v] + (dv[v] - w0);                                                        \
+            const float g0 = (NP == 1) ? __uint_as_float(__float_as_uint(gv[v]) << 16) : gv[v];           \
+            const float d0 = g0 + (dv[v] - w0);                                                           \
             if constexpr (FULL) {                                                                         \
                 E[(static_cast<uint64_t>(row0 + rl) * n + col0) + off_d] = d0;                            \
             } else {                                                                                      \
