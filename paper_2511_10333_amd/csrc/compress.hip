@@ -1298,6 +1298,9 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
     const uint64_t ldg = ta.ldg;
     const uint32_t ldq = ta.ldq, ldp = ta.ldp, m = ta.m, n = ta.n, r = grp.r, kper = ta.d0, S = ta.d1;
     const bool e_zero = ta.e_zero != 0;
+    // without grp.defer the buffer holds E itself: the same sweep with nothing to subtract (this
+    // kernel's access pattern is the faster one for bf16 gradients in either form)
+    const bool subtract = grp.defer != 0 && !e_zero;
     constexpr bool ROUND_BF16 = (NP == 1);
     constexpr int KT = RT * 2, RP = RT * 32;
     constexpr int ROWQ = NP * RP * 2 + 16;            // LDS bytes per Q row, [column][rank]
@@ -1331,7 +1334,7 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
         const uint32_t row = row0 + jl, c0 = kb * 16 + 8 * g;
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = 0.0f;
-        if (!e_zero && row < m) {
+        if (subtract && row < m) {
             if (c0 + 8 <= r) {
                 const float4 x = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0);
                 const float4 y = *reinterpret_cast<const float4*>(P + static_cast<size_t>(row) * ldp + c0 + 4);
@@ -1508,7 +1511,7 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
         f32x16 acc[2];                                                                                    \
         _Pragma("unroll") for (int ct = 0; ct < 2; ++ct)                                                  \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;                             \
-        if (!e_zero) {                                                                                    \
+        if (subtract) {                                                                                   \
             _Pragma("unroll") for (int ct = 0; ct < 2; ++ct) {                                            \
                 _Pragma("unroll") for (int kb = 0; kb < KT; ++kb) {                                       \
                     bf16x8 b[NP];                                                                         \
@@ -1924,7 +1927,12 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     // measured: ~4 blocks per CU stream best (3 are resident; more splits only add partials).
     // The deferred kernel above rank 64 starts every block with 64 KB of P^ fragments: there
     // exactly the two blocks per CU that are resident (0 to 7 % faster per step than four).
-    const uint32_t per_cu = (g.defer && with_grad && RT == 4) ? 2u : 4u;
+    // the kernels of the deferred form: above rank 64 only for that form; up to rank 64 also for bf16
+    // gradients with the residual stored (its sweep is the faster one there: 295 against 390 us on the
+    // hidden-5120 block)
+    const bool use_narrow = with_grad && g.defer && RT == 4;
+    const bool use_wide = with_grad && RT <= 2 && (g.defer || NP == 1);
+    const uint32_t per_cu = use_narrow ? 2u : 4u;
     const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : per_cu);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
@@ -1945,8 +1953,8 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         t.sp = S;
         t.first = blocks;
         blocks += RB * S;
-        // 16-byte accesses; the deferred form reads and writes two columns per lane
-        const uint32_t w = (g.defer && with_grad) ? 2u : 4u;
+        // 16-byte accesses; the kernel of the deferred form reads and writes two columns per lane
+        const uint32_t w = use_wide ? 2u : 4u;
         if (w == 2u) vec = vec && t.ldg < (1ull << 28) && t.n < (1u << 28);   // its per-lane offsets are 32-bit
         vec = vec && (t.n % w == 0) && (t.ldg % w == 0) &&
               (reinterpret_cast<uintptr_t>(t.G) % (w * sizeof(GT)) == 0) &&
@@ -1956,8 +1964,9 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         bytes += mn * ((with_grad ? sizeof(GT) : 0) + (t.e_zero ? 0 : 4) + 4);
         flops += 2.0 * mn * g.r;
     }
-    if (g.defer && with_grad) {
+    if (use_narrow || use_wide) {
         // D_prev is read where the other form reads E_old: the same bytes; two products per element
+        const double fl = g.defer ? 2.0 * flops : flops;
         if constexpr (RT == 4) {
             // above rank 64: 32-column stages, 4-byte accesses (no alignment beyond the element's);
             // `vec` here: the kernel's 32-bit lane offsets hold
@@ -1966,15 +1975,15 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
             for (uint32_t i = 0; i < g.count; ++i)
                 off32 = off32 && g.t[i].ldg < (1ull << 28) && g.t[i].n < (1u << 28);
             if (off32)
-                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred_narrow<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, fl, (k_pass_p_deferred_narrow<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
             else
-                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred_narrow<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, fl, (k_pass_p_deferred_narrow<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
         } else {
             constexpr size_t lds = deferred_lds<NP, RT>();
             if (vec)
-                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, fl, (k_pass_p_deferred<NP, RT, true><<<blocks, 256, lds, st>>>(g)));
             else
-                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
+                EDGC_LAUNCH(ctx, st, KID_PASS_P_DEFERRED, bytes, fl, (k_pass_p_deferred<NP, RT, false><<<blocks, 256, lds, st>>>(g)));
         }
     } else if (vec)
         EDGC_LAUNCH(ctx, st, KID_PASS_P, bytes, flops, (k_pass_p<NP, RT, true><<<blocks, 256, 0, st>>>(g)));
