@@ -1232,15 +1232,7 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
     using T = std::true_type;
     using F = std::false_type;
 
-    auto run_stage = [&](uint32_t st, float (&dcur)[16][2], float (&dnxt)[16][2]) {
-        __syncthreads();                     // previous stage's LDS reads are done
-        stage_q();
-        __syncthreads();
-        if (st + 1 < st_end) {               // next stage's loads fly during this stage's work
-            fetch_q(st + 1);
-            if (stage_full(st + 1)) fetch_d(st + 1, dnxt, T{}); else fetch_d(st + 1, dnxt, F{});
-        }
-        f32x16 acc[2];
+    auto product = [&](f32x16 (&acc)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
 #pragma unroll
@@ -1254,14 +1246,66 @@ __global__ __launch_bounds__(256) void k_decompress(const Group grp)
                 acc[ct] = mma<NP>(a[kb], b, acc[ct]);
             }
         }
+    };
+    auto run_stage = [&](uint32_t st, float (&dcur)[16][2], float (&dnxt)[16][2]) __attribute__((always_inline)) {
+        __syncthreads();                     // previous stage's LDS reads are done
+        stage_q();
+        __syncthreads();
+        if (st + 1 < st_end) {               // next stage's loads fly during this stage's work
+            fetch_q(st + 1);
+            if (stage_full(st + 1)) fetch_d(st + 1, dnxt, T{}); else fetch_d(st + 1, dnxt, F{});
+        }
+        f32x16 acc[2];
+        product(acc);
         if (stage_full(st)) finish(st, dcur, acc, T{}); else finish(st, dcur, acc, F{});
     };
+    // The same between two stages that lie wholly inside the matrix: every load is unconditional, so
+    // the compiler can count them, and the wait for the Q rows at the top of a stage leaves what was
+    // issued after them (the next stage's D, this stage's stores) in flight; with loads under
+    // conditions it waits for everything there, the stores included.
+    auto fetch_q_fast = [&](uint32_t st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jj = idx / (RP / 4), c4 = (idx % (RP / 4)) * 4;
+            // rank columns from ldq on are masked when the tile is staged: any address inside the row will do
+            const uint32_t cc = min(static_cast<uint32_t>(c4), ldq - 4u);
+            const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(st * 64 + jj) * ldq + cc);
+            qv[p][0] = q.x; qv[p][1] = q.y; qv[p][2] = q.z; qv[p][3] = q.w;
+        }
+    };
+    auto run_stage_fast = [&](uint32_t st, float (&dcur)[16][2], float (&dnxt)[16][2]) __attribute__((always_inline)) {
+        __syncthreads();
+        stage_q();
+        __syncthreads();
+        fetch_q_fast(st + 1);
+        fetch_d(st + 1, dnxt, T{});
+        f32x16 acc[2];
+        product(acc);
+        finish(st, dcur, acc, T{});
+    };
 
-    if (st_begin < st_end) {
+    // stages [st_begin, fast_end) are full and followed by a full stage; they are taken in pairs
+    // (the two D register sets swap roles)
+    // (fp32 above rank 64: the second copy of the loop costs the two registers that let two waves
+    // share a SIMD, 128 instead of 103 us on the hidden-4096 layer: left out there)
+    constexpr bool FAST = !(NP == 2 && RT == 4);
+    const uint32_t whole_end = (FAST && VECOK && rows_full) ? min(st_end, n / 64) : 0;
+    uint32_t st = st_begin;
+    if (FAST && whole_end > st_begin + 2) {
+        if constexpr (FAST) {
+            fetch_q_fast(st_begin);
+            fetch_d(st_begin, dv[0], T{});
+            for (; st + 3 <= whole_end; st += 2) {
+                run_stage_fast(st, dv[0], dv[DEFER ? 0 : 1]);
+                run_stage_fast(st + 1, dv[DEFER ? 0 : 1], dv[0]);
+            }
+        }
+    } else if (st_begin < st_end) {
         fetch_q(st_begin);
         if (stage_full(st_begin)) fetch_d(st_begin, dv[0], T{}); else fetch_d(st_begin, dv[0], F{});
     }
-    for (uint32_t st = st_begin; st < st_end; st += 2) {
+    for (; st < st_end; st += 2) {
         run_stage(st, dv[0], dv[DEFER ? 0 : 1]);
         if (st + 1 < st_end) run_stage(st + 1, dv[DEFER ? 0 : 1], dv[0]);
     }
@@ -1502,12 +1546,7 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
     }
     // One register set for G and D_prev: the next stage's loads are issued as soon as this stage
     // has used it and fly during its second product and the next stage's first one.
-#define EDGC_DEFERRED_STAGE(ST, CUR, NXT)                                                                 \
-    {                                                                                                     \
-        __syncthreads(); /* previous stage's LDS reads are done */                                        \
-        stage_q();                                                                                        \
-        __syncthreads();                                                                                  \
-        if ((ST) + 1 < n_st) fetch_q((ST) + 1);                                                           \
+#define EDGC_DEFERRED_M_HAT()                                                                             \
         f32x16 acc[2];                                                                                    \
         _Pragma("unroll") for (int ct = 0; ct < 2; ++ct)                                                  \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[ct][v] = 0.0f;                             \
@@ -1520,11 +1559,8 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
                     acc[ct] = mma<NP>(a[kb], b, acc[ct]);                                                 \
                 }                                                                                         \
             }                                                                                             \
-        }                                                                                                 \
-        if (stage_full(ST)) EDGC_DEFERRED_COMBINE(ST, CUR::value, true)                                   \
-        else EDGC_DEFERRED_COMBINE(ST, CUR::value, false)                                                 \
-        fetch_next((ST) + 1, NXT{});                                                                      \
-        __syncthreads(); /* D tile and Q^T are in LDS */                                                  \
+        }
+#define EDGC_DEFERRED_P_PRODUCT()                                                                         \
         const unsigned char* pa = ldsA + (wave * 32 + jl) * ROWB + g * 16;                                \
         const unsigned char* pb = ldsT + jl * ROWB + g * 16;                                              \
         _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) {                                                \
@@ -1537,12 +1573,101 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
                     b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + q * 128 + kb * 32);     \
                 accp[ct] = mma<NP>(af, b, accp[ct]);                                                      \
             }                                                                                             \
-        }                                                                                                 \
+        }
+#define EDGC_DEFERRED_STAGE(ST, CUR, NXT)                                                                 \
+    {                                                                                                     \
+        __syncthreads(); /* previous stage's LDS reads are done */                                        \
+        stage_q();                                                                                        \
+        __syncthreads();                                                                                  \
+        if ((ST) + 1 < n_st) fetch_q((ST) + 1);                                                           \
+        EDGC_DEFERRED_M_HAT()                                                                             \
+        if (stage_full(ST)) EDGC_DEFERRED_COMBINE(ST, CUR::value, true)                                   \
+        else EDGC_DEFERRED_COMBINE(ST, CUR::value, false)                                                 \
+        fetch_next((ST) + 1, NXT{});                                                                      \
+        __syncthreads(); /* D tile and Q^T are in LDS */                                                  \
+        EDGC_DEFERRED_P_PRODUCT()                                                                         \
     }
+    // The same between two stages that lie wholly inside the matrix and the block's column range,
+    // with a residual to add: every load is unconditional, so the compiler can count them and the
+    // wait for the Q rows at the top of a stage leaves the G / D_prev loads behind them in flight
+    // (with loads under conditions it waits for everything there).
+#define EDGC_DEFERRED_STAGE_FAST(ST, STREAM)                                                              \
+    {                                                                                                     \
+        __syncthreads();                                                                                  \
+        stage_q();                                                                                        \
+        __syncthreads();                                                                                  \
+        fetch_q_fast((ST) + 1);                                                                           \
+        EDGC_DEFERRED_M_HAT()                                                                             \
+        EDGC_DEFERRED_COMBINE(ST, 0, true)                                                                \
+        fetch_dg_fast((ST) + 1, std::integral_constant<bool, STREAM>{});                                  \
+        __syncthreads();                                                                                  \
+        EDGC_DEFERRED_P_PRODUCT()                                                                         \
+    }
+    auto fetch_q_fast = [&](uint32_t st) __attribute__((always_inline)) {
+        const uint32_t col0 = k_begin + st * 64;
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jp = idx & 31, c4 = (idx >> 5) * 4;
+            // rank columns from ldq on are masked when the tile is staged: any address inside the row will do
+            const uint32_t cc = min(static_cast<uint32_t>(c4), ldq - 4u);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(col0 + 2 * jp + h) * ldq + cc);
+                qv[p][h][0] = q.x; qv[p][h][1] = q.y; qv[p][h][2] = q.z; qv[p][h][3] = q.w;
+            }
+        }
+    };
+    auto fetch_dg_fast = [&](uint32_t st, auto stream_tag) __attribute__((always_inline)) {
+        constexpr bool STREAM = decltype(stream_tag)::value;
+        const uint32_t col0 = k_begin + st * 64;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rowu = row0 + 8 * (v / 4) + (v % 4);
+            const GT* pg = G + (static_cast<uint64_t>(rowu) * ldg + col0) + off_g;
+            const float* pd = E + (static_cast<uint64_t>(rowu) * n + col0) + off_d;
+            if constexpr (NP == 2) {
+                const vf2 x = __builtin_nontemporal_load(reinterpret_cast<const vf2*>(pg));
+                gv[0][v][0] = x.x; gv[0][v][1] = x.y;
+            } else {
+                gv[0][v][0] = __uint_as_float(__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(pg)));
+                gv[0][v][1] = 0.0f;
+            }
+            if constexpr (STREAM) {
+                const vf2 x = __builtin_nontemporal_load(reinterpret_cast<const vf2*>(pd));
+                dv[0][v][0] = x.x; dv[0][v][1] = x.y;
+            } else {
+                const float2 x = *reinterpret_cast<const float2*>(pd);
+                dv[0][v][0] = x.x; dv[0][v][1] = x.y;
+            }
+        }
+    };
 
-    if (n_st) fetch_q(0);
-    fetch_next(0, B0{});
-    for (uint32_t st = 0; st < n_st; ++st) EDGC_DEFERRED_STAGE(st, B0, B0)
+    // stages [0, n_fast) are full and followed by a full stage.  (fp32 at ranks 33 to 64 has no
+    // registers to spare for the second copy of the loop: it spills there and gets slower.)
+    constexpr bool FAST = !(NP == 2 && RT == 2);
+    const uint32_t n_whole = (FAST && VECOK && rows_full && !e_zero) ? (k_end - k_begin) / 64 : 0;
+    const uint32_t n_fast = n_whole > 1 ? n_whole - 1 : 0;
+    uint32_t st = 0;
+    if (FAST && n_fast) {
+        if constexpr (FAST) {
+            fetch_q_fast(0);
+            if (grp.stream) {
+                fetch_dg_fast(0, T{});
+                for (; st < n_fast; ++st) EDGC_DEFERRED_STAGE_FAST(st, true)
+            } else {
+                fetch_dg_fast(0, F{});
+                for (; st < n_fast; ++st) EDGC_DEFERRED_STAGE_FAST(st, false)
+            }
+        }
+    } else {
+        if (n_st) fetch_q(0);
+        fetch_next(0, B0{});
+    }
+    for (; st < n_st; ++st) EDGC_DEFERRED_STAGE(st, B0, B0)
+#undef EDGC_DEFERRED_STAGE_FAST
+#undef EDGC_DEFERRED_M_HAT
+#undef EDGC_DEFERRED_P_PRODUCT
 #undef EDGC_DEFERRED_STAGE
 #undef EDGC_DEFERRED_COMBINE
 
