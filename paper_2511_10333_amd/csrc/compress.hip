@@ -1862,49 +1862,112 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_narrow(const Group g
         }                                                                                                 \
     }
 
-    if (n_st) {
+    // Stages wholly inside the matrix run through a copy of the loop whose loads are all
+    // unconditional (with no residual yet, D_prev is loaded all the same and dropped), so that the
+    // compiler can count what is in flight: its wait for the Q rows at the top of a stage then
+    // leaves the G / D_prev loads issued behind them alone.
+    auto fetch_q_fast = [&](uint32_t st) __attribute__((always_inline)) {
+        const uint32_t col0 = k_begin + st * 32;
+#pragma unroll
+        for (int p = 0; p < PQ; ++p) {
+            const int idx = tid + p * 256;
+            const int jp = idx & 15, c4 = (idx >> 4) * 4;
+            const uint32_t cc = min(static_cast<uint32_t>(c4), ldq - 4u);   // masked from r on when staged
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float4 q = *reinterpret_cast<const float4*>(Q + static_cast<size_t>(col0 + 2 * jp + h) * ldq + cc);
+                qv[p][h][0] = q.x; qv[p][h][1] = q.y; qv[p][h][2] = q.z; qv[p][h][3] = q.w;
+            }
+        }
+    };
+    auto fetch_dg_fast = [&](uint32_t st, auto stream_tag) __attribute__((always_inline)) {
+        constexpr bool STREAM = decltype(stream_tag)::value;
+        const uint32_t col0 = k_begin + st * 32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t rowu = row0 + 8 * (v / 4) + (v % 4);
+            const GT* pg = G + (static_cast<uint64_t>(rowu) * ldg + col0) + off_g;
+            const float* pd = E + (static_cast<uint64_t>(rowu) * n + col0) + off_d;
+            if constexpr (NP == 2) gv[v] = __builtin_nontemporal_load(pg);
+            else gv[v] = __uint_as_float(static_cast<uint32_t>(__builtin_nontemporal_load(pg)));
+            dv[v] = STREAM ? __builtin_nontemporal_load(pd) : *pd;
+        }
+    };
+#define EDGC_NARROW_M_HAT()                                                                               \
+        f32x16 acc;                                                                                       \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[v] = 0.0f;                                     \
+        if (!e_zero) { /* M^_prev of the stage's 32 columns, as the decompress formed it */               \
+            _Pragma("unroll") for (int kb = 0; kb < KT; ++kb) {                                           \
+                bf16x8 b[NP];                                                                             \
+                _Pragma("unroll") for (int p = 0; p < NP; ++p)                                            \
+                    b[p] = *reinterpret_cast<const bf16x8*>(ldsQ + jl * ROWQ + p * (RP * 2) + kb * 32 + g * 16); \
+                acc = mma<NP>(a[kb], b, acc);                                                             \
+            }                                                                                             \
+        }
+#define EDGC_NARROW_P_PRODUCT()                                                                           \
+        const unsigned char* pa = ldsA + (wave * 32 + jl) * ROWB + g * 16;                                \
+        const unsigned char* pb = ldsT + jl * ROWB + g * 16;                                              \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                                \
+            bf16x8 af[NP];                                                                                \
+            _Pragma("unroll") for (int q = 0; q < NP; ++q)                                                \
+                af[q] = *reinterpret_cast<const bf16x8*>(pa + q * 64 + kb * 32);                          \
+            _Pragma("unroll") for (int ct = 0; ct < RT; ++ct) {                                           \
+                bf16x8 b[NP];                                                                             \
+                _Pragma("unroll") for (int q = 0; q < NP; ++q)                                            \
+                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + q * 64 + kb * 32);      \
+                accp[ct] = mma<NP>(af, b, accp[ct]);                                                      \
+            }                                                                                             \
+        }
+#define EDGC_NARROW_STAGE_FAST(ST, STREAM)                                                                \
+    {                                                                                                     \
+        __syncthreads();                                                                                  \
+        stage_q();                                                                                        \
+        __syncthreads();                                                                                  \
+        fetch_q_fast((ST) + 1);                                                                           \
+        EDGC_NARROW_M_HAT()                                                                               \
+        if (e_zero) { _Pragma("unroll") for (int v = 0; v < 16; ++v) dv[v] = 0.0f; }                      \
+        EDGC_NARROW_COMBINE(ST, true)                                                                     \
+        fetch_dg_fast((ST) + 1, std::integral_constant<bool, STREAM>{});                                  \
+        __syncthreads();                                                                                  \
+        EDGC_NARROW_P_PRODUCT()                                                                           \
+    }
+
+    // stages [0, n_fast) are full and followed by a full stage.  (With fp32 gradients the second
+    // copy of the loop costs more in spilled registers than the waits it removes: bf16 only.)
+    constexpr bool FAST = (NP == 1);
+    const uint32_t n_whole = (FAST && VECOK && rows_full) ? (k_end - k_begin) / 32 : 0;
+    const uint32_t n_fast = n_whole > 1 ? n_whole - 1 : 0;
+    uint32_t st = 0;
+    if (FAST && n_fast) {
+        if constexpr (FAST) {
+            fetch_q_fast(0);
+            if (grp.stream) {
+                fetch_dg_fast(0, T{});
+                for (; st < n_fast; ++st) EDGC_NARROW_STAGE_FAST(st, true)
+            } else {
+                fetch_dg_fast(0, F{});
+                for (; st < n_fast; ++st) EDGC_NARROW_STAGE_FAST(st, false)
+            }
+        }
+    } else if (n_st) {
         fetch_q(0);
         if (stage_full(0)) fetch_dg(0, T{}); else fetch_dg(0, F{});
     }
-    for (uint32_t st = 0; st < n_st; ++st) {
+    for (; st < n_st; ++st) {
         __syncthreads();                     // previous stage's LDS reads are done
         stage_q();
         __syncthreads();
         if (st + 1 < n_st) fetch_q(st + 1);
-        f32x16 acc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-        if (!e_zero) {                       // M^_prev of the stage's 32 columns, as the decompress formed it
-#pragma unroll
-            for (int kb = 0; kb < KT; ++kb) {
-                bf16x8 b[NP];
-#pragma unroll
-                for (int p = 0; p < NP; ++p)
-                    b[p] = *reinterpret_cast<const bf16x8*>(ldsQ + jl * ROWQ + p * (RP * 2) + kb * 32 + g * 16);
-                acc = mma<NP>(a[kb], b, acc);
-            }
-        }
+        EDGC_NARROW_M_HAT()
         if (stage_full(st)) EDGC_NARROW_COMBINE(st, true)
         else EDGC_NARROW_COMBINE(st, false)
         if (st + 1 < n_st) { if (stage_full(st + 1)) fetch_dg(st + 1, T{}); else fetch_dg(st + 1, F{}); }
         __syncthreads();                     // D tile and Q^T are in LDS
-        const unsigned char* pa = ldsA + (wave * 32 + jl) * ROWB + g * 16;
-        const unsigned char* pb = ldsT + jl * ROWB + g * 16;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            bf16x8 af[NP];
-#pragma unroll
-            for (int q = 0; q < NP; ++q) af[q] = *reinterpret_cast<const bf16x8*>(pa + q * 64 + kb * 32);
-#pragma unroll
-            for (int ct = 0; ct < RT; ++ct) {
-                bf16x8 b[NP];
-#pragma unroll
-                for (int q = 0; q < NP; ++q)
-                    b[q] = *reinterpret_cast<const bf16x8*>(pb + ct * 32 * ROWB + q * 64 + kb * 32);
-                accp[ct] = mma<NP>(af, b, accp[ct]);
-            }
-        }
+        EDGC_NARROW_P_PRODUCT()
     }
+#undef EDGC_NARROW_STAGE_FAST
+#undef EDGC_NARROW_M_HAT
+#undef EDGC_NARROW_P_PRODUCT
 #undef EDGC_NARROW_COMBINE
 
     // partial P of this k-range: part[s][row][c], c over the padded rank
