@@ -42,7 +42,7 @@ MEASURED_TRAFFIC_BYTES = {
     # coming from the same counters on a plain 1 GiB device copy (FETCH_SIZE reads half the bytes)
     ("cfg2_gpt_h2048_r16", "k_pass_p", 2, "explicit"): int((2 * 9.764e4 + 1.125e5) * 1024),
     # profiles/k_pass_p_deferred_cfg2_traffic.md, the same way
-    ("cfg2_gpt_h2048_r16", "k_pass_p_deferred", 2, "deferred"): int((2 * 1.0134e5 + 1.1251e5) * 1024),
+    ("cfg2_gpt_h2048_r16", "k_pass_p_deferred", 2, "deferred"): int((2 * 1.01527e5 + 1.12512e5) * 1024),
 }
 
 
