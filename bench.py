@@ -243,9 +243,13 @@ def main() -> int:
         else:
             # entropy launches stay eager (their sampling slot changes with the step); the
             # compress + decompress launches of all layers are one captured graph
-            for L in layers:
-                L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
-                                                w["bins"], L["ent"][t % NBUF], stream=L["estream"])
+            if groups:
+                stage["ectx"].entropy_estimate_async(stage["flats"], w["stride"], w["chunk"], w["seed"], t,
+                                                     w["bins"], stage["ent"][t % NBUF], stream=stage["estream"])
+            else:
+                for L in layers:
+                    L["ctx"].entropy_estimate_async(L["flat"], w["stride"], w["chunk"], w["seed"], t,
+                                                    w["bins"], L["ent"][t % NBUF], stream=L["estream"])
             with torch.cuda.stream(main_stream):
                 graph["g"].replay()
                 for ev in step_events[t % NBUF][:n_streams]:
