@@ -1507,8 +1507,8 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred(const Group grp)
     };
     using B0 = std::integral_constant<int, 0>;
 
-    // The stage body is spelled out once per register set (a macro, not a lambda: with the
-    // D / G / accumulator arrays handed to a lambda the compiler spills).
+    // The stage body is spelled out by macros, not lambdas: with the D / G / accumulator arrays
+    // handed to a lambda the compiler spills 50 to 120 registers of the same code.
     //   M^_prev of the stage from LDS, as the decompress formed it;
     //   E = D_prev - M^_prev, D = G + E: to the residual buffer and, as bf16 planes, to the wave's LDS rows.
 #define EDGC_DEFERRED_COMBINE(ST, CUR, FULL)                                                              \
