@@ -211,3 +211,23 @@ def test_seeded_sweep_of_small_and_ragged_shapes_deferred_equals_explicit():
             assert torch.equal(x.P[:, :r], y.P[:, :r]) and torch.equal(x.Q[:, :r], y.Q[:, :r]), (case, m, n, r, dtype, step)
             assert torch.equal(x.residual, y.residual - y.grad_out.float()), (case, m, n, r, dtype, step)
         del a, b
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_deferred_with_the_reconstruction_written_over_the_gradient(dtype):
+    """grad_out may be the gradient buffer itself (the reconstruction replaces the gradient in place):
+    the P-pass has read the gradient before the decompress of the same step overwrites it."""
+    shapes, r = [(384, 640), (130, 260)], 16
+    a = Stage(shapes, r, dtype, seed=4, deferred=True)
+    b = Stage(shapes, r, dtype, seed=4, deferred=True)
+    fresh = [t.grad.clone() for t in b.t]
+    for t in b.t:
+        t.grad_out = t.grad
+    for step in range(3):
+        for t, g in zip(b.t, fresh):
+            t.grad.copy_(g)                                   # a new gradient arrives in the same buffer
+        a.step_device()
+        b.step_device()
+        for i, (x, y) in enumerate(zip(a.t, b.t)):
+            assert torch.equal(x.grad_out, y.grad), (step, i)
+            assert torch.equal(x.residual, y.residual) and torch.equal(x.P, y.P) and torch.equal(x.Q, y.Q), (step, i)
