@@ -35,6 +35,42 @@ def test_flat_buffer_entropy_sweep(dtype):
             assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_flat_buffer_of_1e9_elements_sampled(dtype):
+    """The flat buffer at its full size of 1e9 elements (generated on the device: Laplace(0, 1e-3)
+    with 0.1 % of the values at 100 times the scale).  The oracle gets the sample: its own index
+    set gathers the sampled elements, and its estimator runs over them with every element taken;
+    counts are compared bit for bit.  Strides 1000, 100 and 10 (the 100 % cell is covered on the
+    2^26-element slice above)."""
+    n = 1_000_000_000
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.empty(n, device="cuda")
+    x.exponential_(1.0, generator=g)                                   # |Laplace(0, 1)|
+    sign = torch.empty(n, device="cuda").uniform_(-1.0, 1.0, generator=g)
+    x.mul_(torch.sign(sign))
+    x.mul_(torch.where(sign.abs() < 1e-3, 1e-1, 1e-3))                 # 0.1 % outliers at 100 x scale
+    del sign
+    if dtype == "bf16":
+        x = x.bfloat16()
+    c = ctx()
+    for stride in (1000, 100, 10):
+        idx = torch.from_numpy(orc.sample_indices(n, stride, 64, 0, 5).astype(np.int64)).cuda()
+        sample = x[idx]
+        del idx
+        host = to_host(sample) if dtype == "bf16" else sample.cpu().numpy()
+        del sample
+        for bins in (256, 4096, 65536):
+            ref = orc.entropy(host, 1, 1, 0, 0, bins)
+            counts = torch.empty(bins, dtype=torch.int64, device="cuda")
+            got = c.entropy_estimate(x, stride, 64, 0, 5, bins, None, counts)
+            assert (got.n_sampled, got.n_nonfinite, got.lo, got.hi) == (ref.n_sampled, 0, ref.lo, ref.hi)
+            assert got.n_sampled == host.size
+            assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts), (stride, bins)
+            assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5
+    del x
+    torch.cuda.empty_cache()
+
+
 # ---------------------------------------------------------------------------
 # hidden-5120 bf16 attention projection, rank 64, residual carried over three steps
 # ---------------------------------------------------------------------------
