@@ -353,6 +353,19 @@ def main() -> int:
             for k, v in kernels.items()
             if k in ("k_pass_p", "k_pass_p_deferred", "k_pass_q", "k_decompress") and v["tflops"]}
 
+    # what a plain copy, a plain read and a bf16 MFMA loop reach on this device (context beside the
+    # published peaks the fractions above are taken against)
+    pa = torch.ones(1 << 28, dtype=torch.float32, device="cuda")          # 1 GiB each
+    pb = torch.empty_like(pa)
+    torch.cuda.synchronize()
+    peaks = ctxs[0].measure_device_peaks(pa, pb, reps=10)
+    del pa, pb
+    device_peaks = dict(copy_gbs=round(peaks["copy_gbs"], 1), read_gbs=round(peaks["read_gbs"], 1),
+                        mfma_bf16_tflops=round(peaks["mfma_bf16_tflops"], 1), bytes=peaks["bytes"],
+                        what="plain copy (read + written bytes), plain read, register-resident "
+                             "32x32x16 bf16 MFMA loop; 10 launches each between one pair of events")
+    roofline["frac_of_measured_copy"] = round(achieved / peaks["copy_gbs"], 4)
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import edgc_oracle as orc
@@ -394,6 +407,7 @@ def main() -> int:
                    "residual": "deferred" if deferred else "explicit",
                    "gradient_bytes_per_step": grad_bytes},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "mfma": mfma,
+        "device_peaks_measured": device_peaks,
         "last_rank_decision": decisions[-1].rank if decisions else None,
         "host_issue_ms_per_step": round(host_issue_ms, 4),
         "host_issue_idle_gpu_ms_per_step": round(host_issue_idle_ms, 4),

@@ -105,6 +105,8 @@ def load_library() -> C.CDLL:
     L.edgc_measure_rank_costs.restype = i32
     L.edgc_measure_rank_costs.argtypes = [vp, vp, i32, u32, u32, u64, vp, vp, u32, vp, u32, vp,
                                           C.POINTER(u32), u32, u32, i32, C.POINTER(_RankCost), vp]
+    L.edgc_measure_device_peaks.restype = i32
+    L.edgc_measure_device_peaks.argtypes = [vp, vp, vp, u64, u32, C.POINTER(_DevicePeaks), vp]
     L.edgc_tensor_bypassed.restype = i32
     L.edgc_tensor_bypassed.argtypes = [u32, u32, u32]
     L.edgc_reserve_batch.restype = i32
@@ -127,6 +129,11 @@ def load_library() -> C.CDLL:
     L.edgc_decompress.argtypes = [vp, vp, u32, vp, u32, u32, u32, u32, vp, vp, i32, u64, vp]
     _lib = L
     return L
+
+
+class _DevicePeaks(C.Structure):
+    _fields_ = [("copy_gbs", C.c_double), ("read_gbs", C.c_double), ("mfma_bf16_tflops", C.c_double),
+                ("bytes", C.c_uint64)]
 
 
 class _Tensor(C.Structure):
@@ -453,6 +460,20 @@ class Context:
         self._check(rc, "edgc_measure_rank_costs")
         return [RankCost(int(c.rank), c.t_compress, c.t_decompress, c.bytes_compressed)
                 for c in list(out)[:len(ranks)]]
+
+    def measure_device_peaks(self, buf_a, buf_b, reps: int = 10, stream=None) -> dict:
+        """edgc_measure_device_peaks: what a plain copy, a plain read and a bf16 MFMA loop reach on
+        this device; buf_a is read, buf_b overwritten (two tensors of equal size in bytes);
+        synchronises the stream."""
+        nbytes = buf_a.numel() * buf_a.element_size()
+        if nbytes != buf_b.numel() * buf_b.element_size():
+            raise ValueError("the two buffers must have the same size in bytes")
+        out = _DevicePeaks()
+        rc = self._L.edgc_measure_device_peaks(self._h, buf_a.data_ptr(), buf_b.data_ptr(), nbytes, reps,
+                                               C.byref(out), _stream_handle(stream))
+        self._check(rc, "edgc_measure_device_peaks")
+        return {"copy_gbs": out.copy_gbs, "read_gbs": out.read_gbs,
+                "mfma_bf16_tflops": out.mfma_bf16_tflops, "bytes": int(out.bytes)}
 
     # -- batched calls -----------------------------------------------------
     def reserve_batch(self, shapes: Sequence[Sequence[int]]) -> None:
