@@ -58,7 +58,9 @@ typedef struct edgc_ctx edgc_ctx;   /* opaque; owns only scratch memory */
 
 /* Creates a context on GPU `hip_device` with scratch sized for histograms of
  * up to max_bins bins and matrices of up to max_rows x max_cols at rank
- * <= max_rank (max_rank <= 128).  *out is NULL on failure. */
+ * <= max_rank (max_rank <= 128; max_rows, max_cols <= 2^28, which also bounds
+ * every leading dimension of a compressed matrix in the calls below: beyond it
+ * they return EDGC_EINVAL).  *out is NULL on failure. */
 int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, uint32_t max_rank,
                 uint64_t max_rows, uint64_t max_cols);
 int edgc_destroy(edgc_ctx* ctx);

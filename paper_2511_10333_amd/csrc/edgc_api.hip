@@ -53,7 +53,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     if (!out) return EDGC_EINVAL;
     *out = nullptr;
     if (max_bins == 0 || max_bins > (1u << 24) || max_rank == 0 || max_rank > 128 || max_rows == 0 ||
-        max_cols == 0 || max_rows > 0x7fffffffull || max_cols > 0x7fffffffull)
+        max_cols == 0 || max_rows > kMaxDim || max_cols > kMaxDim)
         return EDGC_EINVAL;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || hip_device < 0 || hip_device >= ndev) return EDGC_EHIP;
@@ -286,6 +286,8 @@ static int check_factor_args(edgc_ctx* ctx, const float* P, uint32_t ldp, const 
     if (m > max_rows || n > max_cols) return fail(ctx, EDGC_EINVAL, "matrix larger than the context");
     if (r == 0 || r > m || r > n || r > ctx->max_rank) return fail(ctx, EDGC_EINVAL, "rank out of range");
     if (ld < n || ldp < r || ldq < r) return fail(ctx, EDGC_EINVAL, "leading dimension too small");
+    if (m > kMaxDim || n > kMaxDim || ld > kMaxDim)
+        return fail(ctx, EDGC_EINVAL, "rows, columns and leading dimensions are limited to 2^28");
     if (ldp % 4 || ldq % 4 || !aligned_to(P, 16) || !aligned_to(Q, 16))
         return fail(ctx, EDGC_EINVAL, "P and Q need 16-byte alignment and leading dimensions that are multiples of 4");
     return EDGC_OK;
@@ -391,6 +393,10 @@ extern "C" int edgc_reserve_batch(edgc_ctx* ctx, const uint32_t* rows, const uin
         b.rows = rows[i];
         b.cols = cols[i];
         if (rows[i] == 0 || cols[i] == 0 || rows[i] == 1 || cols[i] == 1) continue;   // never compressed
+        if (rows[i] > kMaxDim || cols[i] > kMaxDim) {
+            free_batch(ctx);
+            return fail(ctx, EDGC_EINVAL, "rows and columns of a compressed tensor are limited to 2^28");
+        }
         const uint64_t rows_pad = (static_cast<uint64_t>(rows[i]) + 63) / 64 * 64;
         b.cap.part_elems = compress_part_elems(rows[i], cols[i], ctx->max_rank, ctx->num_cu);
         b.cap.gram_part_elems = (rows_pad / 64) * 36ull * 256ull;
@@ -427,6 +433,8 @@ int check_batch_tensor(edgc_ctx* ctx, const edgc_tensor& d, uint32_t i, edgc_dty
         return fail(ctx, EDGC_EINVAL, "tensor larger than the batch slot reserved for its position");
     if (!d.residual || !aligned_to(d.residual, 4)) return fail(ctx, EDGC_EINVAL, "null or misaligned residual in batch");
     if (int rc = check_factor_args(ctx, d.P, d.ldp, d.Q, d.ldq, d.m, d.n, r, d.n, b.rows, b.cols)) return rc;
+    if ((need_grad && d.ld > kMaxDim) || (need_out && d.ld_out > kMaxDim))
+        return fail(ctx, EDGC_EINVAL, "rows, columns and leading dimensions are limited to 2^28");
     return 0;
 }
 

@@ -33,6 +33,10 @@ struct Scratch {
 
 constexpr int kMaxReduceBlocks = 4096;
 
+// Largest row count, column count or leading dimension of a compressed matrix: the kernels keep
+// lane offsets of up to four rows (4 * leading dimension + column) in 32 bits.
+constexpr uint64_t kMaxDim = 1ull << 28;
+
 // ---------------------------------------------------------------------------
 // Grouped launches of the compressor.  Every compressor kernel works on a list of tensors:
 // the grid is the concatenation of the tensors' block ranges and a block finds its tensor

@@ -204,6 +204,25 @@ def test_bad_arguments_rejected_before_launch():
     with pytest.raises(edgc.EdgcError):                    # rank above the context's max_rank
         small = edgc.Context(0, 256, 4, 64, 96)
         small.compress(G, E, True, Q, P, 8, 1)
+    # rows, columns and leading dimensions stop at 2^28 (the kernels keep lane offsets in 32 bits)
+    # (straight through the C ABI: torch does not build a view with such a stride)
+    L, EINVAL, big_ld = c._L, edgc.binding.EINVAL, (1 << 28) + 4
+    assert L.edgc_compress(c._h, G.data_ptr(), edgc.F32, 64, 96, big_ld, E.data_ptr(), 1, Q.data_ptr(), 8,
+                           P.data_ptr(), 8, 8, 1, None) == EINVAL
+    assert L.edgc_decompress(c._h, P.data_ptr(), 8, Q.data_ptr(), 8, 64, 96, 8, E.data_ptr(), G.data_ptr(),
+                             edgc.F32, big_ld, None) == EINVAL
+    with pytest.raises(edgc.EdgcError):
+        edgc.Context(0, 256, 16, (1 << 28) + 1, 64)
+    with pytest.raises(edgc.EdgcError) as e:
+        c.reserve_batch([((1 << 28) + 1, 64)])
+    assert e.value.code == edgc.binding.EINVAL
+    c.reserve_batch([(64, 96)])
+    desc = (edgc.binding._Tensor * 1)()
+    desc[0] = edgc.binding._Tensor(G.data_ptr(), G.data_ptr(), E.data_ptr(), Q.data_ptr(), P.data_ptr(),
+                                   big_ld, 96, 64, 96, 8, 8, 1, 0)
+    assert L.edgc_compress_batch(c._h, desc, 1, edgc.F32, 8, 1, None) == EINVAL
+    desc[0].ld, desc[0].ld_out = 96, big_ld
+    assert L.edgc_decompress_batch(c._h, desc, 1, edgc.F32, 8, None) == EINVAL
 
 
 @pytest.mark.parametrize("name", ["cfg2_gpt_h2048_r16"])
