@@ -7,7 +7,7 @@ with the deferred subtraction, bit for bit), sampled rows of P = D Q, the orthon
 property (P^T P = I, P = P^ R with R upper triangular and a positive diagonal), sampled rows of
 Q = D^T P^, and sampled elements of the reconstruction P^ Q^T.  The same walk runs over the
 hidden-5120 block with bf16 gradients (its 20480 x 5120 matrix is the largest of the workloads)
-at ranks 128, 32 and 64."""
+at ranks 128, 32 and 64, and over a single matrix of more than 2^31 elements."""
 import numpy as np
 import pytest
 import torch
@@ -24,6 +24,9 @@ CASES = [
     ("cfg5_stage8_h4096", "f32", [16, 16, 64, 64, 128, 8], 1_610_612_736),
     # the hidden-5120 block (its 20480 x 5120 matrix is the largest of the workloads) with bf16 gradients
     ("cfg4_gpt_h5120_bf16", "bf16", [128, 128, 32, 64], 314_572_800),
+    # one matrix of more than 2^31 elements (an embedding-sized gradient): element and byte offsets
+    # beyond 32 bits in every pass and in the sampler
+    ((262144, 8704), "f32", [16, 16, 64], 2_281_701_376),
 ]
 
 
@@ -39,8 +42,11 @@ def _groups(sizes, k):
 
 @pytest.mark.parametrize("name,dtype,RANKS,elements", CASES)
 def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, elements):
-    w = gen.WORKLOADS[name]
-    shapes = [(s.m, s.n) for s in w["layers"]] * w.get("repeat", 1)
+    if isinstance(name, tuple):
+        shapes = [name]
+    else:
+        w = gen.WORKLOADS[name]
+        shapes = [(s.m, s.n) for s in w["layers"]] * w.get("repeat", 1)
     assert sum(m * n for m, n in shapes) == elements
     NT = len(shapes)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -59,7 +65,7 @@ def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, eleme
     seeder = edgc.Context(0, max_bins=16, max_rank=4, max_rows=64, max_cols=64)
     for i in range(NT):
         seeder.init_q(Q[i], 0, RANKS[0], 900 + i)           # seeded start of the warm-started factor
-    members = _groups([m * n for m, n in shapes], 2)
+    members = _groups([m * n for m, n in shapes], min(2, NT))
     ctxs, tens = [], []
     for idx in members:
         c = edgc.Context(0, max_bins=16, max_rank=rmax, max_rows=64, max_cols=64)
@@ -72,6 +78,9 @@ def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, eleme
     pos = [(rng.integers(0, m, 48), rng.integers(0, n, 48)) for m, n in shapes]
     rows = [rng.integers(0, m, 3) for m, _ in shapes]
     cols = [rng.integers(0, n, 3) for _, n in shapes]
+    for (ii, jj), rr, cc, (m, n) in zip(pos, rows, cols, shapes):      # the far corner is always among them
+        ii[-3:], jj[-3:] = [m - 1, m - 1, m - 2], [n - 1, 0, n - 2]
+        rr[-1], cc[-1] = m - 1, n - 1
     idx_cache = {}
     r_prev, d_prev, out_prev = None, None, None
     for step, r in enumerate(RANKS):
