@@ -295,22 +295,19 @@ def test_measure_device_peaks_copies_and_reports_physical_figures():
     c = ctx()
     a = torch.randn(1 << 26, device="cuda")                 # 256 MiB
     b = torch.zeros_like(a)
-    try:
-        # after the call buf_b holds the copy of buf_a, except at its start, where the read and the
-        # MFMA kernel left one float per thread (8 blocks per compute unit of 256 threads)
-        pk = c.measure_device_peaks(a, b, reps=3)
-        sink_floats = 8 * 256 * 256
-        assert torch.equal(a[sink_floats:], b[sink_floats:])
-        assert pk["bytes"] == a.numel() * 4
-        assert 500.0 < pk["read_gbs"] < 20000.0 and 500.0 < pk["copy_gbs"] < 20000.0
-        assert 100.0 < pk["mfma_bf16_tflops"] < 2600.0
-        with pytest.raises(edgc.EdgcError):
-            c.measure_device_peaks(a, a, reps=3)
-        with pytest.raises(edgc.EdgcError):
-            c.measure_device_peaks(a[:1024], b[:1024], reps=3)         # below the minimum size
-        with pytest.raises(edgc.EdgcError):
-            c.measure_device_peaks(a[1:1 + (1 << 22)], b[: 1 << 22], reps=3)   # misaligned
-        with pytest.raises(edgc.EdgcError):
-            c.measure_device_peaks(a, b, reps=0)
-    finally:
-        c.close()
+    # after the call buf_b holds the copy of buf_a, except at its start, where the read and the
+    # MFMA kernel left one float per thread (8 blocks per compute unit of 256 threads)
+    pk = c.measure_device_peaks(a, b, reps=3)
+    sink_floats = 8 * 256 * 256
+    assert torch.equal(a[sink_floats:], b[sink_floats:])
+    assert pk["bytes"] == a.numel() * 4
+    assert 500.0 < pk["read_gbs"] < 20000.0 and 500.0 < pk["copy_gbs"] < 20000.0
+    assert 100.0 < pk["mfma_bf16_tflops"] < 2600.0
+    with pytest.raises(edgc.EdgcError):
+        c.measure_device_peaks(a, a, reps=3)
+    with pytest.raises(edgc.EdgcError):
+        c.measure_device_peaks(a[:1024], b[:1024], reps=3)         # below the minimum size
+    with pytest.raises(edgc.EdgcError):
+        c.measure_device_peaks(a[1:1 + (1 << 22)], b[: 1 << 22], reps=3)   # misaligned
+    with pytest.raises(edgc.EdgcError):
+        c.measure_device_peaks(a, b, reps=0)
