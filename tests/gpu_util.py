@@ -9,7 +9,7 @@ _ctx = {}
 
 def ctx(max_bins=1 << 20, max_rank=128, max_rows=20480, max_cols=20480):
     key = (max_bins, max_rank, max_rows, max_cols)
-    if key not in _ctx:
+    if key not in _ctx or not getattr(_ctx[key], "_h", None):     # (re)create when a test closed it
         _ctx[key] = edgc.Context(0, max_bins, max_rank, max_rows, max_cols)
     return _ctx[key]
 
