@@ -184,13 +184,25 @@ __global__ __launch_bounds__(kMMBlock) void k_minmax(const EntGroup grp,
             cur.advance(G, geom.ipc);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            if (mask[u] == (1u << VEC) - 1u) {
+                // a whole item: no branch per element, a non-finite value stands in as the bound itself
 #pragma unroll
-            for (int p = 0; p < VEC; ++p)
-                if (((mask[u] >> p) & 1u) && finite_f32(v[u][p])) {
-                    lo = fminf(lo, v[u][p]);
-                    hi = fmaxf(hi, v[u][p]);
+                for (int p = 0; p < VEC; ++p) {
+                    const float x = v[u][p];
+                    const bool fin = finite_f32(x);
+                    lo = fminf(lo, fin ? x : lo);
+                    hi = fmaxf(hi, fin ? x : hi);
                 }
+            } else {
+#pragma unroll
+                for (int p = 0; p < VEC; ++p)
+                    if (((mask[u] >> p) & 1u) && finite_f32(v[u][p])) {
+                        lo = fminf(lo, v[u][p]);
+                        hi = fmaxf(hi, v[u][p]);
+                    }
+            }
+        }
     }
     }
 
@@ -273,9 +285,14 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
 
     const float lo = rp->lo, scale = rp->scale;
     const float fbins = static_cast<float>(bins);
+    // largest float below the bin count: truncating a value clamped to [0, top] gives 0 .. bins - 1,
+    // the same index as min(trunc(max(f, 0)), bins - 1)
+    const float top = __uint_as_float(__float_as_uint(fbins) - 1u);
     const uint32_t rep = threadIdx.x & ((1u << rep_shift) - 1u);
     const bool count_nf = (blockIdx.y == 0);
+    const bool whole = (gridDim.y == 1);      // one slice holds every bin
     unsigned long long nf = 0;
+    uint32_t seen = 0, fin_seen = 0;          // elements of whole items taken below, finite ones among them
 
     const uint64_t G = static_cast<uint64_t>(gridDim.x) * kHistBlock;
     constexpr int U = 4;
@@ -297,7 +314,22 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
             cur.advance(G, geom.ipc);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            if (whole && mask[u] == (1u << VEC) - 1u) {
+                // a whole item with every bin in this block's slice: no branch per element.  The index
+                // of a non-finite value is some valid bin (the clamp maps NaN to 0) and it adds 0.
+#pragma unroll
+                for (int p = 0; p < VEC; ++p) {
+                    const float x = v[u][p];
+                    const float t = __fsub_rn(x, lo);
+                    const float f = __builtin_amdgcn_fmed3f(__fmul_rn(t, scale), 0.0f, top);
+                    const uint32_t inc = finite_f32(x) ? 1u : 0u;
+                    atomicAdd(&h[(static_cast<uint32_t>(f) << rep_shift) | rep], inc);
+                    fin_seen += inc;
+                }
+                seen += VEC;
+                continue;
+            }
 #pragma unroll
             for (int p = 0; p < VEC; ++p) {
                 if (!((mask[u] >> p) & 1u)) continue;
@@ -311,8 +343,10 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
                 const uint32_t rel = b - bin_base;
                 if (rel < local_n) atomicAdd(&h[(rel << rep_shift) | rep], 1u);
             }
+        }
     }
     }
+    nf += seen - fin_seen;
     __syncthreads();
 
     // fold the replicas and flush non-empty bins
