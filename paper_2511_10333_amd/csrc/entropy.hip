@@ -169,19 +169,24 @@ __global__ __launch_bounds__(kMMBlock) void k_minmax(const EntGroup grp,
     for (uint32_t ti = 0; ti < grp.count; ++ti) {
     const SampleGeom& geom = grp.geom[ti];
     const T* __restrict__ g = static_cast<const T*>(grp.base[ti]);
+    // a block takes one contiguous range of the buffer's items (the sets are the same as with any
+    // other assignment; consecutive rounds of a block then read consecutive memory)
+    const uint64_t per = (geom.n_items + gridDim.x - 1) / gridDim.x;
+    const uint64_t begin = static_cast<uint64_t>(blockIdx.x) * per;
+    const uint64_t end = min(begin + per, geom.n_items);
     ItemCursor cur;
-    cur.init(gtid, G, geom.ipc);
-    while (cur.item < geom.n_items) {
+    cur.init(begin + threadIdx.x, kMMBlock, geom.ipc);
+    while (cur.item < end) {
         float v[U][VEC];
         uint32_t mask[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             mask[u] = 0;
-            if (cur.item < geom.n_items) {
+            if (cur.item < end) {
                 const uint64_t i0 = cur.elem0(geom, VEC);
                 if (i0 < geom.n) mask[u] = load_item<T, VEC>(g, i0, geom.n, v[u]);
             }
-            cur.advance(G, geom.ipc);
+            cur.advance(kMMBlock, geom.ipc);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -294,24 +299,26 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
     unsigned long long nf = 0;
     uint32_t seen = 0, fin_seen = 0;          // elements of whole items taken below, finite ones among them
 
-    const uint64_t G = static_cast<uint64_t>(gridDim.x) * kHistBlock;
     constexpr int U = 4;
     for (uint32_t ti = 0; ti < grp.count; ++ti) {
     const SampleGeom& geom = grp.geom[ti];
     const T* __restrict__ g = static_cast<const T*>(grp.base[ti]);
+    const uint64_t per = (geom.n_items + gridDim.x - 1) / gridDim.x;      // one contiguous range per block
+    const uint64_t begin = static_cast<uint64_t>(blockIdx.x) * per;
+    const uint64_t end = min(begin + per, geom.n_items);
     ItemCursor cur;
-    cur.init(static_cast<uint64_t>(blockIdx.x) * kHistBlock + threadIdx.x, G, geom.ipc);
-    while (cur.item < geom.n_items) {
+    cur.init(begin + threadIdx.x, kHistBlock, geom.ipc);
+    while (cur.item < end) {
         float v[U][VEC];
         uint32_t mask[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             mask[u] = 0;
-            if (cur.item < geom.n_items) {
+            if (cur.item < end) {
                 const uint64_t i0 = cur.elem0(geom, VEC);
                 if (i0 < geom.n) mask[u] = load_item<T, VEC>(g, i0, geom.n, v[u]);
             }
-            cur.advance(G, geom.ipc);
+            cur.advance(kHistBlock, geom.ipc);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
