@@ -40,8 +40,8 @@ def test_flat_buffer_of_1e9_elements_sampled(dtype):
     """The flat buffer at its full size of 1e9 elements (generated on the device: Laplace(0, 1e-3)
     with 0.1 % of the values at 100 times the scale).  The oracle gets the sample: its own index
     set gathers the sampled elements, and its estimator runs over them with every element taken;
-    counts are compared bit for bit.  Strides 1000, 100 and 10 (the 100 % cell is covered on the
-    2^26-element slice above)."""
+    counts are compared bit for bit, at strides 1000, 100 and 10 on three bin counts; with every
+    element sampled (4096 bins) the oracle reads the whole buffer."""
     n = 1_000_000_000
     g = torch.Generator(device="cuda").manual_seed(3)
     x = torch.empty(n, device="cuda")
@@ -67,7 +67,15 @@ def test_flat_buffer_of_1e9_elements_sampled(dtype):
             assert got.n_sampled == host.size
             assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts), (stride, bins)
             assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5
-    del x
+    # every element sampled: the oracle reads the whole buffer
+    host = to_host(x) if dtype == "bf16" else x.cpu().numpy()
+    ref = orc.entropy(host, 1, 64, 0, 5, 4096)
+    counts = torch.empty(4096, dtype=torch.int64, device="cuda")
+    got = c.entropy_estimate(x, 1, 64, 0, 5, 4096, None, counts)
+    assert (got.n_sampled, got.n_nonfinite, got.lo, got.hi) == (n, 0, ref.lo, ref.hi)
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
+    assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5
+    del x, host
     torch.cuda.empty_cache()
 
 
