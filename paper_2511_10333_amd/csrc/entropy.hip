@@ -115,6 +115,24 @@ __device__ __forceinline__ uint32_t load_item(const T* __restrict__ g, uint64_t 
     }
 }
 
+// The VEC elements of a whole item from its 16 raw bytes.
+template <typename T, int VEC>
+__device__ __forceinline__ void unpack_item(const uint4& q, float (&v)[VEC])
+{
+    static_assert(VEC * sizeof(T) == 16, "a vector item is 16 bytes");
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) v[p] = __uint_as_float(w[p]);
+    } else {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            v[2 * p]     = __uint_as_float(w[p] << 16);
+            v[2 * p + 1] = __uint_as_float(w[p] & 0xffff0000u);
+        }
+    }
+}
+
 // Walks the items owned by one thread: item t, t + G, t + 2G, ... without a
 // division in the loop.  item -> (k-th sampled chunk, e-th item in it).
 struct ItemCursor {
@@ -176,6 +194,43 @@ __global__ __launch_bounds__(kMMBlock) void k_minmax(const EntGroup grp,
     const uint64_t end = min(begin + per, geom.n_items);
     ItemCursor cur;
     cur.init(begin + threadIdx.x, kMMBlock, geom.ipc);
+    if constexpr (VEC > 1) {
+        // rounds of U whole items per thread with the next round's loads in flight (see k_hist)
+        const uint64_t fast_end = (geom.n_items >= geom.ipc) ? min(end, geom.n_items - geom.ipc) : 0;
+        auto round_fits = [&]() { return cur.item + static_cast<uint64_t>(U - 1) * kMMBlock < fast_end; };
+        auto fetch_raw = [&](uint4 (&raw)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                raw[u] = *reinterpret_cast<const uint4*>(g + cur.elem0(geom, VEC));
+                cur.advance(kMMBlock, geom.ipc);
+            }
+        };
+        auto fold_raw = [&](const uint4 (&raw)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float v[VEC];
+                unpack_item<T, VEC>(raw[u], v);
+#pragma unroll
+                for (int p = 0; p < VEC; ++p) {
+                    const bool fin = finite_f32(v[p]);
+                    lo = fminf(lo, fin ? v[p] : lo);
+                    hi = fmaxf(hi, fin ? v[p] : hi);
+                }
+            }
+        };
+        if (round_fits()) {
+            uint4 ra[U], rb[U];
+            fetch_raw(ra);
+            while (true) {
+                if (!round_fits()) { fold_raw(ra); break; }
+                fetch_raw(rb);
+                fold_raw(ra);
+                if (!round_fits()) { fold_raw(rb); break; }
+                fetch_raw(ra);
+                fold_raw(rb);
+            }
+        }
+    }
     while (cur.item < end) {
         float v[U][VEC];
         uint32_t mask[U];
@@ -308,6 +363,51 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(
     const uint64_t end = min(begin + per, geom.n_items);
     ItemCursor cur;
     cur.init(begin + threadIdx.x, kHistBlock, geom.ipc);
+    if constexpr (VEC > 1) {
+        // Rounds of U whole items per thread, the next round's loads issued before the current round is
+        // binned.  Every item before the buffer's last sampled chunk is whole (the chunk size is a multiple
+        // of VEC), so these loads need no condition and stay in flight across the binning.
+        const uint64_t fast_end = (geom.n_items >= geom.ipc) ? min(end, geom.n_items - geom.ipc) : 0;
+        auto round_fits = [&]() { return cur.item + static_cast<uint64_t>(U - 1) * kHistBlock < fast_end; };
+        auto fetch_raw = [&](uint4 (&raw)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                raw[u] = *reinterpret_cast<const uint4*>(g + cur.elem0(geom, VEC));
+                cur.advance(kHistBlock, geom.ipc);
+            }
+        };
+        auto bin_raw = [&](const uint4 (&raw)[U]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float v[VEC];
+                unpack_item<T, VEC>(raw[u], v);
+#pragma unroll
+                for (int p = 0; p < VEC; ++p) {
+                    const float t = __fsub_rn(v[p], lo);
+                    const float f = __builtin_amdgcn_fmed3f(__fmul_rn(t, scale), 0.0f, top);
+                    const uint32_t inc = finite_f32(v[p]) ? 1u : 0u;
+                    atomicAdd(&h[(static_cast<uint32_t>(f) << rep_shift) | rep], inc);
+                    fin_seen += inc;
+                }
+            }
+            seen += U * VEC;
+        };
+        // (measured on a 1e9-element buffer: with every element sampled 0.86 instead of 0.91 ms on fp32 and
+        // 0.51 instead of 0.63 ms on bf16; on the 10 % sample, 256-byte runs 2.5 KB apart, 0.19 instead of
+        // 0.15 ms, so strided samples keep the plain loop below)
+        if (whole && geom.stride == 1 && round_fits()) {
+            uint4 ra[U], rb[U];
+            fetch_raw(ra);
+            while (true) {
+                if (!round_fits()) { bin_raw(ra); break; }
+                fetch_raw(rb);
+                bin_raw(ra);
+                if (!round_fits()) { bin_raw(rb); break; }
+                fetch_raw(ra);
+                bin_raw(rb);
+            }
+        }
+    }
     while (cur.item < end) {
         float v[U][VEC];
         uint32_t mask[U];
