@@ -38,7 +38,7 @@ void free_batch(edgc_ctx* ctx)
 
 void free_scratch(Scratch& s)
 {
-    void* ptrs[] = {s.mm_part, s.done_counter, s.counts, s.nonfinite, s.range, s.result_dev,
+    void* ptrs[] = {s.mm_part, s.done_counter, s.counts, s.range, s.result_dev,
                     s.part, s.gram_part, s.gram, s.rinv, s.pt};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -87,7 +87,6 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     ok = ok && dev_alloc(&s.mm_part, 2 * kMaxReduceBlocks) == hipSuccess;
     ok = ok && dev_alloc(&s.done_counter, 4) == hipSuccess;
     ok = ok && dev_alloc(&s.counts, max_bins) == hipSuccess;
-    ok = ok && dev_alloc(&s.nonfinite, 1) == hipSuccess;
     ok = ok && hipMalloc(&s.range, 64) == hipSuccess;
     ok = ok && hipMalloc(&s.result_dev, sizeof(edgc_entropy_result)) == hipSuccess;
     ok = ok && dev_alloc(&s.part, s.part_elems) == hipSuccess;

@@ -17,7 +17,6 @@ struct Scratch {
     float*              mm_part      = nullptr;  // [2 * kMaxReduceBlocks] per-block (lo, hi)
     unsigned int*       done_counter = nullptr;  // [4] last-block tickets, zero between calls
     unsigned long long* counts       = nullptr;  // [max_bins] histogram when the caller gives none
-    unsigned long long* nonfinite    = nullptr;  // [1]
     void*               range        = nullptr;  // RangeParams
     void*               result_dev   = nullptr;  // edgc_entropy_result
     // compress / decompress
