@@ -604,10 +604,11 @@ static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins, const fl
     const size_t lds = static_cast<size_t>(bins_local << rep_shift) * sizeof(uint32_t);
     // enough items per block that zeroing and flushing the LDS histogram stays small
     const int per_thread = small ? 8 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
-    // a histogram of more than 64 KiB leaves room for one block per CU: then a block of 1024 threads
-    // (1e9 fp32 elements on 65536 bins: 1.78 instead of 3.60 ms); two blocks of 512 otherwise (on 4096
-    // bins 0.86 against 0.94 ms with 1024)
-    if (lds > 65536) {
+    // One block of 1024 threads per CU when a histogram of more than 64 KiB leaves room for one block only
+    // (1e9 fp32 elements on 65536 bins: 1.6 instead of 3.6 ms) and for samples of 8 Mi items or more (1e8
+    // fp32 elements on 4096 bins: 0.13 instead of 0.18 ms; 1e9: 0.83 instead of 0.86 ms); two blocks of
+    // 512 per CU otherwise (1e7 bf16 elements: 0.040 against 0.044 ms; two blocks of 1024: slower throughout)
+    if (lds > 65536 || g.n_items >= (8ull << 20)) {
         const uint32_t gx = grid_for(g.n_items, kHistBlockFat, per_thread, ctx->num_cu);
         EDGC_LAUNCH(ctx, st, KID_HIST, sample_bytes * ny, 0.0,
                     k_hist<T, VEC, kHistBlockFat><<<dim3(gx, ny), kHistBlockFat, lds, st>>>(
