@@ -250,6 +250,32 @@ def test_stage_entropy_over_separate_buffers(dtype, stride, chunk, bins):
         c.entropy_estimate([], stride, chunk, 9, 1, bins)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stage_entropy_large_union_sample(dtype):
+    """A union sample large enough for the launch shapes of large samples (one block of 1024 threads
+    per compute unit, whole-item rounds with the next loads in flight) over several buffers of
+    different sizes, with a ragged tail and a few non-finite values."""
+    sizes = [(1 << 25) + 5, 1 << 24, (1 << 23) + 64, 12_345_679]
+    bufs = [gen.laplace_mixture(n, 70 + i, dtype=dtype, scale=1e-3 * (1 + i)) for i, n in enumerate(sizes)]
+    nan, inf = (0x7fc0, 0x7f80) if dtype == "bf16" else (np.float32(np.nan), np.float32(np.inf))
+    bufs[0][12345] = nan
+    bufs[1][-1] = inf
+    bufs[3][7] = nan
+    dev = [to_dev(b) for b in bufs]
+    c = edgc.Context(0, max_bins=65536, max_rank=4, max_rows=64, max_cols=64)
+    for stride, chunk, bins in [(1, 64, 4096), (1, 64, 65536), (3, 64, 1024)]:
+        counts = torch.zeros(bins, dtype=torch.int64, device="cuda")
+        got = c.entropy_estimate(dev, stride, chunk, 9, 2, bins, counts_out=counts)
+        want, n_s = _oracle_union_entropy(bufs, stride, chunk, 9, 2, bins)
+        assert got.n_sampled == n_s == want.n_sampled
+        assert got.n_nonfinite == want.n_nonfinite and (stride != 1 or got.n_nonfinite == 3)
+        assert (got.lo, got.hi) == (want.lo, want.hi)
+        assert np.array_equal(counts.cpu().numpy().astype(np.uint64), want.counts), (stride, bins)
+        assert int(counts.sum()) == n_s - got.n_nonfinite
+        assert abs(got.H_bits - want.H_bits) <= 1e-5 and abs(got.h_diff_nats - want.h_diff_nats) <= 1e-5
+    c.close()
+
+
 # ---------------------------------------------------------------------------
 # the batched calls under HIP graph capture: no allocation, no synchronisation, no memset
 # node inside them, so a captured step replays like the eager one
