@@ -622,11 +622,11 @@ extern "C" int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dty
     for (uint32_t i = 0; rc == EDGC_OK && i < n_ranks; ++i) {
         const uint32_t r = ranks[i];
         double t_c = 0.0, t_d = 0.0;
-        // round 0 is untimed and starts from a zero residual and fresh Q columns
+        // repetition 0 is untimed and starts from a zero residual and fresh Q columns
         rc = edgc_init_q(ctx, Q, n, ldq, 0, r, 0x5eedULL + r, hip_stream);
         for (uint32_t rep = 0; rc == EDGC_OK && rep <= reps; ++rep) {
             if (!hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) break;
-            // a deferred compress needs D and the factors of a step before it: not in round 0
+            // a deferred compress needs D and the factors of a step before it: not in repetition 0
             rc = compress_one(ctx, grad, dtype, m, n, ld, residual, rep == 0, Q, ldq, P, ldp, r, 1,
                               rep == 0 ? 0u : defer, hip_stream);
             if (rc != EDGC_OK) break;
