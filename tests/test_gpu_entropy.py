@@ -164,3 +164,44 @@ def test_result_reaches_pageable_and_pinned_host_memory_alike():
     assert a == edgc.EntropyResult.from_buffer(odd.numpy().tobytes())
     want = orc.entropy(x, 100, 64, 3, 7, 1024)
     assert a.n_sampled == want.n_sampled and abs(a.H_bits - want.H_bits) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_seeded_sweep_of_sizes_offsets_strides_chunks_and_bins(dtype):
+    """Sixty seeded draws of (size, start offset, stride, chunk, bins, step, seed) on slices of one
+    buffer, some with NaN and -Inf planted: sizes around the chunk and item boundaries up to samples
+    that take the launch shapes of large samples, aligned and unaligned starts.  Counts, range and
+    non-finite count bit-exact, entropy to 1e-5; a draw whose sample is empty must fail on both sides."""
+    rng = np.random.default_rng(2024 if dtype == "f32" else 2025)
+    big = gen.laplace_mixture(72_000_000, 99, dtype=dtype)
+    c = edgc.Context(0, max_bins=65536, max_rank=4, max_rows=64, max_cols=64)
+    sizes = [1, 7, 63, 64, 65, 4095, 4096, 4097, 100_003, 1 << 20, 3_000_001, 20_000_000, 33_554_433,
+             39_999_999, 67_108_871]
+    for it in range(60):
+        n = int(rng.choice(sizes))
+        off = int(rng.choice([0, 0, 0, 1, 3, 4, 8]))
+        stride = int(rng.choice([1, 1, 2, 3, 7, 10, 100, 1000]))
+        chunk = int(rng.choice([1, 8, 16, 48, 64, 64, 256, 4096]))
+        bins = int(rng.choice([16, 256, 1024, 4096, 16384, 32768, 65536]))
+        step, seed = int(rng.integers(0, 1000)), int(rng.integers(0, 1 << 30))
+        host = big[off:off + n].copy()
+        if n > 100 and it % 4 == 0:
+            host[rng.integers(0, n, 3)] = 0x7fc0 if dtype == "bf16" else np.float32(np.nan)
+            host[rng.integers(0, n)] = 0xff80 if dtype == "bf16" else np.float32(-np.inf)
+        dev = to_dev(np.concatenate([np.zeros(off, dtype=host.dtype), host]))[off:]
+        case = (it, n, off, stride, chunk, bins, step, seed)
+        try:
+            ref = orc.entropy(host, stride, chunk, seed, step, bins)
+        except orc.OracleError:
+            with pytest.raises(edgc.EdgcError):
+                c.entropy_estimate(dev, stride, chunk, seed, step, bins)
+            continue
+        counts = torch.zeros(bins, dtype=torch.int64, device="cuda")
+        got = c.entropy_estimate(dev, stride, chunk, seed, step, bins, None, counts)
+        assert (got.n_sampled, got.n_nonfinite) == (ref.n_sampled, ref.n_nonfinite), case
+        assert (got.lo, got.hi) == (ref.lo, ref.hi), case
+        assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts), case
+        assert abs(got.H_bits - ref.H_bits) <= 1e-5, case
+        # (a sample of one value has no width: -inf on both sides)
+        assert got.h_diff_nats == ref.h_diff_nats or abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5, case
+    c.close()
