@@ -371,7 +371,9 @@ static void contract_P(const float* D, uint32_t m, uint32_t n, const float* Qop,
 }
 
 /* Q = D^T * Pop   (n x m) * (m x r); fp64 accumulation over i = 0..m-1 in order.
- * Threads own disjoint column ranges of D, so every (j, c) sum is sequential. */
+ * Threads own disjoint ranges of JB columns of D and keep the JB * r sums of their
+ * range side by side, so that D is read along its rows; every (j, c) sum is still
+ * the plain sequential sum over i, and the result does not depend on JB. */
 static void contract_Q(const float* D, uint32_t m, uint32_t n, const float* Pop, uint32_t r,
                        int round_d, float* Q, uint32_t ldq)
 {

@@ -11,8 +11,11 @@
  * Only tests, the smoke check and the benchmark's cpu_baseline leg may call
  * this library.  It shares no code, header, table or constant generator with
  * the HIP implementation.  Storage is fp32 where the method stores fp32;
- * every accumulation is fp64; no blocking, fusion or reordering beyond what
- * the definitions state (OpenMP only splits independent output rows).
+ * every accumulation is fp64; no fusion and no reordering of any sum beyond
+ * what the definitions state.  OpenMP only splits independent outputs: rows
+ * of P and of M^, and, for Q = D^T P^, ranges of 64 columns of D per thread
+ * (a loop interchange so that D is walked along its rows; every sum over
+ * i = 0 .. m-1 still runs in that order, one term at a time).
  *
  * Readings of the paper where it is silent or ambiguous (each one is also
  * restated at the function that applies it):
