@@ -251,13 +251,20 @@ int oracle_select_rank(oracle_rank_state* st, const double* H_window, uint32_t k
 {
     if (!st || !H_window || !prm || !out || k == 0) return ORACLE_EINVAL;
     const uint32_t mm = prm->m < prm->n ? prm->m : prm->n;
-    if (mm == 0 || prm->r_max == 0 || prm->r_max > mm || prm->r_min > prm->r_max)
+    /* rank 0 is the warm-up answer, so the lower bound is at least 1 */
+    if (mm == 0 || prm->r_min == 0 || prm->r_max > mm || prm->r_min > prm->r_max)
         return ORACLE_EINVAL;
     const uint32_t r_ref = prm->r_ref ? prm->r_ref : prm->r_max;
     if (r_ref > mm) return ORACLE_EINVAL;
     for (uint32_t i = 0; i < k; ++i) if (!isfinite(H_window[i])) return ORACLE_ENONFINITE;
     for (uint32_t i = 1; i < prm->n_allowed; ++i)
         if (prm->allowed[i] <= prm->allowed[i - 1]) return ORACLE_EINVAL;
+    if (prm->allowed && prm->n_allowed) {           /* R7: some allowed rank must lie in the bounds */
+        int inside = 0;
+        for (uint32_t i = 0; i < prm->n_allowed; ++i)
+            if (prm->allowed[i] >= prm->r_min && prm->allowed[i] <= prm->r_max) inside = 1;
+        if (!inside) return ORACLE_EINVAL;
+    }
 
     /* window-mean entropy (Sec. IV-D-3) */
     double Hm = 0.0;
@@ -312,11 +319,18 @@ int oracle_select_rank(oracle_rank_state* st, const double* H_window, uint32_t k
     st->r_prev = r;
 
     uint32_t rank = (uint32_t)r;
-    if (prm->allowed && prm->n_allowed) {           /* R7: snap up */
-        uint32_t pick = prm->allowed[prm->n_allowed - 1];
-        for (uint32_t i = 0; i < prm->n_allowed; ++i)
-            if (prm->allowed[i] >= rank) { pick = prm->allowed[i]; break; }
-        rank = pick;
+    if (prm->allowed && prm->n_allowed) {
+        /* R7: snap up, but never past r_max (Sec. IV-D-1: from r_max on compression no
+         * longer pays, and Algorithm 1 ends with the clamp to [r_min, r_max]): when no
+         * allowed rank lies in [rank, r_max], the largest allowed rank <= r_max. */
+        uint32_t up = 0, below = 0;
+        for (uint32_t i = 0; i < prm->n_allowed; ++i) {
+            const uint32_t a = prm->allowed[i];
+            if (a < prm->r_min || a > prm->r_max) continue;
+            if (a >= rank && !up) up = a;
+            if (a < rank) below = a;
+        }
+        rank = up ? up : below;
     }
     out->rank = rank;
     out->T_com = prm->eta * (double)rank;           /* T_com(r) = eta r, Sec. IV-D-1 */

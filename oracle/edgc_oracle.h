@@ -36,7 +36,10 @@
  *   R6  The reference point of Theorem 3 is anchored: H0 = mean entropy of
  *       the first window, r0 = r_ref (r_max unless the caller overrides it).
  *   R7  Algorithm 1 runs on an un-snapped integer state r_prev; the emitted
- *       rank is the smallest allowed value >= that state.
+ *       rank is the smallest allowed value >= that state inside [r_min, r_max],
+ *       or, when there is none, the largest allowed value inside the bounds
+ *       (r_max of Sec. IV-D-1 is never exceeded); an allowed set with no
+ *       member inside the bounds is an error, and so is r_min = 0.
  *   R8  The compressor is one (or more) warm-started subspace iteration
  *       steps: P = D Q, orthonormalise P, Q = D^T P, M^ = P Q^T with
  *       D = G + E_old, E_new = D - M^ (PowerSGD, the method the paper cites).

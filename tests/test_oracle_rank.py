@@ -142,6 +142,23 @@ def test_allowed_set_snaps_up_but_state_stays_unsnapped():
     assert ranks == [64, 64, 64, 32, 32, 16, 8, 4, 4]
 
 
+def test_snapping_never_leaves_the_rank_bounds():
+    # Sec. IV-D-1: r_max is where compression stops paying, and Algorithm 1 ends with the clamp to
+    # [r_min, r_max]: with r_max = 48 the set {4, 8, 16, 32, 64} must never emit 64.  Hand table:
+    # the state walks 40, 32, 24, ... down from r_ref = r_max = 48 and back up to 48.
+    prm = _prm(r_min=6, r_max=48, step_limit=8, allowed=[4, 8, 16, 32, 64])
+    st = orc.RankState()
+    orc.select_rank(st, [0.0], 1, prm)
+    down = [(orc.select_rank(st, [-5.0], 1, prm).rank, st.r_prev) for _ in range(7)]
+    assert down == [(32, 40), (32, 32), (32, 24), (16, 16), (8, 8), (8, 6), (8, 6)]   # 4 < r_min is never emitted
+    up = [(orc.select_rank(st, [1.0], 1, prm).rank, st.r_prev) for _ in range(7)]
+    assert up == [(16, 14), (32, 22), (32, 30), (32, 38), (32, 46), (32, 48), (32, 48)]  # 64 > r_max: 32 instead
+    # no allowed rank inside the bounds, or a lower bound of 0 (rank 0 means warm-up): rejected
+    for bad in [_prm(r_min=33, r_max=63, allowed=[4, 8, 16, 32, 64]), _prm(r_min=0)]:
+        with pytest.raises(orc.OracleError):
+            orc.select_rank(orc.RankState(), [0.0], 1, bad)
+
+
 def test_warmup_lasts_at_least_ten_percent():
     prm = _prm(total_iters=200, min_warmup_frac=0.10)
     st = orc.RankState()
