@@ -90,9 +90,10 @@ int edgc_profile_begin(edgc_ctx* ctx, uint32_t max_launches);
 int edgc_profile_end(edgc_ctx* ctx, edgc_kernel_stat* out, uint32_t cap, uint32_t* n_out);
 
 /* ------------------------------------------------------------------------
- * 1. Gradient entropy of a down-sampled buffer (GDS, Sec. IV-B: "selects a
- *    data subset ... based on a gradient sampling rate beta"; entropy as in
- *    Definition 1 / Eq. (1), estimated with an equal-width histogram).
+ * 1. Gradient entropy of a down-sampled buffer (GDS, Sec. IV-B: a subset of
+ *    each iteration's gradient, chosen at gradient sampling rate beta;
+ *    entropy as in Definition 1 / Eq. (1), estimated with an equal-width
+ *    histogram).
  *
  *    Sample: element i of the flat buffer is taken iff
  *        ((i / chunk) mod stride) == slot,  slot = mix64(seed, step) mod stride,
@@ -148,8 +149,10 @@ int edgc_sample_indices(edgc_ctx* ctx, uint64_t n_elems, uint64_t stride, uint32
  *    iters_seen >= min_warmup_frac * total_iters; compression then starts from
  *    r_prev = r_ref.  Algorithm 1: move r_prev towards r_new by at most
  *    step_limit (Constraint 2), clamp to [r_min, r_max], emit the smallest
- *    allowed rank >= r_prev (or r_prev itself when no set is given), and
- *    T_com = eta * rank.  Entropies are the h_diff_nats values above.
+ *    allowed rank >= r_prev inside [r_min, r_max], or the largest allowed
+ *    rank inside the bounds when there is none (r_prev itself when no set is
+ *    given), and T_com = eta * rank.  The emitted rank never leaves the
+ *    bounds.  Entropies are the h_diff_nats values above.
  * ------------------------------------------------------------------------ */
 typedef struct {
     uint32_t m, n;              /* reference matrix shape for g(r; m, n)                  */
@@ -179,8 +182,9 @@ typedef struct {
     double   T_com;
 } edgc_rank_decision;
 
-/* Errors: EDGC_EINVAL for null pointers, k == 0, inconsistent bounds or a
- * non-ascending allowed set; EDGC_ENONFINITE for a NaN/Inf entropy. */
+/* Errors: EDGC_EINVAL for null pointers, k == 0, bounds that are not
+ * 1 <= r_min <= r_max <= min(m, n), a non-ascending allowed set or one with no
+ * member inside [r_min, r_max]; EDGC_ENONFINITE for a NaN/Inf entropy. */
 int edgc_select_rank(edgc_rank_state* state, const double* H_window, uint32_t k,
                      uint64_t iters_in_window, const edgc_rank_params* params,
                      edgc_rank_decision* out);

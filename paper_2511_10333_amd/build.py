@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libedgc.so")
-SOURCES = ["edgc_api.hip", "entropy.hip", "compress.hip", "peaks.hip", "rank_select.cpp", "dac_host.cpp"]
+SOURCES = ["edgc_api.hip", "entropy.hip", "compress.hip", "pass_p_full.hip", "decompress_full.hip", "peaks.hip", "rank_select.cpp", "dac_host.cpp"]
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
@@ -24,14 +24,16 @@ COMMON = [
 
 
 def build(verbose: bool = False) -> str:
-    """Always recompiles every source (a few tens of seconds)."""
+    """Always recompiles every source (a few tens of seconds).  EDGC_EXTRA_HIPCC_FLAGS adds
+    flags for developer builds (e.g. -DEDGC_CHOL_TIMING)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = os.environ.get("EDGC_EXTRA_HIPCC_FLAGS", "").split()
     objs = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
         objs.append(obj)
-        cmd = [hipcc] + COMMON + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + COMMON + extra + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))

@@ -29,96 +29,13 @@
 // MFMA 32x32x16 operand layout (64 lanes): lane l supplies A[i = l%32][k = 8*(l/32) .. +8]
 // and B[k = 8*(l/32) .. +8][j = l%32]; accumulator register v of lane l holds
 // D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].
-#include "edgc_internal.h"
+#include "compress_common.h"
 
 #include <algorithm>
 #include <math.h>
 #include <type_traits>
 
 namespace edgc {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int kLdsRow = 144;   // 128 B of operand data + 16 B pad: conflict-free 16-byte reads
-
-__device__ __forceinline__ float bf16_bits_widen(uint32_t h) { return __uint_as_float(h << 16); }
-
-// x -> planes: p[0] = bf16(x); with two planes p[1] = bf16(x - p[0])
-template <int NP>
-__device__ __forceinline__ void to_planes(float x, __bf16 (&p)[NP])
-{
-    p[0] = static_cast<__bf16>(x);
-    if constexpr (NP == 2) p[1] = static_cast<__bf16>(x - static_cast<float>(p[0]));
-}
-
-// Two floats -> packed bf16 pairs, one 32-bit word per plane (v_cvt_pk_bf16_f32, RNE):
-// w[0] = (bf16(x), bf16(y)); with two planes w[1] holds the rounded remainders.
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-template <int NP>
-__device__ __forceinline__ void pack_pair(float x, float y, uint32_t (&w)[NP])
-{
-    const f32x2 v = {x, y};
-    const bf16x2 h = __builtin_convertvector(v, bf16x2);
-    w[0] = __builtin_bit_cast(uint32_t, h);
-    if constexpr (NP == 2) {
-        const f32x2 hf = __builtin_convertvector(h, f32x2);
-        const bf16x2 l = __builtin_convertvector(v - hf, bf16x2);
-        w[1] = __builtin_bit_cast(uint32_t, l);
-    }
-}
-// eight floats -> one MFMA fragment per plane
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-template <int NP>
-__device__ __forceinline__ void pack8(const float (&v)[8], bf16x8 (&f)[NP])
-{
-    uint32_t w[4][NP];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pack_pair<NP>(v[2 * i], v[2 * i + 1], w[i]);
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const u32x4 q = {w[0][p], w[1][p], w[2][p], w[3][p]};
-        f[p] = __builtin_bit_cast(bf16x8, q);
-    }
-}
-template <int NP>
-__device__ __forceinline__ void pack4(const float (&v)[4], bf16x4 (&f)[NP])
-{
-    uint32_t w[2][NP];
-    pack_pair<NP>(v[0], v[1], w[0]);
-    pack_pair<NP>(v[2], v[3], w[1]);
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const u32x2 q = {w[0][p], w[1][p]};
-        f[p] = __builtin_bit_cast(bf16x4, q);
-    }
-}
-
-template <int NP>
-__device__ __forceinline__ f32x16 mma(const bf16x8 (&a)[NP], const bf16x8 (&b)[NP], f32x16 acc)
-{
-    if constexpr (NP == 2) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[0], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[1], acc, 0, 0, 0);
-    }
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], acc, 0, 0, 0);
-}
-
-// Tensor of a grouped launch that owns block `bid` (tensors with no blocks are skipped).
-// Blocks keep the order of the grid: consecutive blocks, which the dispatcher spreads
-// round-robin over the 8 XCDs, walk along the rows of the matrix, so that neighbouring
-// 256-byte pieces of a DRAM page are requested at about the same time (measured 5 to 20 %
-// faster on small matrices than giving each XCD a contiguous range of tiles; the factor
-// slices the blocks share are small enough to sit in every XCD's L2).
-__device__ __forceinline__ uint32_t locate(const Group& g, uint32_t bid)
-{
-    uint32_t t = 0;
-    for (uint32_t i = 1; i < g.count; ++i) t += (bid >= g.t[i].first) ? 1u : 0u;
-    return t;
-}
 
 // ---------------------------------------------------------------------------
 // seeded N(0,1) start of Q
@@ -141,9 +58,6 @@ __global__ void k_init_q(float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32
 // P-pass:  D = G + E_old,  P_partial[s] = D[:, k-range s] * Q[k-range s, :]
 // Block: 4 waves x 32 rows = 128 rows; k-step of 64 columns.
 // ---------------------------------------------------------------------------
-template <int NP> struct GradElem { using type = float; };
-template <> struct GradElem<1> { using type = uint16_t; };
-
 template <int NP, bool VECOK>
 __device__ __forceinline__ void load_grad4(const typename GradElem<NP>::type* __restrict__ G,
                                            uint64_t ldg, uint32_t row, uint32_t col, uint32_t m,
@@ -571,41 +485,115 @@ __device__ __forceinline__ double readlane_f64(double x, int src_lane)
     return __hiloint2double(hi, lo);
 }
 
-// Lanes 0..15 hold row `lane` of a symmetric 16x16 tile in a[0..15] (entries k <= lane are
-// used).  On return a[] holds row `lane` of its Cholesky factor L, x[] holds COLUMN `lane`
-// of X = L^-1 (x[i] = X[i][lane]), with rows and columns of dead pivots zeroed; the return
-// value has bit k set when pivot k was dead.  Must be called by a whole wavefront.
-__device__ __forceinline__ uint32_t chol16_factor_invert(double (&a)[16], double (&x)[16], int lane)
+// 1/d and d^-1/2 for a pivot d of the scaled Gram matrix (kPivotEps < d, d of order 1 at most):
+// the hardware estimate (about 23 bits) and two Newton steps, a short dependent chain where the
+// library routines' range handling would sit on the critical path of the factorisation.
+__device__ __forceinline__ double pivot_rcp(double d)
 {
+    double y = __builtin_amdgcn_rcp(d);
+    y = fma(y, fma(-d, y, 1.0), y);
+    return fma(y, fma(-d, y, 1.0), y);
+}
+__device__ __forceinline__ double pivot_rsq(double d)
+{
+    double y = __builtin_amdgcn_rsq(d);
+    y = fma(0.5 * y, fma(-(d * y), y, 1.0), y);
+    return fma(0.5 * y, fma(-(d * y), y, 1.0), y);
+}
+
+// Cholesky factorisation of a symmetric 16x16 tile and the inverse X = L^-1 of its factor, by one
+// wavefront, in registers.  The tile S and X (which starts as the identity) are held in the
+// accumulator layout of the fp64 MFMA: register v of lane l = (j = l % 16, q = l / 16) holds
+// element [q + 4v][j].  Because S stays symmetric, the same registers are the MFMA operands of
+// a column: lane (i, k) of register kb holds S[i][4 kb + k].  Pivot c (kb = c / 4, k = c % 4)
+// therefore needs no broadcasts: its column, masked to the lanes of group k, is both operands of
+// one rank-1 MFMA update S -= s s^T / d, and one more MFMA applies the elementary row operation
+// to X: X += m X[c][:], m_c = 1/l_c - 1, m_i = -l_i / l_c = -s_i / d below the pivot.  Only the
+// pivot itself is read back (one read-lane) for its reciprocal.
+// A pivot not above kPivotEps is dead: nothing is eliminated with it, and its row and column of
+// X end up zero; the return value has bit c set for a dead pivot c.
+// Must be called by a whole wavefront.
+#ifdef EDGC_CHOL_TIMING
+#define EDGC_CHOL_DBG_ARG , int dbg
+#define EDGC_CHOL_DBG_PASS , dbg
+#else
+#define EDGC_CHOL_DBG_ARG
+#define EDGC_CHOL_DBG_PASS
+#endif
+__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane EDGC_CHOL_DBG_ARG)
+{
+    const int i = lane & 15, q = lane >> 4;
     uint32_t dead = 0;
-    double rd[16];                                   // 1 / L_kk, wave-uniform
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
-        const double d = readlane_f64(a[k], k);
+    for (int v = 0; v < 4; ++v) x[v] = (q + 4 * v == i) ? 1.0 : 0.0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const int kb = c >> 2, k = c & 3;
+        const double d = readlane_f64(s[kb], c + 16 * k);        // S[c][c]
         const bool ok = d > kPivotEps;
-        const double rs = ok ? rsqrt(d) : 0.0;
-        rd[k] = ok ? rs : 1.0;
-        if (!ok) dead |= 1u << k;
-        const double lk = (lane == k) ? (ok ? d * rs : 1.0) : a[k] * rs;
-        a[k] = lk;
-#pragma unroll
-        for (int j = k + 1; j < 16; ++j) a[j] = fma(-lk, readlane_f64(lk, j), a[j]);
+#ifdef EDGC_CHOL_TIMING
+        const double rd = ok ? ((dbg & 2) ? __builtin_amdgcn_rcp(d) : pivot_rcp(d)) : 0.0;
+#else
+        const double rd = ok ? pivot_rcp(d) : 0.0;
+#endif
+        if (!ok) dead |= 1u << c;
+        const bool col = (q == k) && i >= c;                       // lanes of group k: S[c][i] = S[i][c]
+        const double sic = col ? s[kb] : 0.0;
+        const double neg = -(sic * rd);                            // -s_i / d; -1 on the pivot's own lane
+        s = __builtin_amdgcn_mfma_f64_16x16x4f64(neg, sic, s, 0, 0, 0);
+#ifdef EDGC_CHOL_TIMING
+        if (dbg & 1) continue;
+        const double rs = ok ? ((dbg & 4) ? __builtin_amdgcn_rsq(d) : pivot_rsq(d)) : 0.0;
+#else
+        const double rs = ok ? pivot_rsq(d) : 0.0;                 // 1 / l_c, off the chain of S
+#endif
+        const double mop = (col && i == c) ? rs - 1.0 : neg;
+        const double xrow = (q == k) ? x[kb] : 0.0;                // lane (j, k): X[c][j]
+        x = __builtin_amdgcn_mfma_f64_16x16x4f64(mop, xrow, x, 0, 0, 0);
     }
-    // column `lane` of X by forward substitution: X[i][c] = -rd_i * sum_{k=c}^{i-1} L[i][k] X[k][c]
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        double sacc = 0.0;
-#pragma unroll
-        for (int k = 0; k < i; ++k) sacc = fma(readlane_f64(a[k], i), x[k], sacc);   // x[k] = 0 for k < lane
-        x[i] = (lane == i) ? rd[i] : ((lane < i) ? -rd[i] * sacc : 0.0);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-        if (((dead >> i) & 1u) || ((dead >> (lane & 15)) & 1u)) x[i] = 0.0;
     return dead;
 }
 
-__global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t T16)
+// Tile (i, p), i > p, of X = L^-1:  X_ip = -X_ii sum_{k=p}^{i-1} L_ik X_kp, by one wavefront.
+// A holds L in its lower tiles and X_ip transposed in the upper tile (p, i):
+// A[16p + b][16i + a] = X_ip[a][b]; Xd holds the inverses of the diagonal tiles.  The sum S comes
+// out of the MFMA in the accumulator layout, which is the layout of a B operand: register kk is
+// S[4kk + lq][lr], so the product with -X_ii takes it as it stands.
+__device__ __forceinline__ void chol_inverse_tile(double* A, const double* Xd, int LDA, int i, int p, int lr, int lq)
+{
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    for (int k = p; k < i; ++k) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const double av = A[(16 * i + lr) * LDA + 16 * k + 4 * kk + lq];          // L_ik[a][kk']
+            const double bv = (k == p) ? Xd[(p * 16 + 4 * kk + lq) * 17 + lr]           // X_pp[kk'][b]
+                                       : A[(16 * p + lr) * LDA + 16 * k + 4 * kk + lq]; // X_kp[kk'][b]
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+        }
+    }
+    f64x4 xo = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const double av = -Xd[(i * 16 + lr) * 17 + 4 * kk + lq];                       // X_ii[a][k]
+        xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, acc[kk], xo, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) A[(16 * p + lr) * LDA + 16 * i + lq + 4 * v] = xo[v];  // transposed
+}
+
+#ifdef EDGC_CHOL_TIMING
+// developer build only: shader-clock stamps of the phases of block 0
+__device__ unsigned long long g_chol_clk[64];
+#define EDGC_CHOL_TS(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_chol_clk[i] = __builtin_readcyclecounter(); } while (0)
+extern "C" int edgc_debug_chol_clk(unsigned long long* out)
+{
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_chol_clk), sizeof(g_chol_clk)) == hipSuccess ? 0 : -3;
+}
+#else
+#define EDGC_CHOL_TS(i) do { } while (0)
+#endif
+
+__global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t T16 EDGC_CHOL_DBG_ARG)
 {
     const TensorArgs& ta_ = grp.t[blockIdx.x];          // one block per tensor
     const double* __restrict__ tiles = ta_.tiles;
@@ -624,7 +612,24 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
     const uint32_t ntile = T16 * (T16 + 1) / 2, ne = ntile * 256;
     const int lr = lane & 15, lq = lane >> 4;         // MFMA fragment coordinates
 
-    // ---- assemble the Gram matrix (lower triangle) ----
+    EDGC_CHOL_TS(0);
+    // ---- assemble the scaled Gram matrix C = D W D (lower triangle) ----
+    // Every thread's entries are requested at once (registers), the diagonal first for the scales.
+    constexpr int kMaxPerThread = (36 * 256 + kCholThreads - 1) / kCholThreads;
+    double wv[kMaxPerThread];
+    if (nb == 1) {
+#pragma unroll
+        for (int u = 0; u < kMaxPerThread; ++u) {
+            const uint32_t e = tid + u * kCholThreads;
+            wv[u] = tiles[e < ne ? e : 0];
+        }
+        for (int j = tid; j < RPAD; j += kCholThreads) {
+            // W[j][j] sits in diagonal tile (t, t), t = j / 16, the tile of index t T - t (t - 1) / 2
+            const int t = j >> 4, ti = t * T - t * (t - 1) / 2;
+            const double w = tiles[ti * 256 + (j & 15) * 17];
+            dsc[j] = (w > 0.0) ? rsqrt(w) : 0.0;
+        }
+    }
     for (int e = tid; e < RPAD * LDA; e += kCholThreads) A[e] = 0.0;
     if (nb > 1) {                                     // ne == 256: four interleaved groups per entry
         const uint32_t e = tid & 255, grp = tid >> 8;
@@ -642,44 +647,48 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
         __syncthreads();
         if (tid < 256) red[tid] = ((red[tid] + red[tid + 256]) + red[tid + 512]) + red[tid + 768];
         __syncthreads();
+        if (tid < 16) {
+            const double w = red[tid * 17];
+            dsc[tid] = (w > 0.0) ? rsqrt(w) : 0.0;
+        }
+        wv[0] = red[tid & 255];
     }
     __syncthreads();
-    for (uint32_t e = tid; e < ne; e += kCholThreads) {
-        const double w = (nb > 1) ? red[e] : tiles[e];
-        int ta, tb;
-        tri_tile(static_cast<int>(e >> 8), T, ta, tb);
-        const int a = 16 * ta + ((e >> 4) & 15), b = 16 * tb + (e & 15);
-        if (a <= b) A[b * LDA + a] = w;
-    }
-    __syncthreads();
-    for (int j = tid; j < RPAD; j += kCholThreads) {
-        const double w = A[j * LDA + j];
-        dsc[j] = (w > 0.0) ? rsqrt(w) : 0.0;
-    }
-    __syncthreads();
-    for (int e = tid; e < RPAD * RPAD; e += kCholThreads) {
-        const int a = e / RPAD, b = e % RPAD;
-        if (b <= a) A[a * LDA + b] *= dsc[a] * dsc[b];
+#pragma unroll
+    for (int u = 0; u < kMaxPerThread; ++u) {
+        const uint32_t e = tid + u * kCholThreads;
+        if (e < ne && (nb == 1 || u == 0) && (nb == 1 || tid < 256)) {
+            int ta, tb;
+            tri_tile(static_cast<int>(e >> 8), T, ta, tb);
+            const int a = 16 * ta + ((e >> 4) & 15), b = 16 * tb + (e & 15);
+            if (a <= b) A[b * LDA + a] = wv[u] * (dsc[a] * dsc[b]);
+        }
     }
     __syncthreads();
 
+    EDGC_CHOL_TS(1);
     // ---- blocked right-looking Cholesky ----
     for (int p = 0; p < T; ++p) {
         const int j0 = 16 * p;
+        EDGC_CHOL_TS(2 + 4 * p);
         if (wave == 0) {
-            double a[16], x[16];
+            // the diagonal tile as a full symmetric tile (its lower triangle is what A holds)
+            f64x4 st, xt;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) { a[k] = (lane < 16) ? A[(j0 + lane) * LDA + j0 + k] : 0.0; x[k] = 0.0; }
-            const uint32_t dead = chol16_factor_invert(a, x, lane);
-            if (lane < 16) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    if (k <= lane) A[(j0 + lane) * LDA + j0 + k] = a[k];
-                    Xd[(p * 16 + k) * 17 + lane] = x[k];          // X[k][lane]
-                }
+            for (int v = 0; v < 4; ++v) {
+                const int a = lq + 4 * v, b = lr;                 // element [a][b]
+                st[v] = A[(j0 + max(a, b)) * LDA + j0 + min(a, b)];
             }
+            const uint32_t dead = chol16_factor_invert(st, xt, lane EDGC_CHOL_DBG_PASS);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Xd[(p * 16 + lq + 4 * v) * 17 + lr] = xt[v];   // X[row][col]
             if (lane == 0) deadmask[p] = dead;
+        } else if (p >= 2) {
+            // Beside the diagonal tile's serial factorisation the other wavefronts form row p-1 of
+            // X = L^-1: everything it needs (row p-1 of L, X_(p-1)(p-1), the rows of X above) is final.
+            for (int j = wave - 1; j < p - 1; j += NW - 1) chol_inverse_tile(A, Xd, LDA, p - 1, j, lr, lq);
         }
+        EDGC_CHOL_TS(3 + 4 * p);
         __syncthreads();
         // panel solve: L_ip = C_ip X_pp^T for tiles i > p
         for (int i = p + 1 + wave; i < T; i += NW) {
@@ -694,6 +703,7 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + j0 + lr] = acc[v];
         }
         __syncthreads();
+        EDGC_CHOL_TS(4 + 4 * p);
         // trailing update: C_ic -= L_ip L_cp^T for p < c <= i
         const int rem = T - p - 1, npair = rem * (rem + 1) / 2;
         for (int idx = wave; idx < npair; idx += NW) {
@@ -715,40 +725,17 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
         __syncthreads();
     }
 
-    // ---- blocked inverse: X_ip = -X_ii * sum_{k=p}^{i-1} L_ik X_kp, by tile distance ----
-    // X_ip (i > p) is kept transposed in the upper tile (p, i): A[16p + b][16i + a] = X_ip[a][b]
-    for (int dist = 1; dist < T; ++dist) {
-        for (int p = wave; p + dist < T; p += NW) {
-            const int i = p + dist;
-            f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-            for (int k = p; k < i; ++k) {
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const double av = A[(16 * i + lr) * LDA + 16 * k + 4 * kk + lq];          // L_ik[a][kk']
-                    const double bv = (k == p) ? Xd[(p * 16 + 4 * kk + lq) * 17 + lr]           // X_pp[kk'][b]
-                                               : A[(16 * p + lr) * LDA + 16 * k + 4 * kk + lq]; // X_kp[kk'][b]
-                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-                }
-            }
-            // park S = sum in the target tile (natural orientation), then X_ip = -X_ii S
-#pragma unroll
-            for (int v = 0; v < 4; ++v) A[(16 * p + lq + 4 * v) * LDA + 16 * i + lr] = acc[v];
-            f64x4 xo = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const double av = -Xd[(i * 16 + lr) * 17 + 4 * kk + lq];                       // X_ii[a][k]
-                const double bv = A[(16 * p + 4 * kk + lq) * LDA + 16 * i + lr];               // S[k][b]
-                xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, xo, 0, 0, 0);
-            }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) A[(16 * p + lr) * LDA + 16 * i + lq + 4 * v] = xo[v];  // transposed
-        }
-        __syncthreads();
-    }
+    EDGC_CHOL_TS(40);
+    // the last row of the inverse, with every wavefront
+    for (int j = wave; j + 1 < T; j += NW) chol_inverse_tile(A, Xd, LDA, T - 1, j, lr, lq);
+    __syncthreads();
 
+    EDGC_CHOL_TS(41);
     // ---- R^-1[k][c] = d_k X[c][k] for k <= c, zero elsewhere and for removed columns ----
-    for (uint32_t e = tid; e < r * r; e += kCholThreads) {
-        const uint32_t k = e / r, c = e % r;
+    const int sh = 31 - __clz(RPAD);                  // RPAD is a power of two
+    for (uint32_t e = tid; e < static_cast<uint32_t>(RPAD * RPAD); e += kCholThreads) {
+        const uint32_t k = e >> sh, c = e & (RPAD - 1);
+        if (k >= r || c >= r) continue;
         double v = 0.0;
         const bool dk = (deadmask[k >> 4] >> (k & 15)) & 1u, dc = (deadmask[c >> 4] >> (c & 15)) & 1u;
         if (k <= c && !dk && !dc) {
@@ -756,8 +743,9 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
                                                      : A[k * LDA + c];
             v = dsc[k] * xv;
         }
-        rinv[e] = v;
+        rinv[static_cast<size_t>(k) * r + c] = v;
     }
+    EDGC_CHOL_TS(42);
 }
 
 // ---------------------------------------------------------------------------
@@ -882,7 +870,6 @@ __global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
 // operand comes from the transposed bf16 copy through a double-buffered LDS
 // tile shared by the four waves (one barrier per stage).
 // ---------------------------------------------------------------------------
-typedef float vf2 __attribute__((ext_vector_type(2)));
 template <int NT, bool FULL, bool STREAM>
 __device__ __forceinline__ void load_d_rows(const float* __restrict__ D, uint32_t n, uint32_t m,
                                             uint32_t row_base, uint32_t col, float (&v)[8][NT])
@@ -2055,6 +2042,8 @@ int prepare_compress_kernels(edgc_ctx* ctx)
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 4, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<2, 2, 2>()));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_p_deferred<2, 2>()));
+    EDGC_HIP_TRY(ctx, prepare_pass_p_full());
+    EDGC_HIP_TRY(ctx, prepare_decompress_full());
     return EDGC_OK;
 }
 
@@ -2118,9 +2107,12 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     // the kernels of the deferred form: above rank 64 only for that form; up to rank 64 also for bf16
     // gradients with the residual stored (its sweep is the faster one there: 295 against 390 us on the
     // hidden-5120 block)
+    // groups of whole tiles with a residual to subtract: the kernel without edge paths
+    constexpr edgc_dtype DT = (NP == 1) ? EDGC_BF16 : EDGC_F32;
+    const bool use_full = with_grad && ctx->tune_full != 0 && pass_p_full_applies(g, DT, RT);
     const bool use_narrow = with_grad && g.defer && RT == 4;
     const bool use_wide = with_grad && RT <= 2 && (g.defer || NP == 1);
-    const uint32_t per_cu = use_narrow ? 2u : 4u;
+    const uint32_t per_cu = (use_narrow && !use_full) ? 2u : 4u;
     const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : per_cu);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
@@ -2142,7 +2134,7 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         t.first = blocks;
         blocks += RB * S;
         // 16-byte accesses; the kernel of the deferred form reads and writes two columns per lane
-        const uint32_t w = use_wide ? 2u : 4u;
+        const uint32_t w = (use_wide || use_full) ? 2u : 4u;
         if (w == 2u) vec = vec && t.ldg < (1ull << 28) && t.n < (1u << 28);   // its per-lane offsets are 32-bit
         vec = vec && (t.n % w == 0) && (t.ldg % w == 0) &&
               (reinterpret_cast<uintptr_t>(t.G) % (w * sizeof(GT)) == 0) &&
@@ -2151,6 +2143,12 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         const double mn = static_cast<double>(t.m) * t.n;
         bytes += mn * ((with_grad ? sizeof(GT) : 0) + (t.e_zero ? 0 : 4) + 4);
         flops += 2.0 * mn * g.r;
+    }
+    if (use_full) {
+        const bool qlate = ctx->tune_full == 2;
+        ProfScope prof_scope_(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops);
+        EDGC_HIP_TRY(ctx, launch_pass_p_full(g, DT, RT, blocks, qlate, st));
+        return EDGC_OK;
     }
     if (use_narrow || use_wide) {
         // D_prev is read where the other form reads E_old: the same bytes; two products per element
@@ -2249,8 +2247,14 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
     }
     const size_t rpad = 16 * t16;
     const size_t chol_lds = (rpad * (rpad + 1) + t16 * 16 * 17 + rpad + kCholThreads) * sizeof(double) + t16 * sizeof(uint32_t);
+#ifdef EDGC_CHOL_TIMING
+    const int chol_dbg = getenv("EDGC_CHOL_DBG") ? atoi(getenv("EDGC_CHOL_DBG")) : 0;
+#define EDGC_CHOL_DBG_VAL , chol_dbg
+#else
+#define EDGC_CHOL_DBG_VAL
+#endif
     EDGC_LAUNCH(ctx, st, KID_CHOL, bytes, g.count * 2.0 * r * r * r / 3.0,
-                k_chol<<<g.count, kCholThreads, chol_lds, st>>>(g, t16));
+                k_chol<<<g.count, kCholThreads, chol_lds, st>>>(g, t16 EDGC_CHOL_DBG_VAL));
     EDGC_HIP_TRY(ctx, hipGetLastError());
 
     // P^ = P R^-1 and its transposed bf16 copy
@@ -2401,7 +2405,15 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
     constexpr uint32_t RP = RT * 32;
     constexpr size_t lds = static_cast<size_t>(64) * (NP * RP * 2 + 16);
     constexpr uint32_t esz = (NP == 1) ? 2 : 4;          // one plane <=> bf16 gradient and output
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_d ? ctx->tune_d : 4u);
+    // write-only reconstruction of whole-tile groups: the kernel without edge paths, 256 rows per block
+    constexpr edgc_dtype DT = (NP == 1) ? EDGC_BF16 : EDGC_F32;
+    // (up to rank 64 the general kernel already writes at the rate the store pattern allows)
+    const uint32_t waves = ctx->tune_dfull == 4 ? 4u : 8u;
+    const bool use_full = g.defer && (ctx->tune_dfull > 0 || (ctx->tune_dfull < 0 && RT == 4)) &&
+                          decompress_full_applies(g, DT, waves);
+    const uint32_t rows_per_block = use_full ? 32u * waves : 128u;
+    const uint32_t per_cu = ctx->tune_d ? ctx->tune_d : (use_full && waves == 8 ? 2u : 4u);
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * per_cu;
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
     bool vec = true;
@@ -2409,7 +2421,7 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
     double bytes = 0.0, flops = 0.0;
     for (uint32_t i = 0; i < g.count; ++i) {
         TensorArgs& t = g.t[i];
-        const uint32_t RB = cdiv(t.m, 128), stages = cdiv(t.n, 64);
+        const uint32_t RB = cdiv(t.m, rows_per_block), stages = cdiv(t.n, 64);
         uint32_t JS = std::max(1u, std::min(stages, tgt[i] / RB));
         const uint32_t sps = cdiv(stages, JS);
         JS = cdiv(stages, sps);
@@ -2422,6 +2434,11 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
         // algorithmic traffic: write M^ (if asked for); read D and write E_new unless deferred
         bytes += static_cast<double>(t.m) * t.n * ((g.defer ? 0 : 8) + (t.out ? esz : 0));
         flops += 2.0 * t.m * t.n * g.r;
+    }
+    if (use_full) {
+        ProfScope prof_scope_(ctx, st, KID_DECOMPRESS, bytes, flops);
+        EDGC_HIP_TRY(ctx, launch_decompress_full(g, DT, RT, blocks, waves, st));
+        return EDGC_OK;
     }
     if (g.defer) {
         if (vec)

@@ -75,6 +75,8 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     if (const char* e = getenv("EDGC_TUNE_Q")) ctx->tune_q = std::max(1, atoi(e));
     if (const char* e = getenv("EDGC_TUNE_D")) ctx->tune_d = std::max(1, atoi(e));
     if (const char* e = getenv("EDGC_TUNE_STREAM")) ctx->tune_stream = atoi(e);
+    if (const char* e = getenv("EDGC_TUNE_FULL")) ctx->tune_full = atoi(e);
+    if (const char* e = getenv("EDGC_TUNE_DFULL")) ctx->tune_dfull = atoi(e);
 
     Scratch& s = ctx->s;
     const uint64_t rp = (max_rank <= 32) ? 32 : (max_rank <= 64 ? 64 : 128);

@@ -127,6 +127,11 @@ struct edgc_ctx {
     // decompress); 0 = the built-in choice
     uint32_t tune_p = 0, tune_q = 0, tune_d = 0;
     int tune_stream = -1;   // -1: by size; 0 / 1: force cached / non-temporal reads of D in the Q-pass
+    int tune_dfull = -1;    // write-only decompress of whole-tile groups: -1 built-in choice (above rank
+                            // 64 the whole-tile kernel, 8 waves per block); 0 the general kernel; 4 / 8
+                            // the whole-tile kernel with that many waves per block at every rank
+    int tune_full = -1;     // P-pass of whole-tile groups: -1 built-in choice; 0 the general kernels;
+                            // 1 / 2 the whole-tile kernel with the Q rows requested early / late
     edgc::Scratch s;
     std::vector<edgc::BatchSlot> batch;
     edgc::Profiler prof;
@@ -228,5 +233,16 @@ int launch_copy_rows(edgc_ctx* ctx, const void* src, uint64_t ld_src, void* dst,
 int prepare_compress_kernels(edgc_ctx* ctx);
 int prepare_entropy_kernels(edgc_ctx* ctx);
 size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_rank, int num_cu);
+
+// the P-pass of groups made of whole tiles only (pass_p_full.hip)
+bool pass_p_full_applies(const Group& g, edgc_dtype dt, int rank_tiles);
+hipError_t launch_pass_p_full(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t blocks, bool qlate,
+                              hipStream_t st);
+hipError_t prepare_pass_p_full();
+// the write-only reconstruction of groups made of whole tiles only (decompress_full.hip)
+bool decompress_full_applies(const Group& g, edgc_dtype dt, uint32_t waves);
+hipError_t launch_decompress_full(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t blocks, uint32_t waves,
+                                  hipStream_t st);
+hipError_t prepare_decompress_full();
 
 }  // namespace edgc

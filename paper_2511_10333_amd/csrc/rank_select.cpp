@@ -112,12 +112,17 @@ extern "C" int edgc_select_rank(edgc_rank_state* st, const double* H_window, uin
 {
     if (!st || !H_window || !prm || !out || k == 0) return EDGC_EINVAL;
     const uint32_t mm = std::min(prm->m, prm->n);
-    if (mm == 0 || prm->r_max == 0 || prm->r_max > mm || prm->r_min > prm->r_max) return EDGC_EINVAL;
+    // rank 0 is the warm-up answer: 1 <= r_min <= r_max <= min(m, n)
+    if (mm == 0 || prm->r_min == 0 || prm->r_max > mm || prm->r_min > prm->r_max) return EDGC_EINVAL;
     const uint32_t r_ref = prm->r_ref ? prm->r_ref : prm->r_max;
     if (r_ref > mm) return EDGC_EINVAL;
     if (prm->n_allowed && !prm->allowed) return EDGC_EINVAL;
     for (uint32_t i = 1; i < prm->n_allowed; ++i)
         if (prm->allowed[i] <= prm->allowed[i - 1]) return EDGC_EINVAL;
+    // the allowed ranks inside the bounds, [lo_ok, hi_ok): the only ones ever emitted
+    const uint32_t* const lo_ok = std::lower_bound(prm->allowed, prm->allowed + prm->n_allowed, prm->r_min);
+    const uint32_t* const hi_ok = std::upper_bound(prm->allowed, prm->allowed + prm->n_allowed, prm->r_max);
+    if (prm->n_allowed && lo_ok >= hi_ok) return EDGC_EINVAL;
 
     double sum = 0.0;
     for (uint32_t i = 0; i < k; ++i) {
@@ -166,9 +171,10 @@ extern "C" int edgc_select_rank(edgc_rank_state* st, const double* H_window, uin
 
     uint32_t rank = static_cast<uint32_t>(r);
     if (prm->n_allowed) {
-        const uint32_t* e = prm->allowed + prm->n_allowed;
-        const uint32_t* p = std::lower_bound(prm->allowed, e, rank);
-        rank = (p == e) ? e[-1] : *p;
+        // smallest allowed rank >= the state that stays within r_max (Sec. IV-D-1: from r_max on
+        // compression no longer pays), else the largest allowed rank inside the bounds
+        const uint32_t* p = std::lower_bound(lo_ok, hi_ok, rank);
+        rank = (p == hi_ok) ? hi_ok[-1] : *p;
     }
     out->rank = rank;
     out->T_com = prm->eta * static_cast<double>(rank);       // T_com(r) = eta r (Sec. IV-D-1)

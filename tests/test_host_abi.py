@@ -72,6 +72,26 @@ def test_select_rank_matches_oracle_on_random_entropy_walks(shape, seed):
         assert d_o.T_com == d_p.T_com
 
 
+@pytest.mark.parametrize("bounds", [(6, 48), (5, 31), (9, 100), (16, 16)])
+def test_select_rank_snaps_inside_the_bounds_like_the_oracle(bounds):
+    # allowed ranks outside [r_min, r_max] are never emitted (r_max of Sec. IV-D-1 is a hard bound)
+    rng = np.random.default_rng(7)
+    r_min, r_max = bounds
+    prm = dict(m=512, n=768, r_min=r_min, r_max=r_max, step_limit=8, allowed=[4, 8, 16, 32, 64, 128], eta=0.5,
+               total_iters=0, min_warmup_frac=0.0, r_ref=0)
+    H, windows = -6.0, []
+    for k in range(40):
+        H += float(rng.normal(-0.08 if k < 20 else 0.12, 0.1))
+        windows.append(([H], 10))
+    seen = set()
+    for d_o, d_p in _both(prm, windows):
+        assert d_o.rank == d_p.rank and d_o.r_unclamped == d_p.r_unclamped and d_o.T_com == d_p.T_com
+        if d_p.rank:
+            assert r_min <= d_p.rank <= r_max
+            seen.add(d_p.rank)
+    assert seen
+
+
 def test_select_rank_hand_table_and_warmup():
     prm = dict(m=512, n=512, r_min=16, r_max=64, step_limit=8, eta=0.5, total_iters=100,
                min_warmup_frac=0.10)
@@ -86,7 +106,8 @@ def test_select_rank_hand_table_and_warmup():
 
 def test_select_rank_rejects_bad_input():
     st = edgc.RankState()
-    for kw in [dict(r_max=0), dict(r_max=1000), dict(r_min=65), dict(allowed=[8, 4])]:
+    for kw in [dict(r_max=0), dict(r_max=1000), dict(r_min=65), dict(allowed=[8, 4]), dict(r_min=0),
+               dict(r_min=33, r_max=63, allowed=[4, 8, 16, 32, 64])]:
         a = dict(m=512, n=512, r_min=4, r_max=64); a.update(kw)
         with pytest.raises(edgc.EdgcError) as e:
             edgc.select_rank(st, [0.0], 1, edgc.RankParams(**a))
