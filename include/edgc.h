@@ -447,6 +447,24 @@ int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* grads, const u
                                 const float* range_lo_hi_or_null, edgc_entropy_result* out,
                                 uint64_t* counts_out_or_null, void* hip_stream);
 
+/* edgc_entropy_estimate for callers that cannot allocate device memory and cannot have a
+ * library do it for them: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, result and errors as edgc_entropy_estimate, same kernels;
+ * what differs is where the estimate's scratch lives (per-block ranges, last-block tickets,
+ * the range parameters, the 64-bit histogram when counts_out_or_null is NULL, the result
+ * before it is copied to non-pinned `out`): not in memory the context allocated but in a
+ * file-scope device array of the library, 545 KiB, which every GPU the library runs on holds
+ * from the load of the library's code to the end of the process.  Limit: bins <= 65536
+ * (EDGC_EINVAL beyond, whatever max_bins the context was created with).  The call itself
+ * allocates and frees nothing (no hipMalloc, no hipFree); the array's address on the context's
+ * device is looked up once, in edgc_create.  All calls on one GPU, from whatever context or
+ * stream, share that GPU's array: calls that overlap on one GPU race; calls in sequence are
+ * safe (each call resets what must start at zero). */
+int edgc_entropy_estimate_noalloc(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint64_t n_elems,
+                                  uint64_t stride, uint32_t chunk, uint64_t seed, uint64_t step,
+                                  uint32_t bins, const float* range_lo_hi_or_null,
+                                  edgc_entropy_result* out, uint64_t* counts_out_or_null,
+                                  void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -83,6 +83,8 @@ def load_library() -> C.CDLL:
     L.edgc_profile_end.argtypes = [vp, C.POINTER(_KernelStat), u32, C.POINTER(u32)]
     L.edgc_entropy_estimate.restype = i32
     L.edgc_entropy_estimate.argtypes = [vp, vp, i32, u64, u64, u32, u64, u64, u32, vp, vp, vp, vp]
+    L.edgc_entropy_estimate_noalloc.restype = i32
+    L.edgc_entropy_estimate_noalloc.argtypes = [vp, vp, i32, u64, u64, u32, u64, u64, u32, vp, vp, vp, vp]
     L.edgc_entropy_estimate_batch.restype = i32
     L.edgc_entropy_estimate_batch.argtypes = [vp, C.POINTER(C.c_void_p), C.POINTER(u64), u32, i32, u64, u32,
                                               u64, u64, u32, vp, vp, vp, vp]
@@ -371,6 +373,19 @@ class Context:
                 for i in range(min(cap, n.value))}
 
     # -- entropy -----------------------------------------------------------
+    def entropy_estimate_noalloc(self, grad, stride: int, chunk: int, seed: int, step: int, bins: int,
+                                 out_pinned, value_range=None, counts_out=None, stream=None) -> None:
+        """edgc_entropy_estimate_noalloc: the estimate on the library's file-scope scratch array
+        (bins <= 65536); ``out_pinned`` as for :meth:`entropy_estimate_async`."""
+        rng = None
+        if value_range is not None:
+            rng = (C.c_float * 2)(float(value_range[0]), float(value_range[1]))
+        rc = self._L.edgc_entropy_estimate_noalloc(
+            self._h, grad.data_ptr(), _dtype_code(grad), grad.numel(), stride, chunk, seed, step, bins,
+            C.cast(rng, C.c_void_p) if rng is not None else None, out_pinned.data_ptr(),
+            counts_out.data_ptr() if counts_out is not None else None, _stream_handle(stream))
+        self._check(rc, "edgc_entropy_estimate_noalloc")
+
     def entropy_estimate_async(self, grad, stride: int, chunk: int, seed: int, step: int, bins: int,
                                out_pinned, value_range=None, counts_out=None, stream=None) -> None:
         """edgc_entropy_estimate, or edgc_entropy_estimate_batch when ``grad`` is a list of tensors

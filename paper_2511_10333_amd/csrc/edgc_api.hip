@@ -99,6 +99,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     ok = ok && hipMemset(s.done_counter, 0, 4 * sizeof(unsigned int)) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     ok = ok && prepare_entropy_kernels(ctx) == EDGC_OK && prepare_compress_kernels(ctx) == EDGC_OK;
+    ok = ok && resolve_static_scratch(ctx) == EDGC_OK;
     if (!ok) {
         (void)hipGetLastError();
         free_scratch(s);
@@ -213,8 +214,8 @@ extern "C" int edgc_entropy_estimate(edgc_ctx* ctx, const void* grad, edgc_dtype
                                        out, counts_out, hip_stream);
 }
 
-extern "C" int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* grads, const uint64_t* n_elems,
-                                           uint32_t count, edgc_dtype dtype, uint64_t stride, uint32_t chunk,
+static int entropy_estimate_impl(edgc_ctx* ctx, bool static_scratch, const void* const* grads, const uint64_t* n_elems,
+                                 uint32_t count, edgc_dtype dtype, uint64_t stride, uint32_t chunk,
                                            uint64_t seed, uint64_t step, uint32_t bins, const float* range,
                                            edgc_entropy_result* out, uint64_t* counts_out, void* hip_stream)
 {
@@ -224,7 +225,12 @@ extern "C" int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* gra
         return fail(ctx, EDGC_EINVAL, "an entropy estimate takes 1 to 32 buffers");
     if (dtype != EDGC_F32 && dtype != EDGC_BF16) return fail(ctx, EDGC_EINVAL, "unknown dtype");
     if (int rc = check_sampler_args(ctx, stride, chunk)) return rc;
-    if (bins == 0 || bins > ctx->max_bins) return fail(ctx, EDGC_EINVAL, "bins == 0 or bins > max_bins");
+    if (static_scratch) {
+        if (bins == 0 || bins > kStaticMaxBins)
+            return fail(ctx, EDGC_EINVAL, "edgc_entropy_estimate_noalloc takes 1 to 65536 bins");
+    } else if (bins == 0 || bins > ctx->max_bins) {
+        return fail(ctx, EDGC_EINVAL, "bins == 0 or bins > max_bins");
+    }
     if (range && !(range[0] <= range[1])) return fail(ctx, EDGC_EINVAL, "range needs lo <= hi");
     if (counts_out && !aligned_to(counts_out, 8)) return fail(ctx, EDGC_EINVAL, "counts misaligned");
     for (uint32_t i = 0; i < count; ++i) {
@@ -249,8 +255,31 @@ extern "C" int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* gra
     }
     if (g.n_sampled == 0) return fail(ctx, EDGC_ENONFINITE, "the sampling predicate selects no element");
     EDGC_HIP_TRY(ctx, hipSetDevice(ctx->device));
+    if (static_scratch)
+        return launch_entropy_static(ctx, g, dtype, bins, range, out, counts_out, static_cast<hipStream_t>(hip_stream));
     return launch_entropy(ctx, g, dtype, bins, range, out, counts_out, static_cast<hipStream_t>(hip_stream));
 }
+
+extern "C" int edgc_entropy_estimate_batch(edgc_ctx* ctx, const void* const* grads, const uint64_t* n_elems,
+                                           uint32_t count, edgc_dtype dtype, uint64_t stride, uint32_t chunk,
+                                           uint64_t seed, uint64_t step, uint32_t bins, const float* range,
+                                           edgc_entropy_result* out, uint64_t* counts_out, void* hip_stream)
+{
+    return entropy_estimate_impl(ctx, false, grads, n_elems, count, dtype, stride, chunk, seed, step, bins, range,
+                                 out, counts_out, hip_stream);
+}
+
+extern "C" int edgc_entropy_estimate_noalloc(edgc_ctx* ctx, const void* grad, edgc_dtype dtype,
+                                             uint64_t n_elems, uint64_t stride, uint32_t chunk, uint64_t seed,
+                                             uint64_t step, uint32_t bins, const float* range,
+                                             edgc_entropy_result* out, uint64_t* counts_out, void* hip_stream)
+{
+    if (!ctx) return EDGC_EINVAL;
+    if (!grad || !out) return fail(ctx, EDGC_EINVAL, "null grad or out");
+    return entropy_estimate_impl(ctx, true, &grad, &n_elems, 1, dtype, stride, chunk, seed, step, bins, range, out,
+                                 counts_out, hip_stream);
+}
+
 
 extern "C" int edgc_sample_indices(edgc_ctx* ctx, uint64_t n_elems, uint64_t stride, uint32_t chunk,
                                    uint64_t seed, uint64_t step, uint64_t* idx_out, uint64_t cap,

@@ -219,6 +219,11 @@ int launch_entropy(edgc_ctx* ctx, const EntGroup& grp, edgc_dtype dt, uint32_t b
                    const float* range, edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st);
 int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uint64_t cap,
                           hipStream_t st);
+// the estimate on the file-scope scratch array (no allocation anywhere): at most kStaticMaxBins bins
+constexpr uint32_t kStaticMaxBins = 65536;
+int resolve_static_scratch(edgc_ctx* ctx);      // once per device, from edgc_create
+int launch_entropy_static(edgc_ctx* ctx, const EntGroup& grp, edgc_dtype dt, uint32_t bins, const float* range,
+                          edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st);
 
 // launchers (compress.hip)
 int launch_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t c0, uint32_t c1,

@@ -566,11 +566,20 @@ static uint32_t grid_for(uint64_t n_items, int block, int per_thread, int max_bl
     return static_cast<uint32_t>(want);
 }
 
+// The device memory an estimate works in beyond its inputs and outputs: the context's own
+// allocations, or the file-scope array of the entry point that allocates nothing.
+struct EntScratch {
+    float*              mm_part;       // [2 * kMaxReduceBlocks] per-block (lo, hi)
+    unsigned int*       done_counter;  // [2] last-block tickets, zero between calls
+    unsigned long long* counts;        // histogram when the caller gives none
+    void*               range;         // RangeParams
+    void*               result_dev;    // edgc_entropy_result
+};
+
 template <typename T, int VEC>
-static int run_entropy(edgc_ctx* ctx, const EntGroup& g, uint32_t bins, const float* range,
+static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, uint32_t bins, const float* range,
                        uint64_t* counts_out, edgc_entropy_result* res, hipStream_t st)
 {
-    Scratch& s = ctx->s;
     auto* counts = counts_out ? reinterpret_cast<unsigned long long*>(counts_out) : s.counts;
     auto* rp = static_cast<RangeParams*>(s.range);
     const float fbins = static_cast<float>(bins);
@@ -656,15 +665,15 @@ int prepare_entropy_kernels(edgc_ctx* ctx)
     return EDGC_OK;
 }
 
-int launch_entropy(edgc_ctx* ctx, const EntGroup& g, edgc_dtype dt, uint32_t bins,
-                   const float* range, edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st)
+static int launch_entropy_on(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, edgc_dtype dt, uint32_t bins,
+                             const float* range, edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st)
 {
     // the kernels are compiled for one vector width: every buffer of the group was given the same
     bool vec = true;
     for (uint32_t i = 0; i < g.count; ++i) vec = vec && g.geom[i].vec > 1;
     // Pinned (device-accessible) host memory takes the result straight from the kernel; any
     // other host memory gets it through a copy on the stream.
-    auto* res = static_cast<edgc_entropy_result*>(ctx->s.result_dev);
+    auto* res = static_cast<edgc_entropy_result*>(s.result_dev);
     bool direct = false;
     hipPointerAttribute_t attr;
     if (reinterpret_cast<uintptr_t>(out) % alignof(edgc_entropy_result) == 0 &&
@@ -677,15 +686,68 @@ int launch_entropy(edgc_ctx* ctx, const EntGroup& g, edgc_dtype dt, uint32_t bin
     }
     int rc;
     if (dt == EDGC_F32)
-        rc = vec ? run_entropy<float, 4>(ctx, g, bins, range, counts_out, res, st)
-                 : run_entropy<float, 1>(ctx, g, bins, range, counts_out, res, st);
+        rc = vec ? run_entropy<float, 4>(ctx, s, g, bins, range, counts_out, res, st)
+                 : run_entropy<float, 1>(ctx, s, g, bins, range, counts_out, res, st);
     else
-        rc = vec ? run_entropy<uint16_t, 8>(ctx, g, bins, range, counts_out, res, st)
-                 : run_entropy<uint16_t, 1>(ctx, g, bins, range, counts_out, res, st);
+        rc = vec ? run_entropy<uint16_t, 8>(ctx, s, g, bins, range, counts_out, res, st)
+                 : run_entropy<uint16_t, 1>(ctx, s, g, bins, range, counts_out, res, st);
     if (rc != EDGC_OK || direct) return rc;
-    EDGC_HIP_TRY(ctx, hipMemcpyAsync(out, ctx->s.result_dev, sizeof(edgc_entropy_result),
+    EDGC_HIP_TRY(ctx, hipMemcpyAsync(out, s.result_dev, sizeof(edgc_entropy_result),
                                      hipMemcpyDeviceToHost, st));
     return EDGC_OK;
+}
+
+int launch_entropy(edgc_ctx* ctx, const EntGroup& g, edgc_dtype dt, uint32_t bins,
+                   const float* range, edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st)
+{
+    const Scratch& c = ctx->s;
+    const EntScratch s{c.mm_part, c.done_counter, c.counts, c.range, c.result_dev};
+    return launch_entropy_on(ctx, s, g, dt, bins, range, out, counts_out, st);
+}
+
+// ---------------------------------------------------------------------------
+// The estimate for callers that cannot allocate: its scratch is a file-scope device array, so
+// nothing has to be allocated for it, by the library or by the caller.  Each GPU holds its own
+// copy of the array at its own address; the address is looked up once per device, at the first
+// edgc_create on that device (with that device current), and host code only ever uses that
+// pointer, never the array's name.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticOffDone   = sizeof(float) * 2 * kMaxReduceBlocks;             // 32 KiB of (lo, hi) pairs
+constexpr size_t kStaticOffRange  = kStaticOffDone + 256;
+constexpr size_t kStaticOffResult = kStaticOffRange + 256;
+constexpr size_t kStaticOffCounts = kStaticOffResult + 256;
+constexpr size_t kStaticBytes     = kStaticOffCounts + sizeof(unsigned long long) * kStaticMaxBins;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+static unsigned char* g_static_scratch[kMaxDevices] = {};     // per device, set once
+
+int resolve_static_scratch(edgc_ctx* ctx)
+{
+    const int dev = ctx->device;
+    if (dev < 0 || dev >= kMaxDevices) return fail(ctx, EDGC_EINVAL, "device index beyond the static scratch table");
+    if (g_static_scratch[dev]) return EDGC_OK;
+    unsigned char* ptr = nullptr;
+    EDGC_HIP_TRY(ctx, hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(ctx, EDGC_EHIP, "hipGetSymbolAddress returned a null address");
+    // the tickets must start at zero; the array is zero-initialised when the code object is loaded
+    // and every estimate leaves them at zero, but a process may have been interrupted mid-call
+    EDGC_HIP_TRY(ctx, hipMemset(ptr + kStaticOffDone, 0, 256));
+    EDGC_HIP_TRY(ctx, hipDeviceSynchronize());
+    g_static_scratch[dev] = ptr;
+    return EDGC_OK;
+}
+
+int launch_entropy_static(edgc_ctx* ctx, const EntGroup& g, edgc_dtype dt, uint32_t bins, const float* range,
+                          edgc_entropy_result* out, uint64_t* counts_out, hipStream_t st)
+{
+    unsigned char* base = (ctx->device >= 0 && ctx->device < kMaxDevices) ? g_static_scratch[ctx->device] : nullptr;
+    if (!base) return fail(ctx, EDGC_EHIP, "the static scratch of this device was not set up");
+    const EntScratch s{reinterpret_cast<float*>(base),
+                       reinterpret_cast<unsigned int*>(base + kStaticOffDone),
+                       reinterpret_cast<unsigned long long*>(base + kStaticOffCounts),
+                       base + kStaticOffRange, base + kStaticOffResult};
+    return launch_entropy_on(ctx, s, g, dt, bins, range, out, counts_out, st);
 }
 
 int launch_sample_indices(edgc_ctx* ctx, const SampleGeom& g, uint64_t* idx, uint64_t cap,
