@@ -17,6 +17,17 @@
 /* small exact helpers                                                       */
 /* ------------------------------------------------------------------------ */
 
+/* How many threads the loops over independent outputs use from now on (n >= 1);
+ * no effect on any result.  Lets the benchmark time the oracle on one core and on all. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

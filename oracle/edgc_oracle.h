@@ -141,6 +141,7 @@ double oracle_reconstruct_one(const float* P, uint32_t ldp, const float* Q, uint
 float    oracle_bf16_to_f32(uint16_t h);
 uint16_t oracle_f32_to_bf16(float x);
 int      oracle_num_threads(void);
+void     oracle_set_num_threads(int n);   /* threads for the loops over independent outputs */
 
 #ifdef __cplusplus
 }

@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         L.oracle_f32_to_bf16.restype = C.c_uint16
         L.oracle_f32_to_bf16.argtypes = [C.c_float]
         L.oracle_num_threads.restype = C.c_int
+        L.oracle_set_num_threads.restype = None
+        L.oracle_set_num_threads.argtypes = [C.c_int]
         _lib = L
     return _lib
 
@@ -105,6 +107,11 @@ def _check_grad(grad: np.ndarray) -> int:
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the oracle's loops over independent outputs use from now on (no effect on results)."""
+    lib().oracle_set_num_threads(int(n))
 
 
 def mix64(seed: int, ctr: int) -> int:

@@ -206,3 +206,23 @@ def test_bad_arguments_rejected():
         orc.compress(G, None, _q0(8, 9), 9)           # r > min(m, n)
     with pytest.raises(orc.OracleError):
         orc.compress(G, None, _q0(8, 2), 2, power_iters=0)
+
+
+def test_thread_count_does_not_change_any_result():
+    # the oracle's OpenMP loops only split independent outputs: one thread and all threads agree bit for bit
+    G = gen.lowrank_plus_noise(96, 200, 16, 0.9, 1e-3, seed=3)
+    Q0 = np.zeros((200, 8), dtype=np.float32)
+    orc.init_q(Q0, 0, 8, 5)
+    n0 = orc.num_threads()
+    try:
+        outs = []
+        for nt in (1, max(n0, 2)):
+            orc.set_num_threads(nt)
+            assert orc.num_threads() == nt
+            P, Q, D = orc.compress(G, None, Q0, 8)
+            out, E = orc.decompress(P, Q, D, orc.F32)
+            outs.append((P, Q, D, out, E))
+        for a, b in zip(*outs):
+            assert np.array_equal(a, b)
+    finally:
+        orc.set_num_threads(n0)
