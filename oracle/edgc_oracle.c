@@ -511,6 +511,40 @@ int oracle_compress(const void* grad, int dtype, uint32_t m, uint32_t n, uint64_
     return ORACLE_OK;
 }
 
+/* The steps of oracle_compress one by one, for checks of a full-size run on sampled rows and
+ * columns: the same routines the whole step calls, with the operand roundings of R10. */
+int oracle_contract_p(const float* D, uint32_t m, uint32_t n, const float* Q, uint32_t ldq, uint32_t r,
+                      int dtype, float* P, uint32_t ldp)
+{
+    if (!D || !Q || !P || m == 0 || n == 0 || r == 0 || ldq < r || ldp < r) return ORACLE_EINVAL;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+    const int bf = (dtype == ORACLE_BF16);
+    float* Qop = factor_operand(Q, n, ldq, r, bf);
+    if (!Qop) return ORACLE_ENOMEM;
+    contract_P(D, m, n, Qop, r, bf, P, ldp);
+    free(Qop);
+    return ORACLE_OK;
+}
+
+int oracle_contract_q(const float* D, uint32_t m, uint32_t n, const float* P, uint32_t ldp, uint32_t r,
+                      int dtype, float* Q, uint32_t ldq)
+{
+    if (!D || !Q || !P || m == 0 || n == 0 || r == 0 || ldq < r || ldp < r) return ORACLE_EINVAL;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return ORACLE_EINVAL;
+    const int bf = (dtype == ORACLE_BF16);
+    float* Pop = factor_operand(P, m, ldp, r, bf);
+    if (!Pop) return ORACLE_ENOMEM;
+    contract_Q(D, m, n, Pop, r, bf, Q, ldq);
+    free(Pop);
+    return ORACLE_OK;
+}
+
+int oracle_orthonormalise(float* P, uint32_t m, uint32_t r, uint32_t ldp)
+{
+    if (!P || m == 0 || r == 0 || ldp < r) return ORACLE_EINVAL;
+    return orthonormalise(P, m, r, ldp);
+}
+
 double oracle_reconstruct_one(const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
                               uint32_t r, uint32_t i, uint32_t j, int dtype)
 {

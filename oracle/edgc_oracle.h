@@ -133,6 +133,17 @@ int oracle_compress(const void* grad, int dtype, uint32_t m, uint32_t n, uint64_
 int oracle_decompress(const float* P, uint32_t ldp, const float* Q, uint32_t ldq,
                       uint32_t m, uint32_t n, uint32_t r, float* residual,
                       void* grad_out, int dtype, uint64_t ld);
+/* The steps of oracle_compress one by one (the routines the whole step is made of), so that a
+ * full-size run can be checked on gathered rows and columns:
+ *   oracle_contract_p      P = D Q       D: m x n dense (e.g. gathered rows of D), Q: n x r
+ *   oracle_contract_q      Q = D^T P^    D: m x n dense (e.g. gathered columns of D), P: m x r
+ *   oracle_orthonormalise  P -> P^ in place (R9)
+ * dtype selects the operand rounding of R10 (ORACLE_BF16: D, Q, P^ rounded to bf16). */
+int oracle_contract_p(const float* D, uint32_t m, uint32_t n, const float* Q, uint32_t ldq, uint32_t r,
+                      int dtype, float* P, uint32_t ldp);
+int oracle_contract_q(const float* D, uint32_t m, uint32_t n, const float* P, uint32_t ldp, uint32_t r,
+                      int dtype, float* Q, uint32_t ldq);
+int oracle_orthonormalise(float* P, uint32_t m, uint32_t r, uint32_t ldp);
 /* One element of M^ = P^ Q^T (fp64 accumulate, then rounded as decompress does);
  * lets a test check sampled outputs of a full-size run one by one. */
 double oracle_reconstruct_one(const float* P, uint32_t ldp, const float* Q, uint32_t ldq,

@@ -80,6 +80,12 @@ def lib() -> C.CDLL:
                                       u32, u32]
         L.oracle_decompress.restype = C.c_int
         L.oracle_decompress.argtypes = [vp, u32, vp, u32, u32, u32, u32, vp, vp, C.c_int, u64]
+        L.oracle_contract_p.restype = C.c_int
+        L.oracle_contract_p.argtypes = [vp, u32, u32, vp, u32, u32, C.c_int, vp, u32]
+        L.oracle_contract_q.restype = C.c_int
+        L.oracle_contract_q.argtypes = [vp, u32, u32, vp, u32, u32, C.c_int, vp, u32]
+        L.oracle_orthonormalise.restype = C.c_int
+        L.oracle_orthonormalise.argtypes = [vp, u32, u32, u32]
         L.oracle_reconstruct_one.restype = dbl
         L.oracle_reconstruct_one.argtypes = [vp, u32, vp, u32, u32, u32, u32, C.c_int]
         L.oracle_bf16_to_f32.restype = C.c_float
@@ -269,6 +275,43 @@ def decompress(P: np.ndarray, Q: np.ndarray, delta: np.ndarray, dtype: int):
     if rc != OK:
         raise OracleError(rc, "oracle_decompress")
     return out, E
+
+
+def contract_p(D: np.ndarray, Q: np.ndarray, dtype: int) -> np.ndarray:
+    """P = D Q as the compress step forms it (D: rows x n fp32, e.g. gathered rows; Q: n x r)."""
+    D = np.ascontiguousarray(D, dtype=np.float32)
+    Q = np.ascontiguousarray(Q, dtype=np.float32)
+    m, n = D.shape
+    r = Q.shape[1]
+    assert Q.shape[0] == n
+    P = np.zeros((m, r), dtype=np.float32)
+    rc = lib().oracle_contract_p(_ptr(D), m, n, _ptr(Q), r, r, dtype, _ptr(P), r)
+    if rc != OK:
+        raise OracleError(rc, "oracle_contract_p")
+    return P
+
+
+def contract_q(D: np.ndarray, P: np.ndarray, dtype: int) -> np.ndarray:
+    """Q = D^T P^ as the compress step forms it (D: m x cols fp32, e.g. gathered columns; P: m x r)."""
+    D = np.ascontiguousarray(D, dtype=np.float32)
+    P = np.ascontiguousarray(P, dtype=np.float32)
+    m, n = D.shape
+    r = P.shape[1]
+    assert P.shape[0] == m
+    Q = np.zeros((n, r), dtype=np.float32)
+    rc = lib().oracle_contract_q(_ptr(D), m, n, _ptr(P), r, r, dtype, _ptr(Q), r)
+    if rc != OK:
+        raise OracleError(rc, "oracle_contract_q")
+    return Q
+
+
+def orthonormalise(P: np.ndarray) -> np.ndarray:
+    """The orthonormalisation step of compress (modified Gram-Schmidt in fp64) on a copy of P."""
+    out = np.array(P, dtype=np.float32, order="C", copy=True)
+    rc = lib().oracle_orthonormalise(_ptr(out), out.shape[0], out.shape[1], out.shape[1])
+    if rc != OK:
+        raise OracleError(rc, "oracle_orthonormalise")
+    return out
 
 
 def reconstruct_one(P: np.ndarray, Q: np.ndarray, i: int, j: int, dtype: int) -> float:

@@ -226,3 +226,31 @@ def test_thread_count_does_not_change_any_result():
             assert np.array_equal(a, b)
     finally:
         orc.set_num_threads(n0)
+
+
+def test_single_steps_equal_the_whole_step_and_numpy():
+    # contract_p / orthonormalise / contract_q are the routines compress is made of: chained they give
+    # compress bit for bit, on gathered rows / columns they give the corresponding rows of its result, and
+    # each equals the plain NumPy product of the (rounded) operands
+    for dtype, code in (("f32", orc.F32), ("bf16", orc.BF16)):
+        G = gen.lowrank_plus_noise(150, 260, 24, 0.9, 1e-3, seed=8, dtype=dtype)
+        E = gen.gaussian(150 * 260, 1e-4, 9).reshape(150, 260)
+        Q0 = np.zeros((260, 12), dtype=np.float32)
+        orc.init_q(Q0, 0, 12, 4)
+        P, Q1, D = orc.compress(G, E, Q0, 12)
+        P_raw = orc.contract_p(D, Q0, code)
+        P_hat = orc.orthonormalise(P_raw)
+        assert np.array_equal(P_hat, P)
+        assert np.array_equal(orc.contract_q(D, P_hat, code), Q1)
+        rows, cols = [0, 7, 149], [3, 259, 100]
+        assert np.array_equal(orc.contract_p(D[rows], Q0, code), P_raw[rows])
+        assert np.array_equal(orc.contract_q(D[:, cols], P_hat, code), Q1[cols])
+        rnd = (lambda a: gen.bf16_bits_to_f32(gen.to_bf16_bits(a))) if dtype == "bf16" else (lambda a: a)
+        want_p = rnd(D).astype(np.float64) @ rnd(Q0).astype(np.float64)
+        assert np.abs(P_raw - want_p).max() <= 1e-6 * np.abs(want_p).max()
+        want_q = rnd(D).astype(np.float64).T @ rnd(P_hat).astype(np.float64)
+        assert np.abs(Q1 - want_q).max() <= 1e-6 * np.abs(want_q).max()
+        # the orthonormalisation against NumPy's QR with the diagonal of R made positive
+        Qn, Rn = np.linalg.qr(P_raw.astype(np.float64))
+        Qn = Qn * np.sign(np.diag(Rn))
+        assert np.abs(P_hat - Qn).max() <= 1e-5
