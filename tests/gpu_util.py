@@ -31,3 +31,27 @@ def rel_fro(a, b) -> float:
     a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
     den = np.linalg.norm(b)
     return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
+
+
+def elementwise_ratio(got, want, P, Q, chunk=1024) -> float:
+    """max over (i, j) of |got_ij - want_ij| / (||P_i|| ||Q_j||): the reconstruction error of every single
+    element against the scale Cauchy-Schwarz gives it (P: m x r, Q: n x r of the reference)."""
+    npn = np.linalg.norm(np.asarray(P, dtype=np.float64), axis=1)
+    nq = np.linalg.norm(np.asarray(Q, dtype=np.float64), axis=1)
+    worst = 0.0
+    for i0 in range(0, got.shape[0], chunk):
+        d = np.abs(np.asarray(got[i0:i0 + chunk], dtype=np.float64) - np.asarray(want[i0:i0 + chunk], dtype=np.float64))
+        den = npn[i0:i0 + chunk, None] * nq[None, :]
+        ok = den > 0
+        if ok.any():
+            worst = max(worst, float((d[ok] / den[ok]).max()))
+        if (~ok).any():
+            assert float(d[~ok].max()) == 0.0, "non-zero reconstruction where a factor row is zero"
+    return worst
+
+
+# Element-wise bar on the reconstruction, in units of ||p_i|| ||q_j||: the Frobenius tolerance for fp32; with bf16
+# gradients the two sides may round an operand of a term, or the output, to neighbouring bf16 values (their
+# fp32 factors agree to ~1e-5, not to the bit): one bf16 ulp (2^-8 relative) on either operand and on the
+# output, 3 * 2^-8 = 1.17e-2 of ||p_i|| ||q_j|| at most by Cauchy-Schwarz.
+ELEMENTWISE_TOL = {"f32": 1e-3, "bf16": 3.0 / 256.0}

@@ -10,7 +10,7 @@ import torch
 import edgc_inputs as gen
 import paper_2511_10333_amd as edgc
 from oracle import edgc_oracle as orc
-from gpu_util import ctx, rel_fro, to_dev, to_host
+from gpu_util import ELEMENTWISE_TOL, ctx, elementwise_ratio, rel_fro, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -41,7 +41,7 @@ def test_flat_buffer_of_1e9_elements_sampled(dtype):
     with 0.1 % of the values at 100 times the scale).  The oracle gets the sample: its own index
     set gathers the sampled elements, and its estimator runs over them with every element taken;
     counts are compared bit for bit, at strides 1000, 100 and 10 on three bin counts; with every
-    element sampled (4096 bins) the oracle reads the whole buffer."""
+    element sampled the oracle reads the whole buffer (256, 4096 and 65536 bins)."""
     n = 1_000_000_000
     g = torch.Generator(device="cuda").manual_seed(3)
     x = torch.empty(n, device="cuda")
@@ -67,47 +67,77 @@ def test_flat_buffer_of_1e9_elements_sampled(dtype):
             assert got.n_sampled == host.size
             assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts), (stride, bins)
             assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5
-    # every element sampled: the oracle reads the whole buffer
+    # every element sampled: the oracle reads the whole buffer, on all three bin counts (65536 bins: the
+    # histogram no longer fits one LDS slice)
     host = to_host(x) if dtype == "bf16" else x.cpu().numpy()
-    ref = orc.entropy(host, 1, 64, 0, 5, 4096)
-    counts = torch.empty(4096, dtype=torch.int64, device="cuda")
-    got = c.entropy_estimate(x, 1, 64, 0, 5, 4096, None, counts)
-    assert (got.n_sampled, got.n_nonfinite, got.lo, got.hi) == (n, 0, ref.lo, ref.hi)
-    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
-    assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5
+    for bins in (256, 4096, 65536):
+        ref = orc.entropy(host, 1, 64, 0, 5, bins)
+        counts = torch.empty(bins, dtype=torch.int64, device="cuda")
+        got = c.entropy_estimate(x, 1, 64, 0, 5, bins, None, counts)
+        assert (got.n_sampled, got.n_nonfinite, got.lo, got.hi) == (n, 0, ref.lo, ref.hi), bins
+        assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts), bins
+        assert abs(got.H_bits - ref.H_bits) <= 1e-5 and abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5, bins
     del x, host
     torch.cuda.empty_cache()
 
 
 # ---------------------------------------------------------------------------
-# hidden-5120 bf16 attention projection, rank 64, residual carried over three steps
+# hidden-5120 bf16 attention projection at ranks 32, 64 and 128: the same low-rank part with fresh
+# noise every step, the error-feedback residual carried across 10 steps.  Every step the device path
+# is run from the ORACLE's carried state (its residual and warm-started Q) and held to the one-step
+# bar; the device's own chain runs beside it and is checked for what stays unique on a free run:
+# D of the first step, error-feedback conservation and the size of the residual.  (At rank 128 the
+# spectrum 0.97^i leaves the trailing directions of the subspace nearly degenerate: two free runs
+# settle on slightly different bases, P of the two chains is 1.1e-2 apart after ten steps.)
 # ---------------------------------------------------------------------------
-def test_hidden5120_bf16_residual_carried_over_steps():
+@pytest.mark.parametrize("r", [32, 64, 128])
+def test_hidden5120_bf16_residual_carried_over_ten_steps(r):
     m = n = 5120
-    r = 64
+    steps, tol = 10, 1e-2
     U, V = gen.orthonormal_factors(m, n, 512, 1)
     Q0 = np.zeros((n, r), dtype=np.float32)
     orc.init_q(Q0, 0, r, 0)
     c = ctx()
     Qd = to_dev(Q0); Pd = torch.empty((m, r), device="cuda")
     Ed = torch.empty((m, n), device="cuda"); out = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    Pt = torch.empty((m, r), device="cuda"); ot = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
     Qo, Eo = Q0, None
-    for t in range(3):
+    sumG = np.zeros((m, n)); sum_out = torch.zeros((m, n), dtype=torch.float64, device="cuda")
+    for t in range(steps):
         G = gen.lowrank_plus_noise(m, n, 512, 0.97, 1e-4, 1, "bf16", noise_seed=50 + t, factors=(U, V))
-        Po, Qo, Do = orc.compress(G, Eo, Qo, r)
-        out_o, Eo = orc.decompress(Po, Qo, Do, orc.BF16)
         Gd = to_dev(G)
-        c.compress(Gd, Ed, t == 0, Qd, Pd, r)
+        E_prev, Q_prev = Eo, Qo
+        Po, Qo, Do = orc.compress(G, E_prev, Q_prev, r)
+        out_o, Eo = orc.decompress(Po, Qo, Do, orc.BF16)
+        nD = np.linalg.norm(Do.astype(np.float64))
+        # one step of the device path from the oracle's state
+        Et = torch.empty((m, n), device="cuda") if E_prev is None else to_dev(E_prev)
+        Qt = to_dev(Q_prev)
+        c.compress(Gd, Et, E_prev is None, Qt, Pt, r)
         torch.cuda.synchronize()
-        assert rel_fro(to_host(Ed), Do) <= 1e-2                  # D (exact at t = 0)
+        assert np.array_equal(to_host(Et), Do), t                  # D = G + E_old: one fp32 add
+        c.decompress(Pt, Qt, r, Et, ot)
+        torch.cuda.synchronize()
+        assert rel_fro(to_host(Pt), Po) <= tol and rel_fro(to_host(Qt), Qo) <= tol, t
+        got = gen.bf16_bits_to_f32(to_host(ot))
+        assert rel_fro(got, gen.bf16_bits_to_f32(out_o)) <= tol, t
+        assert elementwise_ratio(got, gen.bf16_bits_to_f32(out_o), Po, Qo) <= ELEMENTWISE_TOL["bf16"], t
+        assert np.linalg.norm(to_host(Et).astype(np.float64) - Eo) <= tol * nD, t
+        # the device's own chain
+        c.compress(Gd, Ed, t == 0, Qd, Pd, r)
+        if t == 0:
+            torch.cuda.synchronize()
+            assert np.array_equal(to_host(Ed), Do)
         c.decompress(Pd, Qd, r, Ed, out)
         torch.cuda.synchronize()
-        assert rel_fro(to_host(Pd), Po) <= 1e-2 and rel_fro(to_host(Qd), Qo) <= 1e-2
-        assert rel_fro(gen.bf16_bits_to_f32(to_host(out)), gen.bf16_bits_to_f32(out_o)) <= 1e-2
-        assert np.linalg.norm(to_host(Ed).astype(np.float64) - Eo) <= 1e-2 * np.linalg.norm(Do.astype(np.float64))
-        if t == 0:
-            assert np.array_equal(to_host(Ed) + gen.bf16_bits_to_f32(to_host(out)), Do) or \
-                rel_fro(to_host(Ed) + gen.bf16_bits_to_f32(to_host(out)), Do) < 1e-6
+        sumG += gen.bf16_bits_to_f32(G)
+        sum_out += out.double()
+        if t in (0, steps - 1):
+            Eg = to_host(Ed).astype(np.float64)
+            lost = sumG - sum_out.cpu().numpy() - Eg
+            assert np.linalg.norm(lost) <= 1e-5 * np.linalg.norm(sumG), t
+            assert abs(np.linalg.norm(Eg) - np.linalg.norm(Eo.astype(np.float64))) <= 0.05 * nD, t
+            assert rel_fro(gen.bf16_bits_to_f32(to_host(out)), gen.bf16_bits_to_f32(out_o)) <= 3 * tol, t
 
 
 # ---------------------------------------------------------------------------
@@ -116,13 +146,18 @@ def test_hidden5120_bf16_residual_carried_over_steps():
 # 20-step window, ranks in {4, 8, 16, 32, 64}; both sides run free (their own entropies,
 # their own decisions, their own warm-started Q and residual)
 # ---------------------------------------------------------------------------
-def test_dynamic_rank_run_free_running():
-    hidden, steps, window = 256, 200, 20
+# Two runs: the configuration's own ramp 0.90 -> 0.99 on a hidden-256 replica (the entropy rises, so the
+# reference rank of Theorem 3 is set to r_min: with the paper's r0 = r_max such a run never leaves
+# warm-up), and the ramp reversed, 0.99 -> 0.90, on a hidden-512 replica with the paper's own rule
+# (r_ref = 0, i.e. r0 = r_max): the entropy falls and the rank comes down from r_max.
+@pytest.mark.parametrize("hidden,d0,d1,r_ref", [(256, 0.90, 0.99, 4), (512, 0.99, 0.90, 0)])
+def test_dynamic_rank_run_free_running(hidden, d0, d1, r_ref):
+    steps, window = 200, 20
     shapes = [(hidden, 3 * hidden), (hidden, hidden), (hidden, 4 * hidden), (4 * hidden, hidden)]
     allowed = [4, 8, 16, 32, 64]
     r_max = 64
     prm = dict(m=hidden, n=hidden, r_min=4, r_max=r_max, step_limit=8, allowed=allowed, eta=1.0,
-               total_iters=steps, min_warmup_frac=0.10, r_ref=4)
+               total_iters=steps, min_warmup_frac=0.10, r_ref=r_ref)
     factors = [gen.orthonormal_factors(m, n, min(m, n), 30 + i) for i, (m, n) in enumerate(shapes)]
     sizes = [m * n for m, n in shapes]
     offs = np.concatenate([[0], np.cumsum(sizes)])
@@ -146,7 +181,7 @@ def test_dynamic_rank_run_free_running():
     sum_out = [torch.zeros((m, n), device="cuda", dtype=torch.float64) for m, n in shapes]
     ranks_seen = []
     for t in range(steps):
-        decay = 0.90 + 0.09 * t / (steps - 1)
+        decay = d0 + (d1 - d0) * t / (steps - 1)
         host = np.empty(int(offs[-1]), dtype=np.float32)
         for i, (m, n) in enumerate(shapes):
             g = gen.lowrank_plus_noise(m, n, min(m, n), decay, 1e-4, 7, noise_seed=1000 * i + t, factors=factors[i])
@@ -208,7 +243,11 @@ def test_dynamic_rank_run_free_running():
     torch.cuda.synchronize()
     assert ranks_seen[0] == 0                       # first window only fixes the reference
     assert len(set(r for r in ranks_seen if r)) >= 3, ranks_seen     # the rank really changed
-    assert ranks_seen == sorted(ranks_seen)         # entropy rises with the flattening spectrum
+    if d1 > d0:
+        assert ranks_seen == sorted(ranks_seen)     # entropy rises with the flattening spectrum
+    else:                                           # entropy falls: down from r_max once warm-up is over
+        live = [r for r in ranks_seen if r]
+        assert live[0] == r_max and live == sorted(live, reverse=True), ranks_seen
 
 
 # ---------------------------------------------------------------------------
@@ -240,3 +279,54 @@ def test_hidden4096_layer_full_size_teacher_forced(m, n, r):
         assert rel_fro(to_host(out), out_o) <= 1e-3, (t, r)
         assert np.linalg.norm(to_host(Ed).astype(np.float64) - E_o) <= 1e-3 * np.linalg.norm(Do.astype(np.float64))
         E_prev, Q_prev = E_o, Qn
+
+
+# ---------------------------------------------------------------------------
+# A rank change at the real layer size, from the ORACLE's state, through the calls a trainer makes:
+# the deferred state of a step (D, P^, Q of the oracle) is loaded into the device buffers,
+# edgc_residual_materialize_batch carries the subtraction out at the old rank, edgc_init_q seeds the
+# columns a larger rank adds (a smaller rank keeps the leading ones), and the step at the new rank is
+# compared with the oracle's step from its own residual and factors: the residual survives the change.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n,r1,r2", [(4096, 4096, 8, 16), (4096, 16384, 32, 64), (16384, 4096, 64, 32)])
+def test_hidden4096_rank_change_full_size_teacher_forced(m, n, r1, r2):
+    tol, ld, seed = 1e-3, 64, 5
+    factors = gen.orthonormal_factors(m, n, 256, 77)
+    Q0 = np.zeros((n, ld), dtype=np.float32)
+    orc.init_q(Q0, 0, ld, seed)
+    GA = gen.lowrank_plus_noise(m, n, 256, 0.90, 1e-4, 7, noise_seed=901, factors=factors)
+    GB = gen.lowrank_plus_noise(m, n, 256, 0.95, 1e-4, 7, noise_seed=902, factors=factors)
+    PA, QA, DA = orc.compress(GA, None, np.ascontiguousarray(Q0[:, :r1]), r1)
+    _, EA = orc.decompress(PA, QA, DA, orc.F32)
+    # the oracle's step at the new rank
+    if r2 > r1:
+        Qb = np.concatenate([QA, Q0[:, r1:r2]], axis=1)          # old columns kept, new ones seeded
+    else:
+        Qb = np.ascontiguousarray(QA[:, :r2])
+    PB, QB, DB = orc.compress(GB, EA, Qb, r2)
+    outB, EB = orc.decompress(PB, QB, DB, orc.F32)
+    # the device: deferred state of step A in the buffers
+    c = edgc.Context(0, max_bins=16, max_rank=ld, max_rows=64, max_cols=64)
+    c.reserve_batch([(m, n)])
+    res = to_dev(DA)
+    Pd = torch.zeros((m, ld), device="cuda"); Pd[:, :r1] = to_dev(PA)
+    Qd = torch.full((n, ld), float("nan"), device="cuda"); Qd[:, :r1] = to_dev(QA)
+    out = torch.empty((m, n), device="cuda")
+    ts = [edgc.Tensor(to_dev(GB), out, res, Qd, Pd, False)]
+    c.residual_materialize_batch(ts, r1)
+    torch.cuda.synchronize()
+    nDA = np.linalg.norm(DA.astype(np.float64))
+    assert np.linalg.norm(to_host(res).astype(np.float64) - EA) <= tol * nDA
+    if r2 > r1:
+        c.init_q(Qd, r1, r2, seed)
+        torch.cuda.synchronize()
+        assert rel_fro(to_host(Qd)[:, r1:r2], Q0[:, r1:r2]) <= 1e-6
+    c.compress_batch(ts, r2, deferred=False)                     # the buffer holds E itself now
+    torch.cuda.synchronize()
+    assert rel_fro(to_host(res), DB) <= tol
+    c.decompress_batch(ts, r2, deferred=True)
+    torch.cuda.synchronize()
+    assert rel_fro(to_host(Pd)[:, :r2], PB) <= tol and rel_fro(to_host(Qd)[:, :r2], QB) <= tol
+    assert rel_fro(to_host(out), outB) <= tol
+    assert elementwise_ratio(to_host(out), outB, PB, QB) <= ELEMENTWISE_TOL["f32"]
+    c.close()

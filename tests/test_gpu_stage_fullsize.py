@@ -1,11 +1,12 @@
 """The whole 8-layer stage of the dynamic-rate configuration at full size (32 tensors, 1.61e9 fp32
 elements, hidden 4096) in the layout bench.py times: two batched groups, one stage-level entropy
 estimate, the residual in the deferred form, ranks changing between steps.  The CPU oracle cannot
-run whole steps at this size in seconds, so what is compared is what it can compute one by one:
+run whole steps at this size in seconds, so its own steps are run on what it can take one by one:
 the entropy of the 1 % sample (gathered, bit-exact counts), sampled elements of D (the recurrence
-with the deferred subtraction, bit for bit), sampled rows of P = D Q, the orthonormalisation as a
-property (P^T P = I, P = P^ R with R upper triangular and a positive diagonal), sampled rows of
-Q = D^T P^, and sampled elements of the reconstruction P^ Q^T.  The same walk runs over the
+with the deferred subtraction, bit for bit), the oracle's P = D Q on gathered rows of D, its
+orthonormalisation of the device's P (whole factor, one tensor of every shape; P^T P = I and
+P = P^ R with R upper triangular and a positive diagonal for all of them), its Q = D^T P^ on gathered
+columns of D, and its reconstruction of sampled elements.  The same walk runs over the
 hidden-5120 block with bf16 gradients (its 20480 x 5120 matrix is the largest of the workloads)
 at ranks 128, 32 and 64, and over a single matrix of more than 2^31 elements."""
 import numpy as np
@@ -51,6 +52,8 @@ def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, eleme
     NT = len(shapes)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     tol = 1e-2 if dtype == "bf16" else 1e-3
+    code = orc.BF16 if dtype == "bf16" else orc.F32
+    first_of_shape = {s: i for i, s in reversed(list(enumerate(shapes)))}
     dev = torch.device("cuda")
     rmax, kdim = max(RANKS), 24
     rng = np.random.default_rng(7)
@@ -139,11 +142,13 @@ def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, eleme
                 # deferred to this P-pass or carried out by the materialisation before a rank change
                 assert np.array_equal(d_now, g_now + (d_prev[i] - out_prev[i])), (step, i)
             assert np.abs(d_now).max() > 0
-            for row in rows[i]:                     # sampled rows of P = D Q in fp64
-                d_row = res[i][row].double().cpu().numpy()
-                want_row = d_row @ q_old[i].double().cpu().numpy()
-                got_row = p_raw[i][row].cpu().numpy()
-                assert np.linalg.norm(got_row - want_row) <= tol * np.linalg.norm(want_row) + 1e-12, (step, i, row)
+            # the oracle's P = D Q on the gathered rows of D (its operand roundings included)
+            rr = torch.from_numpy(np.asarray(rows[i], dtype=np.int64)).to(dev)
+            want_rows = orc.contract_p(res[i][rr].cpu().numpy(), q_old[i].cpu().numpy(), code)
+            got_rows = p_raw[i][rr].cpu().numpy()
+            for k in range(len(rows[i])):
+                assert np.linalg.norm(got_rows[k] - want_rows[k].astype(np.float64)) <= \
+                    tol * np.linalg.norm(want_rows[k].astype(np.float64)) + 1e-12, (step, i, rows[i][k])
         # --- second phase: orthonormalisation and Q = D^T P^ ------------------------------------------
         for c, ts in zip(ctxs, tens):
             c.compress_q_batch(ts, r)
@@ -156,11 +161,18 @@ def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, eleme
             scale = np.abs(np.diag(R)).max()
             assert np.abs(np.tril(R, -1)).max() <= 1e-4 * scale and (np.diag(R) > 0).all(), (step, i)
             assert np.linalg.norm(ph @ R - pr) <= 1e-4 * np.linalg.norm(pr), (step, i)
-            for col in cols[i]:                     # sampled rows of Q = D^T P^
-                d_col = res[i][:, col].double().cpu().numpy()
-                want_q = d_col @ ph
-                got_q = Q[i][col, :r].cpu().numpy()
-                assert np.linalg.norm(got_q - want_q) <= tol * np.linalg.norm(want_q) + 1e-12, (step, i, col)
+            if first_of_shape[(m, n)] == i:         # the oracle's orthonormalisation of the same P, whole factor
+                want_ph = orc.orthonormalise(p_raw[i].cpu().numpy())
+                got_ph = P[i][:, :r].cpu().numpy()
+                assert np.linalg.norm(got_ph.astype(np.float64) - want_ph) <= tol * np.sqrt(r), (step, i)
+                assert np.abs(got_ph.astype(np.float64) - want_ph).max() <= tol * np.abs(want_ph).max(), (step, i)
+            # the oracle's Q = D^T P^ on the gathered columns of D, from the device's P^
+            cc = torch.from_numpy(np.asarray(cols[i], dtype=np.int64)).to(dev)
+            want_q = orc.contract_q(res[i][:, cc].cpu().numpy(), P[i][:, :r].cpu().numpy(), code)
+            got_q = Q[i][cc, :r].cpu().numpy()
+            for k in range(len(cols[i])):
+                assert np.linalg.norm(got_q[k] - want_q[k].astype(np.float64)) <= \
+                    tol * np.linalg.norm(want_q[k].astype(np.float64)) + 1e-12, (step, i, cols[i][k])
         # --- reconstruction ------------------------------------------------------------------------------
         for c, ts in zip(ctxs, tens):
             c.decompress_batch(ts, r, deferred=True)
@@ -170,9 +182,11 @@ def test_stage_at_full_size_sampled_against_the_oracle(name, dtype, RANKS, eleme
         d_prev, out_prev = [], []
         for i, (m, n) in enumerate(shapes):
             ii, jj = pos[i]
-            ph = P[i][ii, :r].double().cpu().numpy()
-            qh = Q[i][jj, :r].double().cpu().numpy()
-            want_o = np.einsum("kr,kr->k", ph, qh)
+            ti, tj = torch.from_numpy(ii).to(dev), torch.from_numpy(jj).to(dev)
+            p32, q32 = P[i][ti, :r].cpu().numpy(), Q[i][tj, :r].cpu().numpy()
+            ph, qh = p32.astype(np.float64), q32.astype(np.float64)
+            # the oracle's reconstruction of the sampled elements (rounded to the gradient's dtype as it rounds)
+            want_o = np.array([orc.reconstruct_one(p32[k:k + 1], q32[k:k + 1], 0, 0, code) for k in range(len(ii))])
             got_o = out[i][ii, jj].float().cpu().numpy()
             bound = tol * np.linalg.norm(ph, axis=1) * np.linalg.norm(qh, axis=1) + 1e-12
             assert (np.abs(got_o - want_o) <= bound).all(), (step, i)
