@@ -513,17 +513,11 @@ __device__ __forceinline__ double pivot_rsq(double d)
 // A pivot not above kPivotEps is dead: nothing is eliminated with it, and its row and column of
 // X end up zero; the return value has bit c set for a dead pivot c.
 // Must be called by a whole wavefront.
-#ifdef EDGC_CHOL_TIMING
-#define EDGC_CHOL_DBG_ARG , int dbg
-#define EDGC_CHOL_DBG_PASS , dbg
-#else
-#define EDGC_CHOL_DBG_ARG
-#define EDGC_CHOL_DBG_PASS
-#endif
-__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane EDGC_CHOL_DBG_ARG)
+__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane)
 {
     const int i = lane & 15, q = lane >> 4;
     uint32_t dead = 0;
+    double mop_prev = 0.0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) x[v] = (q + 4 * v == i) ? 1.0 : 0.0;
 #pragma unroll
@@ -531,25 +525,25 @@ __device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int
         const int kb = c >> 2, k = c & 3;
         const double d = readlane_f64(s[kb], c + 16 * k);        // S[c][c]
         const bool ok = d > kPivotEps;
-#ifdef EDGC_CHOL_TIMING
-        const double rd = ok ? ((dbg & 2) ? __builtin_amdgcn_rcp(d) : pivot_rcp(d)) : 0.0;
-#else
         const double rd = ok ? pivot_rcp(d) : 0.0;
-#endif
         if (!ok) dead |= 1u << c;
         const bool col = (q == k) && i >= c;                       // lanes of group k: S[c][i] = S[i][c]
         const double sic = col ? s[kb] : 0.0;
         const double neg = -(sic * rd);                            // -s_i / d; -1 on the pivot's own lane
         s = __builtin_amdgcn_mfma_f64_16x16x4f64(neg, sic, s, 0, 0, 0);
-#ifdef EDGC_CHOL_TIMING
-        if (dbg & 1) continue;
-        const double rs = ok ? ((dbg & 4) ? __builtin_amdgcn_rsq(d) : pivot_rsq(d)) : 0.0;
-#else
+        // The row operation of pivot c - 1 on X is issued here, one pivot late: it waits for the one before
+        // it, which by now has finished, so the chain of S behind it is not held up.
+        if (c > 0) {
+            const int kbp = (c - 1) >> 2, kp = (c - 1) & 3;
+            const double xrow = (q == kp) ? x[kbp] : 0.0;          // lane (j, k'): X[c - 1][j]
+            x = __builtin_amdgcn_mfma_f64_16x16x4f64(mop_prev, xrow, x, 0, 0, 0);
+        }
         const double rs = ok ? pivot_rsq(d) : 0.0;                 // 1 / l_c, off the chain of S
-#endif
-        const double mop = (col && i == c) ? rs - 1.0 : neg;
-        const double xrow = (q == k) ? x[kb] : 0.0;                // lane (j, k): X[c][j]
-        x = __builtin_amdgcn_mfma_f64_16x16x4f64(mop, xrow, x, 0, 0, 0);
+        mop_prev = (col && i == c) ? rs - 1.0 : neg;
+    }
+    {
+        const double xrow = (q == 3) ? x[3] : 0.0;                 // pivot 15
+        x = __builtin_amdgcn_mfma_f64_16x16x4f64(mop_prev, xrow, x, 0, 0, 0);
     }
     return dead;
 }
@@ -581,19 +575,7 @@ __device__ __forceinline__ void chol_inverse_tile(double* A, const double* Xd, i
     for (int v = 0; v < 4; ++v) A[(16 * p + lr) * LDA + 16 * i + lq + 4 * v] = xo[v];  // transposed
 }
 
-#ifdef EDGC_CHOL_TIMING
-// developer build only: shader-clock stamps of the phases of block 0
-__device__ unsigned long long g_chol_clk[64];
-#define EDGC_CHOL_TS(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_chol_clk[i] = __builtin_readcyclecounter(); } while (0)
-extern "C" int edgc_debug_chol_clk(unsigned long long* out)
-{
-    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_chol_clk), sizeof(g_chol_clk)) == hipSuccess ? 0 : -3;
-}
-#else
-#define EDGC_CHOL_TS(i) do { } while (0)
-#endif
-
-__global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t T16 EDGC_CHOL_DBG_ARG)
+__global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t T16)
 {
     const TensorArgs& ta_ = grp.t[blockIdx.x];          // one block per tensor
     const double* __restrict__ tiles = ta_.tiles;
@@ -612,7 +594,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
     const uint32_t ntile = T16 * (T16 + 1) / 2, ne = ntile * 256;
     const int lr = lane & 15, lq = lane >> 4;         // MFMA fragment coordinates
 
-    EDGC_CHOL_TS(0);
     // ---- assemble the scaled Gram matrix C = D W D (lower triangle) ----
     // Every thread's entries are requested at once (registers), the diagonal first for the scales.
     constexpr int kMaxPerThread = (36 * 256 + kCholThreads - 1) / kCholThreads;
@@ -631,21 +612,27 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
         }
     }
     for (int e = tid; e < RPAD * LDA; e += kCholThreads) A[e] = 0.0;
-    if (nb > 1) {                                     // ne == 256: four interleaved groups per entry
+    if (nb > 1) {                                     // ne == 256: interleaved groups of blocks per entry
+        constexpr uint32_t NG = kCholThreads / 256;
         const uint32_t e = tid & 255, grp = tid >> 8;
         double sacc = 0.0;
         uint32_t b = grp;
-        for (; b + 28 < nb; b += 32) {
+        for (; b + 7 * NG < nb; b += 8 * NG) {
             double xx[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) xx[u] = tiles[static_cast<size_t>(b + 4 * u) * ne + e];
+            for (int u = 0; u < 8; ++u) xx[u] = tiles[static_cast<size_t>(b + NG * u) * ne + e];
 #pragma unroll
             for (int u = 0; u < 8; ++u) sacc += xx[u];
         }
-        for (; b < nb; b += 4) sacc += tiles[static_cast<size_t>(b) * ne + e];
+        for (; b < nb; b += NG) sacc += tiles[static_cast<size_t>(b) * ne + e];
         red[tid] = sacc;
         __syncthreads();
-        if (tid < 256) red[tid] = ((red[tid] + red[tid + 256]) + red[tid + 512]) + red[tid + 768];
+        if (tid < 256) {
+            double t = red[tid];
+#pragma unroll
+            for (uint32_t g2 = 1; g2 < NG; ++g2) t += red[tid + 256 * g2];
+            red[tid] = t;
+        }
         __syncthreads();
         if (tid < 16) {
             const double w = red[tid * 17];
@@ -666,11 +653,9 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
     }
     __syncthreads();
 
-    EDGC_CHOL_TS(1);
     // ---- blocked right-looking Cholesky ----
     for (int p = 0; p < T; ++p) {
         const int j0 = 16 * p;
-        EDGC_CHOL_TS(2 + 4 * p);
         if (wave == 0) {
             // the diagonal tile as a full symmetric tile (its lower triangle is what A holds)
             f64x4 st, xt;
@@ -679,7 +664,7 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
                 const int a = lq + 4 * v, b = lr;                 // element [a][b]
                 st[v] = A[(j0 + max(a, b)) * LDA + j0 + min(a, b)];
             }
-            const uint32_t dead = chol16_factor_invert(st, xt, lane EDGC_CHOL_DBG_PASS);
+            const uint32_t dead = chol16_factor_invert(st, xt, lane);
 #pragma unroll
             for (int v = 0; v < 4; ++v) Xd[(p * 16 + lq + 4 * v) * 17 + lr] = xt[v];   // X[row][col]
             if (lane == 0) deadmask[p] = dead;
@@ -688,7 +673,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             // X = L^-1: everything it needs (row p-1 of L, X_(p-1)(p-1), the rows of X above) is final.
             for (int j = wave - 1; j < p - 1; j += NW - 1) chol_inverse_tile(A, Xd, LDA, p - 1, j, lr, lq);
         }
-        EDGC_CHOL_TS(3 + 4 * p);
         __syncthreads();
         // panel solve: L_ip = C_ip X_pp^T for tiles i > p
         for (int i = p + 1 + wave; i < T; i += NW) {
@@ -703,7 +687,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + j0 + lr] = acc[v];
         }
         __syncthreads();
-        EDGC_CHOL_TS(4 + 4 * p);
         // trailing update: C_ic -= L_ip L_cp^T for p < c <= i
         const int rem = T - p - 1, npair = rem * (rem + 1) / 2;
         for (int idx = wave; idx < npair; idx += NW) {
@@ -725,12 +708,10 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
         __syncthreads();
     }
 
-    EDGC_CHOL_TS(40);
     // the last row of the inverse, with every wavefront
     for (int j = wave; j + 1 < T; j += NW) chol_inverse_tile(A, Xd, LDA, T - 1, j, lr, lq);
     __syncthreads();
 
-    EDGC_CHOL_TS(41);
     // ---- R^-1[k][c] = d_k X[c][k] for k <= c, zero elsewhere and for removed columns ----
     const int sh = 31 - __clz(RPAD);                  // RPAD is a power of two
     for (uint32_t e = tid; e < static_cast<uint32_t>(RPAD * RPAD); e += kCholThreads) {
@@ -745,7 +726,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
         }
         rinv[static_cast<size_t>(k) * r + c] = v;
     }
-    EDGC_CHOL_TS(42);
 }
 
 // ---------------------------------------------------------------------------
@@ -2247,14 +2227,8 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
     }
     const size_t rpad = 16 * t16;
     const size_t chol_lds = (rpad * (rpad + 1) + t16 * 16 * 17 + rpad + kCholThreads) * sizeof(double) + t16 * sizeof(uint32_t);
-#ifdef EDGC_CHOL_TIMING
-    const int chol_dbg = getenv("EDGC_CHOL_DBG") ? atoi(getenv("EDGC_CHOL_DBG")) : 0;
-#define EDGC_CHOL_DBG_VAL , chol_dbg
-#else
-#define EDGC_CHOL_DBG_VAL
-#endif
     EDGC_LAUNCH(ctx, st, KID_CHOL, bytes, g.count * 2.0 * r * r * r / 3.0,
-                k_chol<<<g.count, kCholThreads, chol_lds, st>>>(g, t16 EDGC_CHOL_DBG_VAL));
+                k_chol<<<g.count, kCholThreads, chol_lds, st>>>(g, t16));
     EDGC_HIP_TRY(ctx, hipGetLastError());
 
     // P^ = P R^-1 and its transposed bf16 copy
