@@ -11,7 +11,9 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
     with 0.1 % of the values at 100 times the scale, generated on the device; sampling strides 1000,
     100, 10 and 1 (0.1 % to 100 %) times 256, 4096 and 65536 bins.  One "step" is one estimate
     (range, histogram, entropy) of one cell; the JSON line carries every cell and, as `value`, the
-    100 % / 4096-bin cell of the fp32 buffer, whose two passes read the whole buffer twice."""
+    100 % / 4096-bin cell of the fp32 buffer, whose two passes read the whole buffer twice.  A cell's
+    `reads_of_sample` says how often its kernels read the sample (bf16 samples of 32 Mi elements or
+    more are read once), `sample_gbs` = those reads x sample bytes / time."""
     from paper_2511_10333_amd.binding import ENTROPY_RESULT_BYTES, EntropyResult
     n, chunk, seed = 1_000_000_000, 64, 0
     strides, bins_list = (1000, 100, 10, 1), (256, 4096, 65536)
@@ -44,7 +46,7 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
                 ms = ev0.elapsed_time(ev1) / reps
                 res = EntropyResult.from_buffer(out.numpy().tobytes())
                 # the same launches once more, each kernel between its own pair of events
-                ctx.profile_begin(4 * reps + 8)
+                ctx.profile_begin(6 * reps + 8)
                 for t in range(reps):
                     ctx.entropy_estimate_async(x, stride, chunk, seed, t, bins, out)
                 torch.cuda.synchronize()
@@ -53,9 +55,15 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
                                 gbs=round(v["bytes"] / (v["total_ms"] * 1e-3) / 1e9, 1))
                         for k, v in ks.items() if v["launches"] and v["total_ms"] > 0}
                 sample_bytes = res.n_sampled * esz
+                # reads of the sample: the range pass (not for bf16 counted by bit pattern) and one binning pass
+                # (two for fp32 on more than 32768 bins without the 16-bit counters); kernels that only check
+                # the overflow gate and return (a few microseconds, no bytes) do not count
+                live = {k: v for k, v in kern.items() if v["avg_us"] >= 4.0 or k.startswith("k_wide")}
+                reads = (1 if "k_minmax" in live else 0) + (1 if "k_wide_hist" in live else 0) + \
+                        ((2 if bins > 32768 else 1) if "k_hist" in live else 0)
                 cell = dict(dtype=dtype, stride=stride, bins=bins, n_sampled=res.n_sampled, ms=round(ms, 4),
-                            gradient_gbs=round(n * esz / (ms * 1e-3) / 1e9, 1),
-                            sample_gbs_two_passes=round(2 * sample_bytes / (ms * 1e-3) / 1e9, 1),
+                            gradient_gbs=round(n * esz / (ms * 1e-3) / 1e9, 1), reads_of_sample=reads,
+                            sample_gbs=round(reads * sample_bytes / (ms * 1e-3) / 1e9, 1),
                             H_bits=round(res.H_bits, 6), kernels=kern)
                 cells.append(cell)
                 if dtype == "f32" and stride == 1 and bins == 4096:

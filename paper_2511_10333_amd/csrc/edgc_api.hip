@@ -12,7 +12,7 @@ namespace edgc {
 const char* const kKernelNames[KID_COUNT] = {
     "k_set_range", "k_minmax", "k_hist", "k_sample_indices", "k_init_q", "k_pass_p",
     "k_reduce_gram", "k_gram_sum", "k_chol", "k_apply", "k_pass_q", "k_reduce_q", "k_decompress",
-    "k_pass_p_deferred"};
+    "k_pass_p_deferred", "k_wide_hist", "k_wide_reduce"};
 }
 
 namespace {
@@ -38,7 +38,7 @@ void free_batch(edgc_ctx* ctx)
 
 void free_scratch(Scratch& s)
 {
-    void* ptrs[] = {s.mm_part, s.done_counter, s.counts, s.range, s.result_dev,
+    void* ptrs[] = {s.mm_part, s.done_counter, s.part16, s.wide, s.totals, s.counts, s.range, s.result_dev,
                     s.part, s.gram_part, s.gram, s.rinv, s.pt};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -77,6 +77,8 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     if (const char* e = getenv("EDGC_TUNE_STREAM")) ctx->tune_stream = atoi(e);
     if (const char* e = getenv("EDGC_TUNE_FULL")) ctx->tune_full = atoi(e);
     if (const char* e = getenv("EDGC_TUNE_DFULL")) ctx->tune_dfull = atoi(e);
+    if (const char* e = getenv("EDGC_TUNE_PATTERN")) ctx->tune_pattern = atoi(e);
+    if (const char* e = getenv("EDGC_TUNE_PATTERN_MIN")) ctx->tune_pattern_min = atoll(e);
 
     Scratch& s = ctx->s;
     const uint64_t rp = (max_rank <= 32) ? 32 : (max_rank <= 64 ? 64 : 128);
@@ -88,6 +90,10 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     bool ok = true;
     ok = ok && dev_alloc(&s.mm_part, 2 * kMaxReduceBlocks) == hipSuccess;
     ok = ok && dev_alloc(&s.done_counter, 4) == hipSuccess;
+    s.part16_blocks = static_cast<uint32_t>(ctx->num_cu);
+    ok = ok && dev_alloc(&s.part16, static_cast<size_t>(s.part16_blocks) * 65536) == hipSuccess;
+    ok = ok && dev_alloc(&s.wide, 65536) == hipSuccess;
+    ok = ok && dev_alloc(&s.totals, 65536) == hipSuccess;
     ok = ok && dev_alloc(&s.counts, max_bins) == hipSuccess;
     ok = ok && hipMalloc(&s.range, 64) == hipSuccess;
     ok = ok && hipMalloc(&s.result_dev, sizeof(edgc_entropy_result)) == hipSuccess;
@@ -97,6 +103,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     ok = ok && dev_alloc(&s.rinv, static_cast<size_t>(max_rank) * max_rank) == hipSuccess;
     ok = ok && hipMalloc(&s.pt, s.pt_bytes) == hipSuccess;
     ok = ok && hipMemset(s.done_counter, 0, 4 * sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipMemset(s.wide, 0, 65536 * sizeof(unsigned long long)) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     ok = ok && prepare_entropy_kernels(ctx) == EDGC_OK && prepare_compress_kernels(ctx) == EDGC_OK;
     ok = ok && resolve_static_scratch(ctx) == EDGC_OK;

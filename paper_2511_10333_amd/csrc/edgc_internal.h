@@ -15,7 +15,11 @@ namespace edgc {
 struct Scratch {
     // entropy
     float*              mm_part      = nullptr;  // [2 * kMaxReduceBlocks] per-block (lo, hi)
-    unsigned int*       done_counter = nullptr;  // [4] last-block tickets, zero between calls
+    unsigned int*       done_counter = nullptr;  // [4] last-block tickets and the overflow gate, zero between calls
+    uint16_t*           part16       = nullptr;  // [part16_blocks][65536] 16-bit counters per block
+    uint32_t            part16_blocks = 0;
+    unsigned long long* wide         = nullptr;  // [65536] 64-bit credits per key, zero between calls
+    unsigned long long* totals       = nullptr;  // [65536] counts per bf16 bit pattern
     unsigned long long* counts       = nullptr;  // [max_bins] histogram when the caller gives none
     void*               range        = nullptr;  // RangeParams
     void*               result_dev   = nullptr;  // edgc_entropy_result
@@ -98,7 +102,7 @@ struct BatchSlot {
 enum KernelId {
     KID_SET_RANGE = 0, KID_MINMAX, KID_HIST, KID_SAMPLE_IDX, KID_INIT_Q, KID_PASS_P,
     KID_REDUCE_GRAM, KID_GRAM_SUM, KID_CHOL, KID_APPLY, KID_PASS_Q, KID_REDUCE_Q, KID_DECOMPRESS,
-    KID_PASS_P_DEFERRED, KID_COUNT
+    KID_PASS_P_DEFERRED, KID_WIDE_HIST, KID_WIDE_REDUCE, KID_COUNT
 };
 extern const char* const kKernelNames[KID_COUNT];
 
@@ -132,6 +136,11 @@ struct edgc_ctx {
                             // the whole-tile kernel with that many waves per block at every rank
     int tune_full = -1;     // P-pass of whole-tile groups: -1 built-in choice; 0 the general kernels;
                             // 1 / 2 the whole-tile kernel with the Q rows requested early / late
+    int tune_pattern = 1;   // entropy estimate: 1 one read into 16-bit counters per block where that applies
+                            // (bf16 samples, fp32 on more than 16384 bins); 0 the plain kernels only; 3 as 1,
+                            // and every such estimate reports a counter overflow (tests of the redo path)
+    long long tune_pattern_min = 32 << 20;  // bf16 samples from this many elements on are counted by bit pattern
+                                            // (on more than 16384 bins: from an eighth of it on)
     edgc::Scratch s;
     std::vector<edgc::BatchSlot> batch;
     edgc::Profiler prof;

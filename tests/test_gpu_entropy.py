@@ -3,6 +3,7 @@
 Bar: sample indices, range and histogram counts bit-exact; entropy within 1e-5
 absolute (both sides evaluate it in fp64 from identical integer counts)."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -18,11 +19,11 @@ pytestmark = pytest.mark.gpu
 H_TOL = 1e-5
 
 
-def _compare(x_host, stride, chunk, seed, step, bins, value_range=None, x_dev=None):
+def _compare(x_host, stride, chunk, seed, step, bins, value_range=None, x_dev=None, c=None):
     ref = orc.entropy(x_host, stride, chunk, seed, step, bins, value_range)
     xd = to_dev(x_host) if x_dev is None else x_dev
     counts = torch.full((bins,), -1, dtype=torch.int64, device="cuda")
-    got = ctx().entropy_estimate(xd, stride, chunk, seed, step, bins, value_range, counts)
+    got = (c or ctx()).entropy_estimate(xd, stride, chunk, seed, step, bins, value_range, counts)
     assert got.status == 0
     assert (got.n_sampled, got.n_nonfinite) == (ref.n_sampled, ref.n_nonfinite)
     assert (got.lo, got.hi) == (ref.lo, ref.hi)
@@ -204,4 +205,69 @@ def test_seeded_sweep_of_sizes_offsets_strides_chunks_and_bins(dtype):
         assert abs(got.H_bits - ref.H_bits) <= 1e-5, case
         # (a sample of one value has no width: -inf on both sides)
         assert got.h_diff_nats == ref.h_diff_nats or abs(got.h_diff_nats - ref.h_diff_nats) <= 1e-5, case
+    c.close()
+
+
+
+def _context_with(**env):
+    """A context created under the library's tuning variables (read once, at edgc_create)."""
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update({k: str(v) for k, v in env.items()})
+    try:
+        return edgc.Context(0, max_bins=1 << 17, max_rank=4, max_rows=64, max_cols=64)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                del os.environ[k]
+            else:
+                os.environ[k] = v
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", ["one_read", "redo", "plain"])
+def test_sixteen_bit_counter_kernels_on_small_and_ragged_samples(mode, dtype):
+    """The one-read kernels (16-bit counters per block; bf16 samples counted by bit pattern, fp32
+    samples on more than 16384 bins) are chosen for large samples by default; here they take every
+    sample.  `redo`: every such estimate also reports a counter overflow, so the kernels queued
+    behind it compute the result again from zeroed counters.  `plain`: the two-pass kernels alone.
+    All three must give the oracle's counts, range and entropy."""
+    c = _context_with(EDGC_TUNE_PATTERN={"one_read": 1, "redo": 3, "plain": 0}[mode], EDGC_TUNE_PATTERN_MIN=0)
+    bins_list = [16, 256, 4096, 20000, 65536] + ([100000] if dtype == "bf16" else [])
+    rng = np.random.default_rng(77)
+    big = gen.laplace_mixture(3_000_000, 5, dtype=dtype)
+    for n in (1, 9, 64, 4097, 262_147, 2_999_999):
+        for off in (0, 1):
+            host = big[off:off + n].copy()
+            if n > 1000:
+                host[rng.integers(0, n, 4)] = 0x7fc0 if dtype == "bf16" else np.float32(np.nan)
+                host[rng.integers(0, n)] = 0x7f80 if dtype == "bf16" else np.float32(np.inf)
+                host[n // 2: n // 2 + 700] = 0                    # a run of equal values
+            dev = to_dev(big[:off + n].copy())
+            dev[off:] = to_dev(host)
+            for bins in bins_list:
+                stride, chunk = int(rng.choice([1, 3, 10])), int(rng.choice([1, 8, 64, 256]))
+                try:
+                    _compare(host, stride, chunk, 11, int(rng.integers(0, 50)), bins, x_dev=dev[off:], c=c)
+                except orc.OracleError:
+                    continue
+    x = big[:500_000]
+    _compare(x, 2, 64, 0, 0, 1024, value_range=(-0.01, 0.01), c=c)
+    _compare(x, 1, 64, 0, 0, 40000, value_range=(-0.02, 0.05), c=c)
+    _compare(x, 1, 64, 0, 0, 64, value_range=(0.0, 0.0), c=c)
+    const = np.full(70_000, big[17], dtype=big.dtype)             # one value 70000 times: 16-bit fields wrap twice
+    for bins in (256, 40000):
+        got, _ = _compare(const, 1, 64, 0, 0, bins, c=c)
+        assert got.H_bits == 0.0
+    nan = torch.full((4096,), float("nan"), device="cuda", dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+    assert c.entropy_estimate(nan, 1, 64, 0, 0, 40000).status == edgc.binding.ENONFINITE
+    # a group of buffers is one sample
+    parts = [big[:100_001], big[200_000:200_064], big[1_000_000:1_700_003]]
+    out = torch.zeros(edgc.binding.ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True)
+    counts = torch.zeros(65536, dtype=torch.int64, device="cuda")
+    c.entropy_estimate_async([to_dev(p) for p in parts], 1, 64, 3, 2, 65536, out, None, counts)
+    torch.cuda.synchronize()
+    got = edgc.EntropyResult.from_buffer(out.numpy().tobytes())
+    ref = orc.entropy(np.concatenate(parts), 1, 64, 3, 2, 65536)           # stride 1: every element, however chunked
+    assert (got.n_sampled, got.lo, got.hi) == (ref.n_sampled, ref.lo, ref.hi)
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
     c.close()
