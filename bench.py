@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--explicit-residual", action="store_true",
                     help="keep E = D - M^ in the residual buffer between steps (the decompress reads D and writes E) "
                          "instead of the default deferred subtraction")
+    ap.add_argument("--ent-strides", default="1000,100,10,1", help="cfg3_flat_1e9 only: the sampling strides to run")
+    ap.add_argument("--ent-bins", default="256,4096,65536", help="cfg3_flat_1e9 only: the bin counts to run")
+    ap.add_argument("--ent-dtypes", default="f32,bf16", help="cfg3_flat_1e9 only: the element types to run")
     ap.add_argument("--serial", action="store_true",
                     help="issue everything on ONE stream, also in the timed region: the run to put under "
                          "rocprofv3 --kernel-trace --stats, every kernel alone on the GPU")
@@ -479,9 +482,17 @@ def main() -> int:
     peaks = wl.qctx.measure_device_peaks(pa, pb, reps=10)
     del pa, pb
     device_peaks = dict(copy_gbs=round(peaks["copy_gbs"], 1), read_gbs=round(peaks["read_gbs"], 1),
+                        write_gbs=round(peaks["write_gbs"], 1),
                         mfma_bf16_tflops=round(peaks["mfma_bf16_tflops"], 1), bytes=peaks["bytes"],
-                        what="plain copy (read + written bytes), plain read, register-resident "
+                        what="plain copy (read + written bytes), plain read, plain fill, register-resident "
                              "32x32x16 bf16 MFMA loop; 10 launches each between one pair of events")
+    # each streaming pass against the plain kernel of its own traffic mix: the P-pass reads and writes
+    # (copy), the Q-pass only reads, the deferred decompress only writes
+    against = {"k_pass_p_deferred": "copy_gbs", "k_pass_p": "copy_gbs", "k_pass_q": "read_gbs",
+               "k_decompress": "write_gbs" if wl.deferred else "copy_gbs"}
+    for k, ref in against.items():
+        if k in m["kernels"] and m["kernels"][k].get("gbs"):
+            m["kernels"][k]["frac_of_measured_" + ref[:-4]] = round(m["kernels"][k]["gbs"] / peaks[ref], 4)
     roofline["frac_of_measured_copy"] = round(m["achieved"] / peaks["copy_gbs"], 4)
 
     cpu_baseline = None if args.no_cpu_baseline else cpu_baseline_for(wl, torch)

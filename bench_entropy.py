@@ -16,7 +16,9 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
     more are read once), `sample_gbs` = those reads x sample bytes / time."""
     from paper_2511_10333_amd.binding import ENTROPY_RESULT_BYTES, EntropyResult
     n, chunk, seed = 1_000_000_000, 64, 0
-    strides, bins_list = (1000, 100, 10, 1), (256, 4096, 65536)
+    strides = tuple(int(v) for v in args.ent_strides.split(","))
+    bins_list = tuple(int(v) for v in args.ent_bins.split(","))
+    dtypes = args.ent_dtypes.split(",")
     ctx = edgc.Context(0, max_bins=65536, max_rank=4, max_rows=64, max_cols=64)
     out = torch.empty(ENTROPY_RESULT_BYTES, dtype=torch.uint8, pin_memory=True)
     g = torch.Generator(device="cuda").manual_seed(3)
@@ -26,7 +28,7 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
     x32.mul_(torch.sign(sign))
     x32.mul_(torch.where(sign.abs() < 1e-3, 1e-1, 1e-3))               # 0.1 % outliers at 100 x the scale
     del sign
-    bufs = {"f32": x32, "bf16": x32.bfloat16()}
+    bufs = {k: v for k, v in (("f32", x32), ("bf16", x32.bfloat16() if "bf16" in dtypes else None)) if k in dtypes}
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     cells, headline = [], None
@@ -66,10 +68,11 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
                             sample_gbs=round(reads * sample_bytes / (ms * 1e-3) / 1e9, 1),
                             H_bits=round(res.H_bits, 6), kernels=kern)
                 cells.append(cell)
-                if dtype == "f32" and stride == 1 and bins == 4096:
+                if (dtype == "f32" and stride == 1 and bins == 4096) or headline is None:
                     headline = (cell, ms, ks, reps)
     cell, ms, ks, reps = headline
-    dom = max(("k_minmax", "k_hist"), key=lambda k: ks[k]["total_ms"])
+    dom = max((k for k in ("k_minmax", "k_hist", "k_wide_hist") if k in ks and ks[k]["launches"]),
+              key=lambda k: ks[k]["total_ms"])
     achieved = ks[dom]["bytes"] / (ks[dom]["total_ms"] * 1e-3) / 1e9
     pa = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
     pb = torch.empty_like(pa)
@@ -100,9 +103,9 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
         "metric": metric,
         "value": cell["gradient_gbs"], "unit": "GB/s", "n_gpus": 1, "steps": reps, "warmup": min(args.warmup, 3),
         "ms_per_step": cell["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": cell["dtype"], "data": "synthetic",
         "config": {"workload": "cfg3_flat_1e9", "what": "entropy estimate only; value = the 100 % / 4096-bin "
-                   "cell of the fp32 buffer", "elements": n, "chunk": chunk, "strides": list(strides),
+                   "cell of the fp32 buffer (the first cell run when that one is not among them)", "elements": n, "chunk": chunk, "strides": list(strides),
                    "bins": list(bins_list)},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "cells": cells,
         "device_peaks_measured": {k: (round(v, 1) if isinstance(v, float) else v) for k, v in peaks.items()},

@@ -313,15 +313,15 @@ int edgc_measure_rank_costs(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, u
                             edgc_rank_cost* costs_out, void* hip_stream);
 
 /* Measured ceilings of the device, for reading a kernel's throughput against:
- * what a plain streaming copy and a plain streaming read of `bytes` reach (the
- * passes of section 3 are bounded by HBM), and what a register-resident loop of
+ * what a plain streaming copy, a plain streaming read and a plain streaming
+ * write of `bytes` reach (the passes of section 3 are bounded by HBM), and what a register-resident loop of
  * the 32x32x16 bf16 MFMA that the passes issue reaches.  Not part of the method
  * and not a hot-path call.
  *
  * buf_a, buf_b: two distinct device buffers of `bytes` each (16-byte aligned,
  * bytes a multiple of 16 and at least 8 * compute units * 1 KiB); buf_a is only
  * read (its contents do not matter but should be initialised), buf_b is
- * overwritten.  Each of the three kernels runs once untimed and then reps
+ * overwritten.  Each of the four kernels runs once untimed and then reps
  * times between a pair of events; synchronises the stream.
  * Errors: EDGC_EINVAL for null or misaligned arguments, equal buffers, a size
  * below the minimum or reps == 0; EDGC_EHIP for a failed HIP call. */
@@ -329,7 +329,8 @@ typedef struct {
     double   copy_gbs;          /* (bytes read + bytes written) / time, 1e9 bytes per second */
     double   read_gbs;          /* bytes read / time                                         */
     double   mfma_bf16_tflops;  /* dense bf16 MFMA, fp32 accumulate, 1e12 flop per second    */
-    uint64_t bytes;             /* the size the two memory figures were taken on             */
+    uint64_t bytes;             /* the size the memory figures were taken on                 */
+    double   write_gbs;         /* bytes written / time (a plain fill of buf_b)              */
 } edgc_device_peaks;
 
 int edgc_measure_device_peaks(edgc_ctx* ctx, void* buf_a, void* buf_b, uint64_t bytes,

@@ -135,7 +135,7 @@ def load_library() -> C.CDLL:
 
 class _DevicePeaks(C.Structure):
     _fields_ = [("copy_gbs", C.c_double), ("read_gbs", C.c_double), ("mfma_bf16_tflops", C.c_double),
-                ("bytes", C.c_uint64)]
+                ("bytes", C.c_uint64), ("write_gbs", C.c_double)]
 
 
 class _Tensor(C.Structure):
@@ -488,7 +488,8 @@ class Context:
                                                C.byref(out), _stream_handle(stream))
         self._check(rc, "edgc_measure_device_peaks")
         return {"copy_gbs": out.copy_gbs, "read_gbs": out.read_gbs,
-                "mfma_bf16_tflops": out.mfma_bf16_tflops, "bytes": int(out.bytes)}
+                "mfma_bf16_tflops": out.mfma_bf16_tflops, "bytes": int(out.bytes),
+                "write_gbs": out.write_gbs}
 
     # -- batched calls -----------------------------------------------------
     def reserve_batch(self, shapes: Sequence[Sequence[int]]) -> None:

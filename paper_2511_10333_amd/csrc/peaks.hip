@@ -1,8 +1,8 @@
 // Measured ceilings of the device at hand, for reading the roofline figures against: what a plain
-// streaming copy, a plain streaming read and a register-resident bf16 MFMA loop reach.  None of
-// this is part of the method; the kernels of the hot path (Sec. II-B, IV-B, IV-C) are bounded by
-// HBM, and these three numbers say how much of the published peaks a kernel with no other work
-// gets on this device.
+// streaming copy, a plain streaming read, a plain streaming write and a register-resident bf16 MFMA
+// loop reach.  None of this is part of the method; the kernels of the hot path (Sec. II-B, IV-B,
+// IV-C) are bounded by HBM, and these numbers say how much of the published peaks a kernel with no
+// other work gets on this device.
 #include "edgc_internal.h"
 
 namespace edgc {
@@ -24,6 +24,14 @@ __global__ __launch_bounds__(kPeakThreads) void k_peak_copy(const float4* __rest
     const size_t span = static_cast<size_t>(gridDim.x) * kPeakThreads;
     for (size_t i = static_cast<size_t>(blockIdx.x) * kPeakThreads + threadIdx.x; i < n4; i += span)
         dst[i] = src[i];
+}
+
+// dst[i] = a constant over n4 16-byte items, grid-stride
+__global__ __launch_bounds__(kPeakThreads) void k_peak_fill(float4* __restrict__ dst, size_t n4, float value)
+{
+    const float4 v = make_float4(value, value, value, value);
+    const size_t span = static_cast<size_t>(gridDim.x) * kPeakThreads;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * kPeakThreads + threadIdx.x; i < n4; i += span) dst[i] = v;
 }
 
 // reads n4 16-byte items, one contiguous range per block with kReadUnroll loads per thread in flight,
@@ -112,8 +120,8 @@ extern "C" int edgc_measure_device_peaks(edgc_ctx* ctx, void* buf_a, void* buf_b
     };
     for (auto& e : ev)
         if (!hip_ok(hipEventCreate(&e), "hipEventCreate")) break;
-    double ms[3] = {0.0, 0.0, 0.0};
-    for (int which = 0; rc == EDGC_OK && which < 3; ++which) {
+    double ms[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int which = 0; rc == EDGC_OK && which < 4; ++which) {
         // launch 0 is untimed
         for (uint32_t rep = 0; rc == EDGC_OK && rep <= reps; ++rep) {
             if (rep == 1 && !hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) break;
@@ -121,8 +129,10 @@ extern "C" int edgc_measure_device_peaks(edgc_ctx* ctx, void* buf_a, void* buf_b
                 hipLaunchKernelGGL(k_peak_copy, dim3(blocks_copy), dim3(kPeakThreads), 0, st, a, b4, n4);
             else if (which == 1)
                 hipLaunchKernelGGL(k_peak_read, dim3(blocks_read), dim3(kPeakThreads), 0, st, a, sink, n4);
-            else
+            else if (which == 2)
                 hipLaunchKernelGGL(k_peak_mfma, dim3(blocks_mfma), dim3(kPeakThreads), 0, st, sink, kMfmaIters);
+            else
+                hipLaunchKernelGGL(k_peak_fill, dim3(blocks_copy), dim3(kPeakThreads), 0, st, b4, n4, 1.0f);
             hip_ok(hipGetLastError(), "launch of a peak kernel");
         }
         if (rc != EDGC_OK) break;
@@ -138,6 +148,7 @@ extern "C" int edgc_measure_device_peaks(edgc_ctx* ctx, void* buf_a, void* buf_b
     const double b = static_cast<double>(bytes);
     out->copy_gbs = 2.0 * b / (ms[0] * 1e-3) * 1e-9;
     out->read_gbs = b / (ms[1] * 1e-3) * 1e-9;
+    out->write_gbs = b / (ms[3] * 1e-3) * 1e-9;
     // waves x rounds x 4 chains x (32 x 32 x 16 multiply-adds = 32768 flop)
     const double flop = static_cast<double>(blocks_mfma) * (kPeakThreads / 64) * kMfmaIters * 4.0 * 32768.0;
     out->mfma_bf16_tflops = flop / (ms[2] * 1e-3) * 1e-12;

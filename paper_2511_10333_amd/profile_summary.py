@@ -11,6 +11,10 @@ calibration run (a plain device copy of 1 GiB per launch) gives the bytes one co
 for.  The file ends with one `traffic_bytes_per_launch <kernel> <bytes>` line per kernel, which
 bench.py reads for `roofline.traffic`.
 `kernels`: DIR is the -d folder of a `rocprofv3 --kernel-trace --stats` run.
+`counters`: DIR is the -d folder of any `rocprofv3 --pmc` run: mean of every counter per launch and kernel.
+`cells`: the JSON line of `bench.py --workload cfg3_flat_1e9` as a table of its cells.
+`bench`: the JSON line of a `bench.py` run, the headline figures and the other workloads as tables.
+`rankcosts`: the JSON objects of `python -m paper_2511_10333_amd.calibrate` runs (one per line) as tables.
 Kernels are named as bench.py names them (template arguments dropped, the whole-tile and
 narrow forms of a pass under the pass's name).
 """
@@ -29,7 +33,7 @@ ALIASES = {"k_pass_p_deferred_full": "k_pass_p_deferred", "k_pass_p_deferred_nar
 
 
 def bench_name(kernel: str) -> str:
-    k = re.sub(r"^void\s+", "", kernel)
+    k = re.sub(r"^void\s+", "", kernel).replace("(anonymous namespace)::", "")
     k = re.sub(r"\(.*$", "", k)
     full = k.replace("edgc::", "")
     base = re.sub(r"<.*$", "", full)
@@ -127,6 +131,159 @@ def cmd_kernels(a) -> int:
     return 0
 
 
+def cmd_counters(a) -> int:
+    rows = list(csv.DictReader(open(find_csv(a.dir, "counter_collection.csv"))))
+    val = collections.defaultdict(lambda: collections.defaultdict(dict))     # kernel -> counter -> dispatch -> value
+    names = []
+    for r in rows:
+        full = bench_name(r["Kernel_Name"])[1]
+        if "k_" not in full:
+            continue
+        d = val[full][r["Counter_Name"]]
+        d[r["Dispatch_Id"]] = d.get(r["Dispatch_Id"], 0.0) + float(r["Counter_Value"])
+        if r["Counter_Name"] not in names:
+            names.append(r["Counter_Name"])
+    out = ["# %s\n" % a.title, "Command (after `cd /tmp && export TMPDIR=/tmp`, from the repository root):\n", "```"]
+    out.extend(a.command)
+    out.extend(["```\n",
+                "Mean per launch over the launches that did work; `idle` counts launches whose first counter reads under "
+                "1 % of the kernel's largest (a kernel queued behind the overflow gate of the one-read estimate returns at "
+                "once).\n",
+                "| kernel | launches | idle | " + " | ".join(names) + " |", "|---|---|---|" + "---|" * len(names)])
+    def weight(k):
+        return -max(val[k][names[0]].values() or [0.0])
+    for k in sorted(val, key=weight):
+        first = val[k][names[0]]
+        top = max(first.values() or [0.0])
+        live = [d for d, v in first.items() if v >= 0.01 * top] or list(first)
+        cells = []
+        for c in names:
+            vs = [val[k][c].get(d, 0.0) for d in live]
+            cells.append("%.4g" % (sum(vs) / len(vs)))
+        out.append("| `%s` | %d | %d | %s |" % (k, len(live), len(first) - len(live), " | ".join(cells)))
+    if a.note:
+        out.append("")
+        out.extend(a.note)
+    open(a.out, "w").write("\n".join(out) + "\n")
+    print("\n".join(out[-len(val) - 3 - len(a.note):]))
+    return 0
+
+
+def last_json_line(path: str):
+    import json
+    lines = [l for l in open(path) if l.startswith("{")]
+    if not lines:
+        sys.exit("no JSON line in %s" % path)
+    return json.loads(lines[-1])
+
+
+def cmd_cells(a) -> int:
+    d = last_json_line(a.json)
+    out = ["# %s\n" % a.title, "Command (from the repository root):\n", "```"]
+    out.extend(a.command)
+    out.extend(["```\n",
+                "`ms`: one whole estimate, from a pair of events around back-to-back estimates.  `reads`: how often the "
+                "estimate's kernels read the sample.  Kernel columns: microseconds per launch from a second pass with every "
+                "launch between its own events (a kernel that only checks the overflow gate and returns reads about 1.6).\n",
+                "| dtype | stride | bins | sampled | ms | reads | sample GB/s | buffer GB/s | kernels (us) |",
+                "|---|---|---|---|---|---|---|---|---|"])
+    for c in d["cells"]:
+        ks = ", ".join("`%s` %.1f" % (k, v["avg_us"]) for k, v in c["kernels"].items() if v["avg_us"] >= 4.0)
+        out.append("| %s | %d | %d | %d | %.4f | %d | %.0f | %.0f | %s |" % (
+            c["dtype"], c["stride"], c["bins"], c["n_sampled"], c["ms"], c["reads_of_sample"], c["sample_gbs"],
+            c["gradient_gbs"], ks))
+    pk = d.get("device_peaks_measured") or {}
+    out.append("")
+    out.append("Measured on the same device in the same run: plain copy %s GB/s, plain read %s GB/s." % (
+        pk.get("copy_gbs"), pk.get("read_gbs")))
+    if d.get("roofline"):
+        out.append("Roofline object of the line: `%s`." % d["roofline"])
+    if d.get("cpu_baseline"):
+        out.append("CPU baseline of the line: `%s`." % d["cpu_baseline"])
+    if a.note:
+        out.append("")
+        out.extend(a.note)
+    open(a.out, "w").write("\n".join(out) + "\n")
+    print("wrote", a.out, len(d["cells"]), "cells")
+    return 0
+
+
+def cmd_bench(a) -> int:
+    import json
+    d = last_json_line(a.json)
+    out = ["# %s\n" % a.title, "Command (from the repository root):\n", "```"]
+    out.extend(a.command)
+    out.extend(["```\n"])
+    head = {k: d[k] for k in ("metric", "value", "unit", "ms_per_step", "steps", "warmup", "dtype", "arithmetic") if k in d}
+    out.append("Headline: `%s`\n" % json.dumps(head))
+    out.append("Workload: `%s`\n" % json.dumps(d.get("config")))
+    out.append("Roofline: `%s`\n" % json.dumps(d.get("roofline")))
+    out.append("CPU baseline: `%s`\n" % json.dumps(d.get("cpu_baseline")))
+    out.append("Measured device ceilings: `%s`\n" % json.dumps(d.get("device_peaks_measured")))
+    if d.get("kernels"):
+        out.extend(["| kernel | launches per step | us per launch | GB/s (algorithmic bytes) | TFLOP/s | of the plain kernel of its traffic mix |",
+                    "|---|---|---|---|---|---|"])
+        for k, v in d["kernels"].items():
+            frac = next((("%s %.3f" % (kk[len("frac_of_measured_"):], vv)) for kk, vv in v.items()
+                         if kk.startswith("frac_of_measured_")), "")
+            out.append("| `%s` | %s | %.2f | %s | %s | %s |" % (k, v.get("launches_per_step"), v["avg_us"], v.get("gbs"),
+                                                               v.get("tflops"), frac))
+        out.append("")
+    if d.get("mfma"):
+        out.append("MFMA: `%s`\n" % json.dumps(d["mfma"]))
+    if d.get("other_workloads"):
+        out.extend(["| workload | rank | ms per step | gradient GB/s | dominant kernel | its GB/s | of 8 TB/s |", "|---|---|---|---|---|---|---|"])
+        for o in d["other_workloads"]:
+            out.append("| `%s` | %s | %s | %s | `%s` | %s | %s |" % (
+                o.get("workload"), o.get("rank"), o.get("ms_per_step"), o.get("gradient_gbs"), o.get("dominant_kernel"),
+                o.get("dominant_gbs"), o.get("dominant_frac_of_hbm_peak")))
+        out.append("")
+    if d.get("dynamic"):
+        dy = dict(d["dynamic"])
+        out.append("Dynamic-rate run: `%s`\n" % json.dumps(dy))
+    if a.note:
+        out.extend(a.note)
+    open(a.out, "w").write("\n".join(out) + "\n")
+    print("wrote", a.out)
+    return 0
+
+
+def cmd_rankcosts(a) -> int:
+    import json
+    objs = [json.loads(l) for l in open(a.json) if l.startswith("{")]
+    out = ["# %s\n" % a.title, "Commands (each prints one JSON object; the tables below are those numbers):\n", "```"]
+    out.extend(a.command)
+    out.extend(["```\n",
+                "Times are sums over the four matrices of one transformer block (QKV, attention projection, MLP up, MLP down), "
+                "one matrix at a time on one stream, each call between HIP events, mean over the rounds.  D_compressed = "
+                "(m + n) r 4 bytes summed over the matrices; T_com = T_compress + T_decompress + D_compressed / B "
+                "(Sec. IV-D-1).\n"])
+    for d in objs:
+        out.append("## hidden %d, %s gradients, %s residual: D_original = %.1f MB\n" % (
+            d["hidden"], d["dtype"], d["residual"], d["bytes_original"] / 1e6))
+        bws = d["bandwidths"]
+        out.append("| rank | T_compress us | T_decompress us | D_compressed MB | " +
+                   " | ".join("T_com @%g Gbit/s us" % b["gbps"] for b in bws) + " |")
+        out.append("|---|---|---|---|" + "---|" * len(bws))
+        for i, c in enumerate(d["costs"]):
+            out.append("| %d | %.1f | %.1f | %.3f | %s |" % (
+                c["rank"], c["t_compress_us"], c["t_decompress_us"], c["bytes_compressed"] / 1e6,
+                " | ".join("%.0f" % b["t_com_us"][i] for b in bws)))
+        out.append("")
+        out.append("| bandwidth Gbit/s | D_original/B us | r_max | r_min | eta us per rank | MAPE % |")
+        out.append("|---|---|---|---|---|---|")
+        for b in bws:
+            out.append("| %g | %.0f | %d | %d | %s | %s |" % (
+                b["gbps"], b["t_uncompressed_us"], b["r_max"], b["r_min"],
+                "-" if b["eta_us"] is None else "%.2f" % b["eta_us"],
+                "-" if b["mape_percent"] is None else "%.1f" % b["mape_percent"]))
+        out.append("")
+    out.extend(a.note)
+    open(a.out, "w").write("\n".join(out) + "\n")
+    print("wrote", a.out)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -142,8 +299,21 @@ def main() -> int:
     k.add_argument("--out", required=True)
     k.add_argument("--command", action="append", default=[])
     k.add_argument("--note", action="append", default=[])
+    c = sub.add_parser("counters")
+    c.add_argument("--dir", required=True)
+    for name in ("cells", "bench", "rankcosts"):
+        j = sub.add_parser(name)
+        j.add_argument("--json", required=True, help="file holding the JSON line bench.py printed")
+        for q in (j,):
+            pass
+    for q in (c, sub.choices["cells"], sub.choices["bench"], sub.choices["rankcosts"]):
+        q.add_argument("--title", required=True)
+        q.add_argument("--out", required=True)
+        q.add_argument("--command", action="append", default=[])
+        q.add_argument("--note", action="append", default=[])
     a = ap.parse_args()
-    return cmd_traffic(a) if a.cmd == "traffic" else cmd_kernels(a)
+    return {"traffic": cmd_traffic, "kernels": cmd_kernels, "counters": cmd_counters, "cells": cmd_cells,
+            "bench": cmd_bench, "rankcosts": cmd_rankcosts}[a.cmd](a)
 
 
 if __name__ == "__main__":

@@ -302,6 +302,7 @@ def test_measure_device_peaks_copies_and_reports_physical_figures():
     assert torch.equal(a[sink_floats:], b[sink_floats:])
     assert pk["bytes"] == a.numel() * 4
     assert 500.0 < pk["read_gbs"] < 20000.0 and 500.0 < pk["copy_gbs"] < 20000.0
+    assert 500.0 < pk["write_gbs"] < 20000.0
     assert 100.0 < pk["mfma_bf16_tflops"] < 2600.0
     with pytest.raises(edgc.EdgcError):
         c.measure_device_peaks(a, a, reps=3)
