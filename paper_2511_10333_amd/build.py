@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libedgc.so")
-SOURCES = ["edgc_api.hip", "entropy.hip", "compress.hip", "pass_p_full.hip", "decompress_full.hip", "peaks.hip", "rank_select.cpp", "dac_host.cpp"]
+SOURCES = ["edgc_api.hip", "entropy.hip", "compress.hip", "pass_p_full.hip", "decompress_full.hip", "pass_q_full.hip", "peaks.hip", "rank_select.cpp", "dac_host.cpp"]
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -2261,9 +2261,22 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
 template <int NP, int RT, int NT>
 static int run_pass_q(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStream_t st)
 {
-    constexpr uint32_t RP = RT * 32, W4 = 4 * 32 * NT;
+    constexpr uint32_t RP = RT * 32;
     constexpr size_t lds = static_cast<size_t>(2) * RP * (NP * 128 + 16);
-    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_q ? ctx->tune_q : 2u);
+    constexpr edgc_dtype DT = (NP == 1) ? EDGC_BF16 : EDGC_F32;
+    // whole-tile groups: the pipelined kernel (pass_q_full.hip), 4 or 8 waves of 64 columns per block
+    // (measured per launch, general kernel / 4 waves / 8 waves: hidden-5120 bf16 block at rank 128: 144 / 142 /
+    // 132 us, at rank 64: 128 / 134 / 124, at rank 32: 128 / 132 / -; hidden-4096 fp32 block at rank 64:
+    // 96 / 86 / 90; hidden-2048 fp32 block at rank 16: 21.4 / 20.5 / -)
+    uint32_t qwaves = 0;
+    if (NT == 2 && ctx->tune_qfull != 0) {
+        const uint32_t want = ctx->tune_qfull > 0 ? (ctx->tune_qfull == 8 ? 8u : 4u)
+                                                  : (NP == 1 ? (RT >= 2 ? 8u : 0u) : 4u);
+        if (want && pass_q_full_applies(g, DT, RT, want)) qwaves = want;
+    }
+    const uint32_t W4 = (qwaves ? qwaves : 4u) * 32 * NT;
+    const uint32_t per_cu = ctx->tune_q ? ctx->tune_q : (qwaves == 8 ? 1u : 2u);
+    const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * per_cu;
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
     bool vec = true;
@@ -2287,7 +2300,10 @@ static int run_pass_q(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStre
         bytes += 4.0 * t.m * t.n;
         flops += 2.0 * t.m * t.n * g.r;
     }
-    if (vec) {
+    if (qwaves) {
+        ProfScope prof_scope_(ctx, st, KID_PASS_Q, bytes, flops);
+        EDGC_HIP_TRY(ctx, launch_pass_q_full(g, DT, RT, blocks, qwaves, st));
+    } else if (vec) {
         auto kern = &k_pass_q<NP, RT, NT, true>;
         EDGC_LAUNCH(ctx, st, KID_PASS_Q, bytes, flops, kern<<<blocks, 256, lds, st>>>(g));
     } else {

@@ -136,6 +136,8 @@ struct edgc_ctx {
                             // the whole-tile kernel with that many waves per block at every rank
     int tune_full = -1;     // P-pass of whole-tile groups: -1 built-in choice; 0 the general kernels;
                             // 1 / 2 the whole-tile kernel with the Q rows requested early / late
+    int tune_qfull = -1;    // Q-pass of whole-tile groups: -1 built-in choice; 0 the general kernel; 4 / 8 the
+                            // pipelined kernel with that many waves per block
     int tune_pattern = 1;   // entropy estimate: 1 one read into 16-bit counters per block where that applies
                             // (bf16 samples, fp32 on more than 16384 bins); 0 the plain kernels only; 3 as 1,
                             // and every such estimate reports a counter overflow (tests of the redo path)
@@ -258,5 +260,10 @@ bool decompress_full_applies(const Group& g, edgc_dtype dt, uint32_t waves);
 hipError_t launch_decompress_full(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t blocks, uint32_t waves,
                                   hipStream_t st);
 hipError_t prepare_decompress_full();
+// pass_q_full.hip: the Q-pass of groups of whole tiles, the next stage's rows requested while the
+// current stage is multiplied
+bool pass_q_full_applies(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t waves);
+hipError_t launch_pass_q_full(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t blocks, uint32_t waves,
+                              hipStream_t st);
 
 }  // namespace edgc

@@ -121,7 +121,10 @@ extern "C" int edgc_measure_device_peaks(edgc_ctx* ctx, void* buf_a, void* buf_b
     for (auto& e : ev)
         if (!hip_ok(hipEventCreate(&e), "hipEventCreate")) break;
     double ms[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int which = 0; rc == EDGC_OK && which < 4; ++which) {
+    // the fill goes first: the buffer ends up holding the copy (behind the sinks of the last two kernels)
+    const int order[4] = {3, 0, 1, 2};
+    for (int oi = 0; rc == EDGC_OK && oi < 4; ++oi) {
+        const int which = order[oi];
         // launch 0 is untimed
         for (uint32_t rep = 0; rc == EDGC_OK && rep <= reps; ++rep) {
             if (rep == 1 && !hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) break;
