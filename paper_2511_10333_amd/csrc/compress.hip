@@ -733,8 +733,8 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
 // and the bf16 operand copy Pt[plane][c][i] (i contiguous, rows padded to a
 // multiple of 64) that the Q-pass reads as MFMA B-fragments.
 // ---------------------------------------------------------------------------
-template <int T16, int NP>
-__global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
+template <int T16, int NP, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void k_apply(const Group grp, uint32_t RP)
 {
     const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
     float* __restrict__ P = ta.P;
@@ -744,26 +744,29 @@ __global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
     constexpr int CW = 16 * T16;
     constexpr int LD = CW + 4;             // floats; 16 rows x 4 columns per read: 2-way at worst
     constexpr int NTILE = T16 * (T16 + 1) / 2;       // upper-triangle 16x16 tiles of R^-1
-    __shared__ __attribute__((aligned(16))) float Ps[64 * LD];
+    constexpr int ROWS = 16 * WAVES, NTH = 64 * WAVES;
+    __shared__ __attribute__((aligned(16))) float Ps[ROWS * LD];
     __shared__ double Rs[NTILE * 256];               // tile (tk <= tc), [k][c] row-major
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t row0 = (blockIdx.x - ta.first) * 64;
+    const uint32_t row0 = (blockIdx.x - ta.first) * ROWS;
     // R^-1 goes to LDS once per block (all loads in flight together): the multiply below then
     // runs without a round trip to L2 per k step
     {
-        const uint32_t kl = tid >> 4, cc = tid & 15;
-        int t = 0;
+        const uint32_t e = tid & 255, kl = e >> 4, cc = e & 15;
 #pragma unroll
-        for (int tk = 0; tk < T16; ++tk)
-#pragma unroll
-            for (int tc = tk; tc < T16; ++tc, ++t) {
+        for (int t0 = 0; t0 < NTILE; t0 += NTH / 256) {
+            const int t = t0 + (tid >> 8);
+            if (t < NTILE) {
+                int tk, tc;
+                tri_tile(t, T16, tk, tc);
                 const uint32_t k = 16 * tk + kl, c = 16 * tc + cc;
-                Rs[t * 256 + tid] = (k < r && c < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
+                Rs[t * 256 + e] = (k < r && c < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
             }
+        }
     }
 #pragma unroll
     for (int it = 0; it < T16; ++it) {
-        const int idx = tid + 256 * it;
+        const int idx = tid + NTH * it;
         const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
         const uint32_t row = row0 + i;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -812,7 +815,7 @@ __global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < T16; ++it) {
-        const int idx = tid + 256 * it;
+        const int idx = tid + NTH * it;
         const int i = idx / (CW / 4), c4 = (idx % (CW / 4)) * 4;
         const uint32_t row = row0 + i;
         if (row < m) {
@@ -827,9 +830,12 @@ __global__ __launch_bounds__(256) void k_apply(const Group grp, uint32_t RP)
             }
         }
     }
-    // transposed operand copy: 8 consecutive rows of one column per 16-byte store
-    for (uint32_t idx = tid; idx < RP * 8; idx += 256) {
-        const uint32_t cc = idx / 8, q = idx % 8;
+    // transposed operand copy: 8 consecutive rows of one column per 16-byte store (the copy's rows are
+    // padded to a multiple of 64, which a block of 128 rows may reach past)
+    constexpr uint32_t SEG = ROWS / 8;
+    for (uint32_t idx = tid; idx < RP * SEG; idx += NTH) {
+        const uint32_t cc = idx / SEG, q = idx % SEG;
+        if (row0 + 8 * q >= m_pad) continue;
         bf16x8 w[NP];
         float v8[8];
 #pragma unroll
@@ -2231,13 +2237,15 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
                 k_chol<<<g.count, kCholThreads, chol_lds, st>>>(g, t16));
     EDGC_HIP_TRY(ctx, hipGetLastError());
 
-    // P^ = P R^-1 and its transposed bf16 copy
+    // P^ = P R^-1 and its transposed bf16 copy.  Above rank 64 the 72 KB of R^-1 tiles leave room for one
+    // block per CU: blocks of 128 rows then keep a group's blocks within one round over the CUs
+    const uint32_t apply_rows = (t16 == 8 && ctx->tune_apply != 4) ? 128u : 64u;
     blocks = 0;
     bytes = flops = 0.0;
     for (uint32_t i = 0; i < g.count; ++i) {
         TensorArgs& t = g.t[i];
         t.first = blocks;
-        blocks += t.m_pad / 64;
+        blocks += cdiv(t.m_pad, apply_rows);
         const double mr = static_cast<double>(t.m) * r;
         bytes += 8.0 * mr + 2.0 * NP * RP * t.m_pad;
         flops += mr * r;
@@ -2245,10 +2253,13 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
     {
         ProfScope prof_scope_(ctx, st, KID_APPLY, bytes, flops);
         switch (t16) {
-        case 1: k_apply<1, NP><<<blocks, 256, 0, st>>>(g, RP); break;
-        case 2: k_apply<2, NP><<<blocks, 256, 0, st>>>(g, RP); break;
-        case 4: k_apply<4, NP><<<blocks, 256, 0, st>>>(g, RP); break;
-        default: k_apply<8, NP><<<blocks, 256, 0, st>>>(g, RP); break;
+        case 1: k_apply<1, NP, 4><<<blocks, 256, 0, st>>>(g, RP); break;
+        case 2: k_apply<2, NP, 4><<<blocks, 256, 0, st>>>(g, RP); break;
+        case 4: k_apply<4, NP, 4><<<blocks, 256, 0, st>>>(g, RP); break;
+        default:
+            if (apply_rows == 128) k_apply<8, NP, 8><<<blocks, 512, 0, st>>>(g, RP);
+            else k_apply<8, NP, 4><<<blocks, 256, 0, st>>>(g, RP);
+            break;
         }
     }
     EDGC_HIP_TRY(ctx, hipGetLastError());
