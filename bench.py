@@ -102,6 +102,7 @@ class Workload:
         self.bf16 = w["dtype"] == "bf16"
         self.mats = mats if mats is not None else gen.workload_matrices(name)
         self.serial = args.serial
+        self.skip_estimate = False    # only for the side measurement of what the estimate costs a step
         self.deferred = not args.explicit_residual
         self.NBUF = 3     # entropy results are read two steps after they are enqueued: the GPU never waits for the host
         n_groups = max(1, min(args.batch, len(self.mats)))
@@ -215,11 +216,13 @@ class Workload:
 
     def step(self):
         t = self.t
-        self.rank_rule(t)
+        if not self.skip_estimate:
+            self.rank_rule(t)
         r = self.cur_rank
         flats = self.flats_ref if t < self.window else self.flats
-        self.ectx.entropy_estimate_async(flats, self.w["stride"], self.w["chunk"], self.w["seed"], t, self.w["bins"],
-                                         self.ent[t % self.NBUF], stream=self.estream)
+        if not self.skip_estimate:
+            self.ectx.entropy_estimate_async(flats, self.w["stride"], self.w["chunk"], self.w["seed"], t, self.w["bins"],
+                                             self.ent[t % self.NBUF], stream=self.estream)
         for g in self.groups if r else []:                  # rank 0: warm-up, the gradients go uncompressed
             first = g["tensors"][0].residual_is_zero
             explicit_in = g.pop("materialized", False)      # after a rank change the buffer holds E itself
@@ -530,6 +533,27 @@ def main() -> int:
             del e
             torch.cuda.empty_cache()
         line["other_workloads"] = others
+        # What the separate entropy estimate costs a step: the headline workload once more with the estimate
+        # left out (NOT a valid step: the bound on what fusing the estimate into the P-pass could save)
+        e = Workload(torch, edgc, gen, HEADLINE[0], HEADLINE[1], args, mats=mats_keep)
+        e.skip_estimate = True
+        for _ in range(args.warmup):
+            e.step()
+        torch.cuda.synchronize()
+        tq0 = time.perf_counter()
+        for _ in range(args.steps):
+            e.step()
+        torch.cuda.synchronize()
+        ms_wo = (time.perf_counter() - tq0) * 1e3 / args.steps
+        e.close()
+        del e
+        torch.cuda.empty_cache()
+        line["entropy_estimate_cost"] = dict(
+            ms_per_step=round(m["ms_per_step"], 4), ms_per_step_without_estimate=round(ms_wo, 4),
+            difference_us=round((m["ms_per_step"] - ms_wo) * 1e3, 1),
+            what="the headline workload again with the estimate's launches (and the rank rule's host call) left out: "
+                 "what a step pays for the separate estimate (it runs on a stream of its own beside the passes), i.e. "
+                 "the most a fused estimate could save")
         del mats_keep
         line["dynamic"] = dynamic_run(torch, edgc, gen, args)
     line["wall_seconds"] = round(time.perf_counter() - t_setup, 1)

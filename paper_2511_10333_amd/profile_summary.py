@@ -29,7 +29,7 @@ import re
 import sys
 
 ALIASES = {"k_pass_p_deferred_full": "k_pass_p_deferred", "k_pass_p_deferred_narrow": "k_pass_p_deferred",
-           "k_decompress_full": "k_decompress"}
+           "k_decompress_full": "k_decompress", "k_pass_q_full": "k_pass_q"}
 
 
 def bench_name(kernel: str) -> str:
