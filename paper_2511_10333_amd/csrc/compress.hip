@@ -2095,10 +2095,15 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     // hidden-5120 block)
     // groups of whole tiles with a residual to subtract: the kernel without edge paths
     constexpr edgc_dtype DT = (NP == 1) ? EDGC_BF16 : EDGC_F32;
-    const bool use_full = with_grad && ctx->tune_full != 0 && pass_p_full_applies(g, DT, RT);
+    // eight waves per block above rank 64 (hidden-5120 bf16 block, per launch, four / eight waves: rank 128
+    // 327 / 307 us; rank 64 294 / 309 us; hidden-4096 fp32 block at rank 64 233 / 243 us)
+    const bool want8 = ctx->tune_pwaves == 8 || (ctx->tune_pwaves < 0 && RT == 4);
+    const uint32_t pwaves = (want8 && pass_p_full_applies(g, DT, RT, 8)) ? 8u : 4u;
+    const bool use_full = with_grad && ctx->tune_full != 0 && pass_p_full_applies(g, DT, RT, pwaves);
     const bool use_narrow = with_grad && g.defer && RT == 4;
     const bool use_wide = with_grad && RT <= 2 && (g.defer || NP == 1);
-    const uint32_t per_cu = (use_narrow && !use_full) ? 2u : 4u;
+    const uint32_t per_cu = (use_narrow && !use_full) ? 2u : (use_full && pwaves == 8 ? 2u : 4u);
+    const uint32_t rows_per_block = use_full ? 32u * pwaves : 128u;
     const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * (ctx->tune_p ? ctx->tune_p : per_cu);
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
@@ -2107,7 +2112,7 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     double bytes = 0.0, flops = 0.0;
     for (uint32_t i = 0; i < g.count; ++i) {
         TensorArgs& t = g.t[i];
-        const uint32_t RB = cdiv(t.m, 128), ksteps = cdiv(t.n, BK);
+        const uint32_t RB = cdiv(t.m, rows_per_block), ksteps = cdiv(t.n, BK);
         uint32_t S = std::max(1u, std::min(ksteps, tgt[i] / RB));
         const uint64_t lim = cap[i].part_elems / (static_cast<uint64_t>(t.m) * RP);
         if (lim == 0) return fail(ctx, EDGC_EINVAL, "partial-factor scratch too small for this shape");
@@ -2133,7 +2138,7 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     if (use_full) {
         const bool qlate = ctx->tune_full == 2;
         ProfScope prof_scope_(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops);
-        EDGC_HIP_TRY(ctx, launch_pass_p_full(g, DT, RT, blocks, qlate, st));
+        EDGC_HIP_TRY(ctx, launch_pass_p_full(g, DT, RT, blocks, qlate, pwaves, st));
         return EDGC_OK;
     }
     if (use_narrow || use_wide) {

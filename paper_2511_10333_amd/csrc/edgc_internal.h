@@ -136,6 +136,7 @@ struct edgc_ctx {
                             // the whole-tile kernel with that many waves per block at every rank
     int tune_full = -1;     // P-pass of whole-tile groups: -1 built-in choice; 0 the general kernels;
                             // 1 / 2 the whole-tile kernel with the Q rows requested early / late
+    int tune_pwaves = -1;   // waves per block of that kernel: -1 built-in choice (8 above rank 64), 4 or 8
     int tune_qfull = -1;    // Q-pass of whole-tile groups: -1 built-in choice; 0 the general kernel; 4 / 8 the
                             // pipelined kernel with that many waves per block
     int tune_apply = -1;    // k_apply above rank 64: 4 keeps four waves (64 rows) per block
@@ -252,9 +253,9 @@ int prepare_entropy_kernels(edgc_ctx* ctx);
 size_t compress_part_elems(uint64_t max_rows, uint64_t max_cols, uint32_t max_rank, int num_cu);
 
 // the P-pass of groups made of whole tiles only (pass_p_full.hip)
-bool pass_p_full_applies(const Group& g, edgc_dtype dt, int rank_tiles);
+bool pass_p_full_applies(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t waves);
 hipError_t launch_pass_p_full(const Group& g, edgc_dtype dt, int rank_tiles, uint32_t blocks, bool qlate,
-                              hipStream_t st);
+                              uint32_t waves, hipStream_t st);
 hipError_t prepare_pass_p_full();
 // the write-only reconstruction of groups made of whole tiles only (decompress_full.hip)
 bool decompress_full_applies(const Group& g, edgc_dtype dt, uint32_t waves);

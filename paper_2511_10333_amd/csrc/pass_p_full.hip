@@ -15,14 +15,16 @@
 
 namespace edgc {
 
-template <int NP, int RT>
+template <int NP, int RT, int WAVES>
 constexpr size_t pass_p_full_lds()
 {
-    return static_cast<size_t>(64) * (NP * RT * 32 * 2 + 16) + static_cast<size_t>(RT * 32 + 128) * (NP * 128 + 16);
+    return static_cast<size_t>(64) * (NP * RT * 32 * 2 + 16) + static_cast<size_t>(RT * 32 + 32 * WAVES) * (NP * 128 + 16);
 }
 
-template <int NP, int RT, bool STREAM, bool QLATE>
-__global__ __launch_bounds__(256, 2) void k_pass_p_deferred_full(const Group grp)
+// WAVES x 32 rows per block share the staged Q tiles (two LDS layouts per stage): eight waves halve that
+// staging work per row.
+template <int NP, int RT, bool STREAM, bool QLATE, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void k_pass_p_deferred_full(const Group grp)
 {
     const TensorArgs& ta = grp.t[locate(grp, blockIdx.x)];
     using GT = typename GradElem<NP>::type;
@@ -39,18 +41,20 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_full(const Group grp
     constexpr int KT = RT * 2, RP = RT * 32;
     constexpr int ROWQ = NP * RP * 2 + 16;            // LDS bytes per Q row, [column][rank]
     constexpr int ROWB = NP * 128 + 16;               // LDS bytes per row of 64 columns
-    constexpr int PQ = 32 * (RP / 4) / 256;           // Q-stage items per thread: 2 rows x 4 ranks each
+    constexpr int NTH = 64 * WAVES;
+    static_assert(32 * (RP / 4) % NTH == 0, "the Q stage divides evenly among the threads");
+    constexpr int PQ = 32 * (RP / 4) / NTH;           // Q-stage items per thread: 2 rows x 4 ranks each
     extern __shared__ __attribute__((aligned(16))) unsigned char plds[];
     unsigned char* ldsQ = plds;                       // 64 x ROWQ
     unsigned char* ldsT = ldsQ + 64 * ROWQ;           // RP x ROWB: Q^T
-    unsigned char* ldsA = ldsT + RP * ROWB;           // 128 x ROWB: D, 32 rows per wave
+    unsigned char* ldsA = ldsT + RP * ROWB;           // 32 WAVES x ROWB: D, 32 rows per wave
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int jl = lane & 31, g = lane >> 5;
     const uint32_t lid = blockIdx.x - ta.first;
     const uint32_t s = lid % S, rb = lid / S;
-    const uint32_t row0 = rb * 128 + wave * 32;
+    const uint32_t row0 = rb * (32 * WAVES) + wave * 32;
     const uint32_t k_begin = s * kper;
     const uint32_t k_end = min(n, k_begin + kper);
     const uint32_t n_st = (k_end - k_begin) / 64;     // whole stages only (the host checks)
@@ -94,7 +98,7 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_full(const Group grp
     {                                                                                                     \
         const uint32_t col0 = k_begin + (ST) * 64;                                                        \
         _Pragma("unroll") for (int p = 0; p < PQ; ++p) {                                                  \
-            const int idx = tid + p * 256;                                                                \
+            const int idx = tid + p * NTH;                                                                \
             const int jp = idx & 31, c4 = (idx >> 5) * 4;                                                 \
             const uint32_t cc = min(static_cast<uint32_t>(c4), ldq - 4u);                                 \
             _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                               \
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_full(const Group grp
     // of two adjacent columns
 #define EDGC_FULL_STAGE_Q()                                                                               \
     _Pragma("unroll") for (int p = 0; p < PQ; ++p) {                                                      \
-        const int idx = tid + p * 256;                                                                    \
+        const int idx = tid + p * NTH;                                                                    \
         const int jp = idx & 31, c4 = (idx >> 5) * 4;                                                     \
         uint32_t w[2][2][NP];                                                                             \
         _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                                   \
@@ -243,14 +247,14 @@ __global__ __launch_bounds__(256, 2) void k_pass_p_deferred_full(const Group grp
 // Whether a group meets what k_pass_p_deferred_full assumes (checked on the host before the
 // launch; the grid decomposition d0 = columns per split is a multiple of 64 by construction).
 template <int NP>
-static bool group_is_full(const Group& g)
+static bool group_is_full(const Group& g, uint32_t waves)
 {
     using GT = typename GradElem<NP>::type;
     if (!g.defer) return false;
     for (uint32_t i = 0; i < g.count; ++i) {
         const TensorArgs& t = g.t[i];
         if (t.e_zero || !t.G) return false;
-        if (t.m % 128 || t.n % 64 || t.ldg % 2) return false;
+        if (t.m % (32 * waves) || t.n % 64 || t.ldg % 2) return false;
         if (t.ldg >= (1ull << 28) || t.n >= (1u << 28)) return false;
         if (t.ldq < 4) return false;
         if (reinterpret_cast<uintptr_t>(t.G) % (2 * sizeof(GT)) || reinterpret_cast<uintptr_t>(t.E) % 8) return false;
@@ -258,51 +262,63 @@ static bool group_is_full(const Group& g)
     return true;
 }
 
-bool pass_p_full_applies(const Group& g, edgc_dtype dt, int rt)
+bool pass_p_full_applies(const Group& g, edgc_dtype dt, int rt, uint32_t waves)
 {
+    if (waves != 4 && !(waves == 8 && rt >= 2)) return false;
     // fp32 gradients above rank 64 would need 103 KB of LDS (one block per CU): not built
-    if (dt == EDGC_BF16) return group_is_full<1>(g);
-    return rt <= 2 && group_is_full<2>(g);
+    if (dt == EDGC_BF16) return group_is_full<1>(g, waves);
+    return rt <= 2 && group_is_full<2>(g, waves);
 }
 
-template <int NP, int RT>
-static hipError_t launch_full(const Group& g, uint32_t blocks, bool qlate, hipStream_t st)
+template <int NP, int RT, int WAVES>
+static hipError_t launch_full_w(const Group& g, uint32_t blocks, bool qlate, hipStream_t st)
 {
-    constexpr size_t lds = pass_p_full_lds<NP, RT>();
+    constexpr size_t lds = pass_p_full_lds<NP, RT, WAVES>();
+    constexpr int NTH = 64 * WAVES;
     if (g.stream) {
-        if (qlate) k_pass_p_deferred_full<NP, RT, true, true><<<blocks, 256, lds, st>>>(g);
-        else k_pass_p_deferred_full<NP, RT, true, false><<<blocks, 256, lds, st>>>(g);
+        if (qlate) k_pass_p_deferred_full<NP, RT, true, true, WAVES><<<blocks, NTH, lds, st>>>(g);
+        else k_pass_p_deferred_full<NP, RT, true, false, WAVES><<<blocks, NTH, lds, st>>>(g);
     } else {
-        if (qlate) k_pass_p_deferred_full<NP, RT, false, true><<<blocks, 256, lds, st>>>(g);
-        else k_pass_p_deferred_full<NP, RT, false, false><<<blocks, 256, lds, st>>>(g);
+        if (qlate) k_pass_p_deferred_full<NP, RT, false, true, WAVES><<<blocks, NTH, lds, st>>>(g);
+        else k_pass_p_deferred_full<NP, RT, false, false, WAVES><<<blocks, NTH, lds, st>>>(g);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_pass_p_full(const Group& g, edgc_dtype dt, int rt, uint32_t blocks, bool qlate, hipStream_t st)
+template <int NP, int RT>
+static hipError_t launch_full(const Group& g, uint32_t blocks, bool qlate, uint32_t waves, hipStream_t st)
+{
+    if constexpr (RT >= 2) {
+        if (waves == 8) return launch_full_w<NP, RT, 8>(g, blocks, qlate, st);
+    }
+    return launch_full_w<NP, RT, 4>(g, blocks, qlate, st);
+}
+
+hipError_t launch_pass_p_full(const Group& g, edgc_dtype dt, int rt, uint32_t blocks, bool qlate, uint32_t waves,
+                              hipStream_t st)
 {
     if (dt == EDGC_BF16) {
         switch (rt) {
-        case 1: return launch_full<1, 1>(g, blocks, qlate, st);
-        case 2: return launch_full<1, 2>(g, blocks, qlate, st);
-        default: return launch_full<1, 4>(g, blocks, qlate, st);
+        case 1: return launch_full<1, 1>(g, blocks, qlate, waves, st);
+        case 2: return launch_full<1, 2>(g, blocks, qlate, waves, st);
+        default: return launch_full<1, 4>(g, blocks, qlate, waves, st);
         }
     }
     switch (rt) {
-    case 1: return launch_full<2, 1>(g, blocks, qlate, st);
-    default: return launch_full<2, 2>(g, blocks, qlate, st);
+    case 1: return launch_full<2, 1>(g, blocks, qlate, waves, st);
+    default: return launch_full<2, 2>(g, blocks, qlate, waves, st);
     }
 }
 
-template <int NP, int RT>
+template <int NP, int RT, int WAVES>
 static hipError_t allow_lds_full()
 {
-    constexpr int lds = static_cast<int>(pass_p_full_lds<NP, RT>());
+    constexpr int lds = static_cast<int>(pass_p_full_lds<NP, RT, WAVES>());
     if (lds <= 64 * 1024) return hipSuccess;
-    const void* fns[4] = {reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, true, true>),
-                          reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, true, false>),
-                          reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, false, true>),
-                          reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, false, false>)};
+    const void* fns[4] = {reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, true, true, WAVES>),
+                          reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, true, false, WAVES>),
+                          reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, false, true, WAVES>),
+                          reinterpret_cast<const void*>(&k_pass_p_deferred_full<NP, RT, false, false, WAVES>)};
     for (const void* f : fns) {
         hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
@@ -312,9 +328,12 @@ static hipError_t allow_lds_full()
 
 hipError_t prepare_pass_p_full()
 {
-    hipError_t e = allow_lds_full<2, 2>();
-    if (e != hipSuccess) return e;
-    return allow_lds_full<1, 4>();
+    hipError_t e = allow_lds_full<2, 2, 4>();
+    if (e == hipSuccess) e = allow_lds_full<1, 4, 4>();
+    if (e == hipSuccess) e = allow_lds_full<1, 2, 8>();
+    if (e == hipSuccess) e = allow_lds_full<1, 4, 8>();
+    if (e == hipSuccess) e = allow_lds_full<2, 2, 8>();
+    return e;
 }
 
 }  // namespace edgc
