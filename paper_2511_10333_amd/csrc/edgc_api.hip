@@ -81,6 +81,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     if (const char* e = getenv("EDGC_TUNE_QFULL")) ctx->tune_qfull = atoi(e);
     if (const char* e = getenv("EDGC_TUNE_PWAVES")) ctx->tune_pwaves = atoi(e);
     if (const char* e = getenv("EDGC_TUNE_APPLY")) ctx->tune_apply = atoi(e);
+    if (const char* e = getenv("EDGC_TUNE_EPT")) ctx->tune_ept = atoi(e);
     if (const char* e = getenv("EDGC_TUNE_PATTERN_MIN")) ctx->tune_pattern_min = atoll(e);
 
     Scratch& s = ctx->s;

@@ -29,6 +29,7 @@ constexpr int kMMBlock   = 256;
 constexpr int kMMBlockFat = 1024;                 // large samples: one block per CU
 constexpr uint64_t kBigSampleItems = 8ull << 20;  // items (16 bytes each) from which a sample counts as large
 constexpr int kHistBlock = 512;
+constexpr int kSmallSampleBlocks = 16;   // blocks a small sample's kernels get at most
 constexpr int kHistBlockFat = 1024;   // when the LDS histogram leaves room for one block per CU
 
 // ---------------------------------------------------------------------------
@@ -941,6 +942,7 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
     const float fbins = static_cast<float>(bins);
 
     const double sample_bytes = static_cast<double>(g.n_sampled) * sizeof(T);
+    const bool small_sample = g.n_items <= static_cast<uint64_t>(kHistBlock) * 4 * ctx->num_cu * 2;
     // One read into 16-bit counters per block (the kernels above), where the context has the memory
     // for the blocks' fields: every bf16 sample of some size (no range pass, any number of bins), and
     // fp32 samples on more bins than 32-bit counters hold in LDS at once.  The plain kernels follow on
@@ -986,7 +988,14 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
                                                                                   fbins, counts, bins,
                                                                                   by_pattern ? gate : nullptr));
         } else {
-            const uint32_t gx = grid_for(g.n_items, kMMBlock, 16, min(kMaxReduceBlocks, ctx->num_cu * 4));
+            // a small sample (the 1 % sample of a transformer block's gradients, say) gets at most 16 blocks:
+            // beside the compressor's passes it is the number of CU slots the estimate takes that costs step
+            // time, not its own duration (hidden-5120 bf16 block at rank 128, 393 Ki items: 96 blocks of 16 items
+            // per thread 1.241 ms per step, 12 blocks 1.207 ms, though the two kernels alone take 88 instead of 44 us)
+            const uint64_t few = static_cast<uint64_t>(kMMBlock) * kSmallSampleBlocks;
+            const int mm_items = ctx->tune_ept > 0 ? 2 * ctx->tune_ept
+                               : (small_sample ? static_cast<int>(std::max<uint64_t>(16, (g.n_items + few - 1) / few)) : 16);
+            const uint32_t gx = grid_for(g.n_items, kMMBlock, mm_items, min(kMaxReduceBlocks, ctx->num_cu * 4));
             EDGC_LAUNCH(ctx, st, KID_MINMAX, sample_bytes, 0.0,
                         k_minmax<T, VEC, kMMBlock><<<gx, kMMBlock, 0, st>>>(g, s.mm_part, s.done_counter, rp,
                                                                             fbins, counts, bins,
@@ -1010,7 +1019,7 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
     // more than 16384 bins are covered in slices of 32768 (128 KiB), one slice per blockIdx.y
     // small samples get few blocks of few items each, and then fewer replicas so that zeroing
     // and folding the LDS histogram does not outweigh the sampling itself
-    const bool small = g.n_items <= static_cast<uint64_t>(kHistBlock) * 4 * ctx->num_cu * 2;
+    const bool small = small_sample;
     const uint32_t word_cap = small ? 4096u : 16384u;
     uint32_t bins_local = bins, rep_shift = 0;
     if (bins <= 16384) {
@@ -1021,7 +1030,10 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
     const uint32_t ny = (bins + bins_local - 1) / bins_local;
     const size_t lds = static_cast<size_t>(bins_local << rep_shift) * sizeof(uint32_t);
     // enough items per block that zeroing and flushing the LDS histogram stays small
-    const int per_thread = small ? 8 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
+    const uint64_t few_h = static_cast<uint64_t>(kHistBlock) * kSmallSampleBlocks;
+    const int per_thread = small ? (ctx->tune_ept > 0 ? ctx->tune_ept
+                                                      : static_cast<int>(std::max<uint64_t>(8, (g.n_items + few_h - 1) / few_h)))
+                                 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
     // One block of 1024 threads per CU when a histogram of more than 64 KiB leaves room for one block only
     // (1e9 fp32 elements on 65536 bins: 1.6 instead of 3.6 ms) and for samples of 8 Mi items or more (1e8
     // fp32 elements on 4096 bins: 0.13 instead of 0.18 ms; 1e9: 0.83 instead of 0.86 ms); two blocks of
