@@ -144,7 +144,7 @@ class Workload:
             gctx.reserve_batch([(self.layers[i]["spec"].m, self.layers[i]["spec"].n) for i in idx])
             tensors = [edgc.Tensor(self.layers[i]["G"], self.layers[i]["out"], self.layers[i]["E"], self.layers[i]["Q"],
                                    self.layers[i]["P"], True) for i in idx]
-            self.groups.append(dict(ctx=gctx, tensors=tensors, stream=self.streams[k], idx=idx))
+            self.groups.append(dict(ctx=gctx, tensors=tensors, prep=edgc.PreparedBatch(tensors), stream=self.streams[k], idx=idx))
         # ONE stage-level entropy estimate per step over all gradient buffers (the paper's rank is per stage)
         self.ectx = edgc.Context(0, max_bins=w["bins"], max_rank=4, max_rows=64, max_cols=64)
         self.flats = [L["G"].view(-1) for L in self.layers]
@@ -226,9 +226,9 @@ class Workload:
         for g in self.groups if r else []:                  # rank 0: warm-up, the gradients go uncompressed
             first = g["tensors"][0].residual_is_zero
             explicit_in = g.pop("materialized", False)      # after a rank change the buffer holds E itself
-            g["ctx"].compress_batch(g["tensors"], r, stream=g["stream"],
+            g["ctx"].compress_batch(g["prep"], r, stream=g["stream"],
                                     deferred=self.deferred and not first and not explicit_in)
-            g["ctx"].decompress_batch(g["tensors"], r, stream=g["stream"], deferred=self.deferred)
+            g["ctx"].decompress_batch(g["prep"], r, stream=g["stream"], deferred=self.deferred)
             for x in g["tensors"]:
                 x.residual_is_zero = False
         for si, g in enumerate(self.groups):

@@ -327,6 +327,28 @@ def _stream_handle(stream) -> int:
     return int(s.cuda_stream)
 
 
+class PreparedBatch:
+    """The descriptor array of a list of :class:`Tensor`, built once.  The batched calls take it in
+    place of the list; only the two per-call flags are written again (``residual_is_zero`` from the
+    Tensor objects, ``deferred`` from the call).  Pointers, shapes and leading dimensions are those
+    the tensors had when it was built: build a new one after any of them changes."""
+
+    def __init__(self, tensors: Sequence[Tensor]):
+        self.tensors = list(tensors)
+        self.arr, self.code = Context._marshal(self.tensors)
+
+    def __len__(self):
+        return len(self.tensors)
+
+    def refresh(self, deferred: bool):
+        d = 1 if deferred else 0
+        for i, t in enumerate(self.tensors):
+            a = self.arr[i]
+            a.residual_is_zero = 1 if t.residual_is_zero else 0
+            a.deferred = d
+        return self.arr, self.code
+
+
 class Context:
     """Owns an ``edgc_ctx``.  Methods take torch CUDA tensors (device memory only) and
     enqueue on ``stream`` (default: torch's current stream); nothing synchronises."""
@@ -500,7 +522,9 @@ class Context:
         self._check(self._L.edgc_reserve_batch(self._h, rows, cols, n), "edgc_reserve_batch")
 
     @staticmethod
-    def _marshal(tensors: Sequence[Tensor], deferred: bool = False):
+    def _marshal(tensors, deferred: bool = False):
+        if isinstance(tensors, PreparedBatch):
+            return tensors.refresh(deferred)
         arr = (_Tensor * max(len(tensors), 1))()
         code = None
         for i, t in enumerate(tensors):

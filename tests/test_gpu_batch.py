@@ -189,6 +189,26 @@ def test_batch_equals_single_tensor_calls(dtype):
     assert torch.equal(one.t[0].residual, E) and torch.equal(one.t[0].grad_out, out)
 
 
+@pytest.mark.parametrize("deferred", [False, True])
+def test_prepared_descriptors_give_the_same_bits_as_a_list(deferred):
+    """binding.PreparedBatch builds the descriptor array once and rewrites only the two per-call
+    flags: three steps through it equal three steps through the plain list bit for bit."""
+    shapes, r = [(512, 768), (256, 1024), (1024, 256)], 16
+    a = Stage(shapes, r, "bf16", seed=5, deferred=deferred)
+    b = Stage(shapes, r, "bf16", seed=5, deferred=deferred)
+    prep = edgc.PreparedBatch(b.t)
+    for step in range(3):
+        a.step_device()
+        b.ctx.compress_batch(prep, r, deferred=deferred and step > 0)
+        b.ctx.decompress_batch(prep, r, deferred=deferred)
+        torch.cuda.synchronize()
+        for t in b.t:
+            t.residual_is_zero = False
+        for ta, tb in zip(a.t, b.t):
+            assert torch.equal(ta.P, tb.P) and torch.equal(ta.Q, tb.Q)
+            assert torch.equal(ta.residual, tb.residual) and torch.equal(ta.grad_out, tb.grad_out)
+
+
 def test_batch_rejects_bad_descriptors_before_launching():
     st = Stage([(256, 256), (128, 384)], 8, "f32", seed=5)
     before = [t.P.clone() for t in st.t]
