@@ -75,11 +75,11 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profile(workload: str, rank: int, kernel: str):
+def traffic_from_profile(workload: str, rank: int, kernel: str, folder: str = None):
     """HBM-side bytes per launch of `kernel` from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary of this
     workload and rank under profiles/ (written by paper_2511_10333_amd/profile_summary.py from the counter CSVs);
     None when no such summary is there."""
-    path = os.path.join(ROOT, "profiles", "traffic_%s_r%d.md" % (workload, rank))
+    path = os.path.join(folder or os.path.join(ROOT, "profiles"), "traffic_%s_r%d.md" % (workload, rank))
     try:
         text = open(path).read()
     except OSError:
