@@ -271,3 +271,36 @@ def test_sixteen_bit_counter_kernels_on_small_and_ragged_samples(mode, dtype):
     assert (got.n_sampled, got.lo, got.hi) == (ref.n_sampled, ref.lo, ref.hi)
     assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
     c.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sixteen_bit_counters_under_the_heaviest_contention(dtype):
+    """Every thread of every block hits the same one or two 16-bit fields: a constant buffer and a
+    two-valued one of 2^26 + 5 elements (large enough for the one-read kernels by default; fp32 takes
+    them on 65536 bins).  The fields wrap thousands of times per block; the counts must still be exact."""
+    n = (1 << 26) + 5
+    bins = 65536 if dtype == "f32" else 4096
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    c = ctx()
+    x = torch.full((n,), 0.375, device="cuda", dtype=tdt)
+    counts = torch.empty(bins, dtype=torch.int64, device="cuda")
+    got = c.entropy_estimate(x, 1, 64, 0, 0, bins, None, counts)
+    assert got.status == 0 and got.n_sampled == n and got.H_bits == 0.0 and (got.lo, got.hi) == (0.375, 0.375)
+    assert int(counts[0]) == n and int(counts.sum()) == n
+    x[1::3] = -2.5                                         # two values, one third / two thirds
+    ref = orc.entropy(to_host_any(x), 1, 64, 0, 0, bins)
+    got = c.entropy_estimate(x, 1, 64, 0, 0, bins, None, counts)
+    assert (got.lo, got.hi, got.n_sampled) == (ref.lo, ref.hi, n)
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
+    assert abs(got.H_bits - ref.H_bits) <= H_TOL
+    x[7::1000] = float("nan")
+    ref = orc.entropy(to_host_any(x), 1, 64, 0, 0, bins)
+    got = c.entropy_estimate(x, 1, 64, 0, 0, bins, None, counts)
+    assert got.n_nonfinite == ref.n_nonfinite > 0
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), ref.counts)
+
+
+def to_host_any(x):
+    if x.dtype == torch.bfloat16:
+        return x.view(torch.int16).cpu().numpy().view(np.uint16)
+    return x.cpu().numpy()
