@@ -60,7 +60,9 @@ typedef struct edgc_ctx edgc_ctx;   /* opaque; owns only scratch memory */
  * up to max_bins bins and matrices of up to max_rows x max_cols at rank
  * <= max_rank (max_rank <= 128; max_rows, max_cols <= 2^28, which also bounds
  * every leading dimension of a compressed matrix in the calls below: beyond it
- * they return EDGC_EINVAL).  *out is NULL on failure. */
+ * they return EDGC_EINVAL).  Besides what these sizes ask for, the entropy
+ * estimate keeps 128 KiB of 16-bit counters per compute unit (32 MiB on a GPU of
+ * 256) and two 512 KiB counter arrays.  *out is NULL on failure. */
 int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, uint32_t max_rank,
                 uint64_t max_rows, uint64_t max_cols);
 int edgc_destroy(edgc_ctx* ctx);
