@@ -2415,7 +2415,13 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
     constexpr edgc_dtype DT = (NP == 1) ? EDGC_BF16 : EDGC_F32;
     // (up to rank 64 the general kernel already writes at the rate the store pattern allows)
     const uint32_t waves = ctx->tune_dfull == 4 ? 4u : 8u;
-    const bool use_full = g.defer && (ctx->tune_dfull > 0 || (ctx->tune_dfull < 0 && RT == 4)) &&
+    // also at lower ranks when the launch writes a gigabyte or more (a 32-tensor stage of hidden-4096 fp32 layers,
+    // 3.2 GB per launch: 727 to 771 us against 833 to 877 at ranks 16, 32 and 64; launches of 0.2 to 0.4 GB are 1 to
+    // 7 % faster through the general kernel)
+    uint64_t out_bytes = 0;
+    for (uint32_t i = 0; i < g.count; ++i) out_bytes += static_cast<uint64_t>(g.t[i].m) * g.t[i].n * esz;
+    const bool big = out_bytes >= (1ull << 30);
+    const bool use_full = g.defer && (ctx->tune_dfull > 0 || (ctx->tune_dfull < 0 && (RT == 4 || big))) &&
                           decompress_full_applies(g, DT, waves);
     const uint32_t rows_per_block = use_full ? 32u * waves : 128u;
     const uint32_t per_cu = ctx->tune_d ? ctx->tune_d : (use_full && waves == 8 ? 2u : 4u);
