@@ -2291,7 +2291,11 @@ static int run_pass_q(edgc_ctx* ctx, Group& g, const TensorScratch* cap, hipStre
         if (want && pass_q_full_applies(g, DT, RT, want)) qwaves = want;
     }
     const uint32_t W4 = (qwaves ? qwaves : 4u) * 32 * NT;
-    const uint32_t per_cu = ctx->tune_q ? ctx->tune_q : (qwaves == 8 ? 1u : 2u);
+    // launches that read a gigabyte or more (a 32-tensor stage: 16 tensors share the blocks, most of them left
+    // with one row split) aim at three blocks per CU: 594 against 649 us
+    uint64_t d_bytes = 0;
+    for (uint32_t i = 0; i < g.count; ++i) d_bytes += 4ull * g.t[i].m * g.t[i].n;
+    const uint32_t per_cu = ctx->tune_q ? ctx->tune_q : (qwaves == 8 ? 1u : (d_bytes >= (1ull << 30) ? 3u : 2u));
     const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * per_cu;
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
@@ -2424,7 +2428,8 @@ static int decompress_impl(edgc_ctx* ctx, Group& g, hipStream_t st)
     const bool use_full = g.defer && (ctx->tune_dfull > 0 || (ctx->tune_dfull < 0 && (RT == 4 || big))) &&
                           decompress_full_applies(g, DT, waves);
     const uint32_t rows_per_block = use_full ? 32u * waves : 128u;
-    const uint32_t per_cu = ctx->tune_d ? ctx->tune_d : (use_full && waves == 8 ? 2u : 4u);
+    // (the 3.2 GB launches of that stage: four blocks per CU aimed at 717 us, two 768 us)
+    const uint32_t per_cu = ctx->tune_d ? ctx->tune_d : (use_full && waves == 8 && !big ? 2u : 4u);
     const uint32_t target = static_cast<uint32_t>(ctx->num_cu) * per_cu;
     uint32_t tgt[kMaxGroup];
     share_targets(g, target, tgt);
