@@ -2099,7 +2099,12 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
     // 327 / 307 us; rank 64 294 / 309 us; hidden-4096 fp32 block at rank 64 233 / 243 us)
     const bool want8 = ctx->tune_pwaves == 8 || (ctx->tune_pwaves < 0 && RT == 4);
     const uint32_t pwaves = (want8 && pass_p_full_applies(g, DT, RT, 8)) ? 8u : 4u;
-    const bool use_full = with_grad && ctx->tune_full != 0 && pass_p_full_applies(g, DT, RT, pwaves);
+    // (fp32 above rank 64, whole-tile kernel against the 32-column-stage kernel: 287 against 316 us on the hidden-4096
+    // block, whose residual streams from HBM; 89 against 86 us on the hidden-2048 block, which the last-level cache
+    // holds: there the general kernel stays)
+    const bool fp32_wide = NP == 2 && RT == 4;
+    const bool use_full = with_grad && ctx->tune_full != 0 && pass_p_full_applies(g, DT, RT, pwaves) &&
+                          (!fp32_wide || g.stream || ctx->tune_full > 0);
     const bool use_narrow = with_grad && g.defer && RT == 4;
     const bool use_wide = with_grad && RT <= 2 && (g.defer || NP == 1);
     const uint32_t per_cu = (use_narrow && !use_full) ? 2u : (use_full && pwaves == 8 ? 2u : 4u);
@@ -2136,7 +2141,8 @@ static int run_pass_p(edgc_ctx* ctx, Group& g, const TensorScratch* cap, bool wi
         flops += 2.0 * mn * g.r;
     }
     if (use_full) {
-        const bool qlate = ctx->tune_full == 2;
+        // fp32 above rank 64: with the next stage's Q rows requested late the kernel spills 6 registers, early 51
+        const bool qlate = ctx->tune_full == 2 || (NP == 2 && RT == 4);
         ProfScope prof_scope_(ctx, st, KID_PASS_P_DEFERRED, bytes, 2.0 * flops);
         EDGC_HIP_TRY(ctx, launch_pass_p_full(g, DT, RT, blocks, qlate, pwaves, st));
         return EDGC_OK;

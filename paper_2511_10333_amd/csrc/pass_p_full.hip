@@ -265,9 +265,10 @@ static bool group_is_full(const Group& g, uint32_t waves)
 bool pass_p_full_applies(const Group& g, edgc_dtype dt, int rt, uint32_t waves)
 {
     if (waves != 4 && !(waves == 8 && rt >= 2)) return false;
-    // fp32 gradients above rank 64 would need 103 KB of LDS (one block per CU): not built
     if (dt == EDGC_BF16) return group_is_full<1>(g, waves);
-    return rt <= 2 && group_is_full<2>(g, waves);
+    // fp32 gradients above rank 64: eight waves only (138 KB of LDS, one block per CU)
+    if (rt > 2 && waves != 8) return false;
+    return group_is_full<2>(g, waves);
 }
 
 template <int NP, int RT, int WAVES>
@@ -306,7 +307,8 @@ hipError_t launch_pass_p_full(const Group& g, edgc_dtype dt, int rt, uint32_t bl
     }
     switch (rt) {
     case 1: return launch_full<2, 1>(g, blocks, qlate, waves, st);
-    default: return launch_full<2, 2>(g, blocks, qlate, waves, st);
+    case 2: return launch_full<2, 2>(g, blocks, qlate, waves, st);
+    default: return launch_full_w<2, 4, 8>(g, blocks, qlate, st);
     }
 }
 
@@ -333,6 +335,7 @@ hipError_t prepare_pass_p_full()
     if (e == hipSuccess) e = allow_lds_full<1, 2, 8>();
     if (e == hipSuccess) e = allow_lds_full<1, 4, 8>();
     if (e == hipSuccess) e = allow_lds_full<2, 2, 8>();
+    if (e == hipSuccess) e = allow_lds_full<2, 4, 8>();
     return e;
 }
 
