@@ -69,6 +69,7 @@ def parse_args():
     ap.add_argument("--ent-strides", default="1000,100,10,1", help="cfg3_flat_1e9 only: the sampling strides to run")
     ap.add_argument("--ent-bins", default="256,4096,65536", help="cfg3_flat_1e9 only: the bin counts to run")
     ap.add_argument("--ent-dtypes", default="f32,bf16", help="cfg3_flat_1e9 only: the element types to run")
+    ap.add_argument("--ent-chunk", type=int, default=64, help="cfg3_flat_1e9 only: elements per sampled chunk")
     ap.add_argument("--serial", action="store_true",
                     help="issue everything on ONE stream, also in the timed region: the run to put under "
                          "rocprofv3 --kernel-trace --stats, every kernel alone on the GPU")

@@ -15,7 +15,7 @@ def entropy_sweep(args, torch, edgc, metric, hbm_peak_gbs) -> int:
     `reads_of_sample` says how often its kernels read the sample (bf16 samples of 32 Mi elements or
     more are read once), `sample_gbs` = those reads x sample bytes / time."""
     from paper_2511_10333_amd.binding import ENTROPY_RESULT_BYTES, EntropyResult
-    n, chunk, seed = 1_000_000_000, 64, 0
+    n, chunk, seed = 1_000_000_000, args.ent_chunk, 0
     strides = tuple(int(v) for v in args.ent_strides.split(","))
     bins_list = tuple(int(v) for v in args.ent_bins.split(","))
     dtypes = args.ent_dtypes.split(",")
