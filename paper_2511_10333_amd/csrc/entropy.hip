@@ -29,7 +29,7 @@ constexpr int kMMBlock   = 256;
 constexpr int kMMBlockFat = 1024;                 // large samples: one block per CU
 constexpr uint64_t kBigSampleItems = 8ull << 20;  // items (16 bytes each) from which a sample counts as large
 constexpr int kHistBlock = 512;
-constexpr int kSmallSampleBlocks = 16;   // blocks a small sample's kernels get at most
+constexpr int kSmallSampleBlocks = 16;   // blocks the kernels of a sample of up to 512 Ki items get at most
 constexpr int kHistBlockFat = 1024;   // when the LDS histogram leaves room for one block per CU
 
 // ---------------------------------------------------------------------------
@@ -943,6 +943,11 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
 
     const double sample_bytes = static_cast<double>(g.n_sampled) * sizeof(T);
     const bool small_sample = g.n_items <= static_cast<uint64_t>(kHistBlock) * 4 * ctx->num_cu * 2;
+    // blocks a sample below 8 Mi items gets at most: 16 up to 1 Mi items; one per 32 Ki items from 2 Mi items on
+    // (1e7 fp32 elements, 2.5 Mi items: 0.068 instead of 0.082 ms alone); between the two the launch shapes of
+    // large samples (1e7 bf16 elements, 1.25 Mi items: 0.056 ms, with the cap 0.089)
+    const uint64_t few_blocks = small_sample ? kSmallSampleBlocks
+                              : (g.n_items >= (2ull << 20) ? (g.n_items >> 15) : ~0ull / (4 * kHistBlockFat));
     // One read into 16-bit counters per block (the kernels above), where the context has the memory
     // for the blocks' fields: every bf16 sample of some size (no range pass, any number of bins), and
     // fp32 samples on more bins than 32-bit counters hold in LDS at once.  The plain kernels follow on
@@ -992,9 +997,11 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
             // beside the compressor's passes it is the number of CU slots the estimate takes that costs step
             // time, not its own duration (hidden-5120 bf16 block at rank 128, 393 Ki items: 96 blocks of 16 items
             // per thread 1.241 ms per step, 12 blocks 1.207 ms, though the two kernels alone take 88 instead of 44 us)
-            const uint64_t few = static_cast<uint64_t>(kMMBlock) * kSmallSampleBlocks;
+            // (a 16 M-element sample of a 32-tensor stage, 4 Mi items: 983 and 491 blocks 6.90 ms per step and 87 + 123
+            // us alone, 123 blocks each 6.82 ms and 69 + 82 us)
+            const uint64_t few = static_cast<uint64_t>(kMMBlock) * few_blocks;
             const int mm_items = ctx->tune_ept > 0 ? 2 * ctx->tune_ept
-                               : (small_sample ? static_cast<int>(std::max<uint64_t>(16, (g.n_items + few - 1) / few)) : 16);
+                                                   : static_cast<int>(std::max<uint64_t>(16, (g.n_items + few - 1) / few));
             const uint32_t gx = grid_for(g.n_items, kMMBlock, mm_items, min(kMaxReduceBlocks, ctx->num_cu * 4));
             EDGC_LAUNCH(ctx, st, KID_MINMAX, sample_bytes, 0.0,
                         k_minmax<T, VEC, kMMBlock><<<gx, kMMBlock, 0, st>>>(g, s.mm_part, s.done_counter, rp,
@@ -1030,10 +1037,12 @@ static int run_entropy(edgc_ctx* ctx, const EntScratch& s, const EntGroup& g, ui
     const uint32_t ny = (bins + bins_local - 1) / bins_local;
     const size_t lds = static_cast<size_t>(bins_local << rep_shift) * sizeof(uint32_t);
     // enough items per block that zeroing and flushing the LDS histogram stays small
-    const uint64_t few_h = static_cast<uint64_t>(kHistBlock) * kSmallSampleBlocks;
-    const int per_thread = small ? (ctx->tune_ept > 0 ? ctx->tune_ept
-                                                      : static_cast<int>(std::max<uint64_t>(8, (g.n_items + few_h - 1) / few_h)))
-                                 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
+    const uint64_t few_h = static_cast<uint64_t>(kHistBlock) * few_blocks;
+    const int floor_items = small ? 8 : ((bins_local << rep_shift) > 16384 ? 64 : 16);
+    const int per_thread = ctx->tune_ept > 0 ? ctx->tune_ept
+                         : (g.n_items < kBigSampleItems
+                                ? static_cast<int>(std::max<uint64_t>(floor_items, (g.n_items + few_h - 1) / few_h))
+                                : floor_items);
     // One block of 1024 threads per CU when a histogram of more than 64 KiB leaves room for one block only
     // (1e9 fp32 elements on 65536 bins: 1.6 instead of 3.6 ms) and for samples of 8 Mi items or more (1e8
     // fp32 elements on 4096 bins: 0.13 instead of 0.18 ms; 1e9: 0.83 instead of 0.86 ms); two blocks of
