@@ -466,8 +466,8 @@ __global__ __launch_bounds__(256) void k_gram_sum(const Group grps, uint32_t ne)
 // Scaled Cholesky of the Gram matrix and the inverse factor, one block, fp64.
 //   W = P^T P,  D = diag(W)^-1/2,  C = D W D = L L^T,  R = L^T D^-1,  R^-1 = D L^-T
 // Blocked right-looking factorisation on 16x16 tiles held in LDS: the diagonal
-// tile is factored and inverted by one wavefront in registers (read-lane
-// broadcasts), the panel solve, the trailing update and the blocked inverse
+// tile is factored and inverted by one wavefront in registers (four pivots at
+// a time), the panel solve, the trailing update and the blocked inverse
 // X = L^-1 run on fp64 MFMA with one tile per wavefront.  X tiles below the
 // diagonal are stored transposed in the (otherwise unused) upper tiles.
 // A pivot of C below kPivotEps marks a column that is numerically dependent on
@@ -478,72 +478,92 @@ __global__ __launch_bounds__(256) void k_gram_sum(const Group grps, uint32_t ne)
 constexpr double kPivotEps = 1e-11;
 constexpr int kCholThreads = 1024;
 
-__device__ __forceinline__ double readlane_f64(double x, int src_lane)
-{
-    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src_lane);
-    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src_lane);
-    return __hiloint2double(hi, lo);
-}
-
-// 1/d and d^-1/2 for a pivot d of the scaled Gram matrix (kPivotEps < d, d of order 1 at most):
-// the hardware estimate (about 23 bits) and two Newton steps, a short dependent chain where the
-// library routines' range handling would sit on the critical path of the factorisation.
-__device__ __forceinline__ double pivot_rcp(double d)
-{
-    double y = __builtin_amdgcn_rcp(d);
-    y = fma(y, fma(-d, y, 1.0), y);
-    return fma(y, fma(-d, y, 1.0), y);
-}
+// d^-1/2 for a pivot d of the scaled Gram matrix (kPivotEps < d, d of order 1 at most): the
+// hardware estimate (about 23 bits) and one third-order step y (1 + e/2 + 3 e^2 / 8), e = 1 - d y^2,
+// whose error term e^3 lies below the rounding of fp64.  Four dependent operations, where the
+// library routine's range handling, or two Newton steps (six), would sit on the critical path of
+// the factorisation: a dependent fp64 operation costs a lone wavefront some 16 cycles.
 __device__ __forceinline__ double pivot_rsq(double d)
 {
-    double y = __builtin_amdgcn_rsq(d);
-    y = fma(0.5 * y, fma(-(d * y), y, 1.0), y);
-    return fma(0.5 * y, fma(-(d * y), y, 1.0), y);
+    const double y = __builtin_amdgcn_rsq(d);
+    const double e = fma(-(d * y), y, 1.0);
+    return fma(y * e, fma(0.375, e, 0.5), y);
 }
 
 // Cholesky factorisation of a symmetric 16x16 tile and the inverse X = L^-1 of its factor, by one
-// wavefront, in registers.  The tile S and X (which starts as the identity) are held in the
-// accumulator layout of the fp64 MFMA: register v of lane l = (j = l % 16, q = l / 16) holds
-// element [q + 4v][j].  Because S stays symmetric, the same registers are the MFMA operands of
-// a column: lane (i, k) of register kb holds S[i][4 kb + k].  Pivot c (kb = c / 4, k = c % 4)
-// therefore needs no broadcasts: its column, masked to the lanes of group k, is both operands of
-// one rank-1 MFMA update S -= s s^T / d, and one more MFMA applies the elementary row operation
-// to X: X += m X[c][:], m_c = 1/l_c - 1, m_i = -l_i / l_c = -s_i / d below the pivot.  Only the
-// pivot itself is read back (one read-lane) for its reciprocal.
-// A pivot not above kPivotEps is dead: nothing is eliminated with it, and its row and column of
-// X end up zero; the return value has bit c set for a dead pivot c.
-// Must be called by a whole wavefront.
-__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane)
+// wavefront, in four block steps of four pivots.  The tile S and X (which starts as the identity)
+// are held in the accumulator layout of the fp64 MFMA: register v of lane l = (j = l % 16,
+// q = l / 16) holds element [q + 4v][j].  Because S stays symmetric, register b is also the MFMA
+// operand of block column b: lane (i, k) holds S[i][4b + k].
+// Block step b:
+//   - the 4x4 diagonal block goes through LDS (`bc`, 16 doubles) to every lane, which factors it
+//     in plain fp64 arithmetic, L_bb, and finds column q of X_bb = L_bb^-1 by substitution;
+//   - one MFMA forms the panel in operand layout: with A = X_bb placed in rows 4b .. 4b+3 and
+//     B = block column b of S, row 4b + k' of the product is L[j][k'] = sum_k X_bb[k'][k] S[j][4b+k],
+//     and it lands in register b of lane (j, k');
+//   - one MFMA is the rank-4 update S -= L L^T.  Rows of L above the block's end are not the
+//     factor's, but an entry (i, j) of the update only takes rows i and j of L, and no entry of S
+//     in those rows or columns is read again;
+//   - two MFMAs apply the block row operation to X: rows of the block X_b <- X_bb X_b, then
+//     rows below X_i <- X_i - L_ib X_b.  They are issued after the update of S, so that they run
+//     while the next block's pivots are computed.
+// A pivot not above kPivotEps is dead: its reciprocal root is taken as zero, so nothing is
+// eliminated with it, and its row and column of X end up zero; the return value has bit c set for
+// a dead pivot c.  Must be called by a whole wavefront.
+__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane, double* bc)
 {
-    const int i = lane & 15, q = lane >> 4;
+    const int j = lane & 15, q = lane >> 4;
     uint32_t dead = 0;
-    double mop_prev = 0.0;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) x[v] = (q + 4 * v == i) ? 1.0 : 0.0;
+    for (int v = 0; v < 4; ++v) x[v] = (q + 4 * v == j) ? 1.0 : 0.0;
+    double e[4];                                        // column q of the identity
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        const int kb = c >> 2, k = c & 3;
-        const double d = readlane_f64(s[kb], c + 16 * k);        // S[c][c]
-        const bool ok = d > kPivotEps;
-        const double rd = ok ? pivot_rcp(d) : 0.0;
-        if (!ok) dead |= 1u << c;
-        const bool col = (q == k) && i >= c;                       // lanes of group k: S[c][i] = S[i][c]
-        const double sic = col ? s[kb] : 0.0;
-        const double neg = -(sic * rd);                            // -s_i / d; -1 on the pivot's own lane
-        s = __builtin_amdgcn_mfma_f64_16x16x4f64(neg, sic, s, 0, 0, 0);
-        // The row operation of pivot c - 1 on X is issued here, one pivot late: it waits for the one before
-        // it, which by now has finished, so the chain of S behind it is not held up.
-        if (c > 0) {
-            const int kbp = (c - 1) >> 2, kp = (c - 1) & 3;
-            const double xrow = (q == kp) ? x[kbp] : 0.0;          // lane (j, k'): X[c - 1][j]
-            x = __builtin_amdgcn_mfma_f64_16x16x4f64(mop_prev, xrow, x, 0, 0, 0);
+    for (int a = 0; a < 4; ++a) e[a] = (q == a) ? 1.0 : 0.0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int jb = j - 4 * b;
+        // S[4b + a][4b + c] as it stands is register b of lane (4b + a, c)
+        if (jb >= 0 && jb < 4) bc[jb * 4 + q] = s[b];
+        __builtin_amdgcn_wave_barrier();
+        const double a00 = bc[0], a10 = bc[4], a20 = bc[8], a30 = bc[12], a11 = bc[5], a21 = bc[9], a31 = bc[13],
+                     a22 = bc[10], a32 = bc[14], a33 = bc[15];
+        __builtin_amdgcn_wave_barrier();
+        const bool ok0 = a00 > kPivotEps;
+        const double r0 = ok0 ? pivot_rsq(a00) : 0.0;
+        const double l10 = a10 * r0, l20 = a20 * r0, l30 = a30 * r0;
+        const double d1 = fma(-l10, l10, a11);
+        const bool ok1 = d1 > kPivotEps;
+        const double r1 = ok1 ? pivot_rsq(d1) : 0.0;
+        const double l21 = fma(-l20, l10, a21) * r1, l31 = fma(-l30, l10, a31) * r1;
+        const double d2 = fma(-l21, l21, fma(-l20, l20, a22));
+        const bool ok2 = d2 > kPivotEps;
+        const double r2 = ok2 ? pivot_rsq(d2) : 0.0;
+        const double l32 = fma(-l31, l21, fma(-l30, l20, a32)) * r2;
+        const double d3 = fma(-l32, l32, fma(-l31, l31, fma(-l30, l30, a33)));
+        const bool ok3 = d3 > kPivotEps;
+        const double r3 = ok3 ? pivot_rsq(d3) : 0.0;
+        dead |= ((ok0 ? 0u : 1u) | (ok1 ? 0u : 2u) | (ok2 ? 0u : 4u) | (ok3 ? 0u : 8u)) << (4 * b);
+        // column q of X_bb: L_bb x = e_q
+        const double x0 = e[0] * r0;
+        const double x1 = fma(-l10, x0, e[1]) * r1;
+        const double x2 = fma(-l21, x1, fma(-l20, x0, e[2])) * r2;
+        const double x3 = fma(-l32, x2, fma(-l31, x1, fma(-l30, x0, e[3]))) * r3;
+        // lane (4b + a, k): X_bb[a][k], other lanes zero (the last pivot's entry is selected last:
+        // it is the one the chain waits for)
+        const double xa012 = (jb == 0) ? x0 : (jb == 1) ? x1 : (jb == 2) ? x2 : 0.0;
+        const double xa = (jb == 3) ? x3 : xa012;
+        const double n1 = xa - ((jb == q) ? 1.0 : 0.0);   // X_bb - I in the block's rows
+        if (b < 3) {
+            f64x4 lp = {0.0, 0.0, 0.0, 0.0};
+            lp = __builtin_amdgcn_mfma_f64_16x16x4f64(xa, s[b], lp, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f64_16x16x4f64(-lp[b], lp[b], s, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            x = __builtin_amdgcn_mfma_f64_16x16x4f64(n1, x[b], x, 0, 0, 0);
+            const double nl = (j >= 4 * b + 4) ? -lp[b] : 0.0;
+            x = __builtin_amdgcn_mfma_f64_16x16x4f64(nl, x[b], x, 0, 0, 0);
+        } else {
+            x = __builtin_amdgcn_mfma_f64_16x16x4f64(n1, x[b], x, 0, 0, 0);
         }
-        const double rs = ok ? pivot_rsq(d) : 0.0;                 // 1 / l_c, off the chain of S
-        mop_prev = (col && i == c) ? rs - 1.0 : neg;
-    }
-    {
-        const double xrow = (q == 3) ? x[3] : 0.0;                 // pivot 15
-        x = __builtin_amdgcn_mfma_f64_16x16x4f64(mop_prev, xrow, x, 0, 0, 0);
     }
     return dead;
 }
@@ -664,7 +684,7 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
                 const int a = lq + 4 * v, b = lr;                 // element [a][b]
                 st[v] = A[(j0 + max(a, b)) * LDA + j0 + min(a, b)];
             }
-            const uint32_t dead = chol16_factor_invert(st, xt, lane);
+            const uint32_t dead = chol16_factor_invert(st, xt, lane, red);
 #pragma unroll
             for (int v = 0; v < 4; ++v) Xd[(p * 16 + lq + 4 * v) * 17 + lr] = xt[v];   // X[row][col]
             if (lane == 0) deadmask[p] = dead;
