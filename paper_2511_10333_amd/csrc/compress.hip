@@ -398,13 +398,15 @@ __global__ __launch_bounds__(256) void k_reduce_gram(const Group grp, uint32_t R
         for (int k0 = 0; k0 < 64; k0 += 4) {
 #pragma unroll
             for (int q = 0; q < TPW; ++q) {
-                const double a = static_cast<double>(pk[k0 * LD + 16 * ta[q]]);
-                const double b = static_cast<double>(pk[k0 * LD + 16 * tb[q]]);
+                // rows from column tile tb, columns from column tile ta: the tile below the diagonal
+                const double a = static_cast<double>(pk[k0 * LD + 16 * tb[q]]);
+                const double b = static_cast<double>(pk[k0 * LD + 16 * ta[q]]);
                 acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[q], 0, 0, 0);
             }
         }
     }
-    // tile t of this block: 256 doubles, [i][j] with i = lane/16 + 4v, j = lane%16
+    // tile t = (ta <= tb) of this block: 256 doubles, [i][j] = W[16 tb + i][16 ta + j] with
+    // i = lane/16 + 4v, j = lane%16 (the lower triangle, which is the one k_chol factors)
 #pragma unroll
     for (int q = 0; q < TPW; ++q) {
         const int t = wave + 4 * q;
@@ -463,22 +465,27 @@ __global__ __launch_bounds__(256) void k_gram_sum(const Group grps, uint32_t ne)
 }
 
 // ---------------------------------------------------------------------------
-// Scaled Cholesky of the Gram matrix and the inverse factor, one block, fp64.
-//   W = P^T P,  D = diag(W)^-1/2,  C = D W D = L L^T,  R = L^T D^-1,  R^-1 = D L^-T
+// Cholesky of the Gram matrix and the inverse factor, one block, fp64.
+//   W = P^T P = L L^T,  R = L^T,  R^-1 = L^-T = X^T with X = L^-1
 // Blocked right-looking factorisation on 16x16 tiles held in LDS: the diagonal
 // tile is factored and inverted by one wavefront in registers (four pivots at
 // a time), the panel solve, the trailing update and the blocked inverse
 // X = L^-1 run on fp64 MFMA with one tile per wavefront.  X tiles below the
-// diagonal are stored transposed in the (otherwise unused) upper tiles.
-// A pivot of C below kPivotEps marks a column that is numerically dependent on
-// the previous ones: it is removed from the factorisation (row and column of X
-// zero), so its P^ column is zero and later columns are not projected on it.
-// `tiles` holds nb sets of upper-triangle tiles (nb > 1 only for a single tile).
+// diagonal are stored transposed in the (otherwise unused) upper tiles, and
+// written out as tiles of R^-1 as they are finished.
+// A pivot of column c not above kPivotEps W[c][c] (the scaled matrix
+// D W D, D = diag(W)^-1/2, would have a pivot not above kPivotEps) marks a
+// column that is numerically dependent on the previous ones: it is removed
+// from the factorisation (row and column of X zero), so its P^ column is zero
+// and later columns are not projected on it.
+// `tiles` holds nb sets of tiles (nb > 1 only for a single tile): tile t = (ta <= tb),
+// row-major over the triangle, is [i][j] = W[16 tb + i][16 ta + j].
 // ---------------------------------------------------------------------------
 constexpr double kPivotEps = 1e-11;
 constexpr int kCholThreads = 1024;
+constexpr int kCholPad = 1;      // LDS row padding of the matrix, doubles (2 and 4 measured the same or slower)
 
-// d^-1/2 for a pivot d of the scaled Gram matrix (kPivotEps < d, d of order 1 at most): the
+// d^-1/2 for a pivot d > 0 of the Gram matrix (a normal number: the entries are sums of squares of fp32 values): the
 // hardware estimate (about 23 bits) and one third-order step y (1 + e/2 + 3 e^2 / 8), e = 1 - d y^2,
 // whose error term e^3 lies below the rounding of fp64.  Four dependent operations, where the
 // library routine's range handling, or two Newton steps (six), would sit on the critical path of
@@ -507,18 +514,22 @@ __device__ __forceinline__ double pivot_rsq(double d)
 //   - two MFMAs apply the block row operation to X: rows of the block X_b <- X_bb X_b, then
 //     rows below X_i <- X_i - L_ib X_b.  They are issued after the update of S, so that they run
 //     while the next block's pivots are computed.
-// A pivot not above kPivotEps is dead: its reciprocal root is taken as zero, so nothing is
-// eliminated with it, and its row and column of X end up zero; the return value has bit c set for
-// a dead pivot c.  Must be called by a whole wavefront.
-__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane, double* bc)
+// A pivot of column c not above wd[c] (kPivotEps times the column's diagonal entry of the Gram matrix)
+// is dead: its reciprocal root is taken as zero, so nothing is eliminated with it, and its row and
+// column of X end up zero; the return value has bit c set for a dead pivot c.  `wd` and `bc` are in
+// LDS.  Must be called by a whole wavefront.
+__device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int lane, double* bc, const double* wd)
 {
     const int j = lane & 15, q = lane >> 4;
     uint32_t dead = 0;
 #pragma unroll
     for (int v = 0; v < 4; ++v) x[v] = (q + 4 * v == j) ? 1.0 : 0.0;
-    double e[4];                                        // column q of the identity
+    double e[4], tn[4];                                 // column q of the identity; a block's pivot thresholds
 #pragma unroll
-    for (int a = 0; a < 4; ++a) e[a] = (q == a) ? 1.0 : 0.0;
+    for (int a = 0; a < 4; ++a) {
+        e[a] = (q == a) ? 1.0 : 0.0;
+        tn[a] = wd[a];
+    }
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const int jb = j - 4 * b;
@@ -528,19 +539,24 @@ __device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int
         const double a00 = bc[0], a10 = bc[4], a20 = bc[8], a30 = bc[12], a11 = bc[5], a21 = bc[9], a31 = bc[13],
                      a22 = bc[10], a32 = bc[14], a33 = bc[15];
         __builtin_amdgcn_wave_barrier();
-        const bool ok0 = a00 > kPivotEps;
+        const double t0 = tn[0], t1 = tn[1], t2 = tn[2], t3 = tn[3];
+        if (b < 3) {                                        // the next block's, off the chain
+#pragma unroll
+            for (int a = 0; a < 4; ++a) tn[a] = wd[4 * b + 4 + a];
+        }
+        const bool ok0 = a00 > t0;
         const double r0 = ok0 ? pivot_rsq(a00) : 0.0;
         const double l10 = a10 * r0, l20 = a20 * r0, l30 = a30 * r0;
         const double d1 = fma(-l10, l10, a11);
-        const bool ok1 = d1 > kPivotEps;
+        const bool ok1 = d1 > t1;
         const double r1 = ok1 ? pivot_rsq(d1) : 0.0;
         const double l21 = fma(-l20, l10, a21) * r1, l31 = fma(-l30, l10, a31) * r1;
         const double d2 = fma(-l21, l21, fma(-l20, l20, a22));
-        const bool ok2 = d2 > kPivotEps;
+        const bool ok2 = d2 > t2;
         const double r2 = ok2 ? pivot_rsq(d2) : 0.0;
         const double l32 = fma(-l31, l21, fma(-l30, l20, a32)) * r2;
         const double d3 = fma(-l32, l32, fma(-l31, l31, fma(-l30, l30, a33)));
-        const bool ok3 = d3 > kPivotEps;
+        const bool ok3 = d3 > t3;
         const double r3 = ok3 ? pivot_rsq(d3) : 0.0;
         dead |= ((ok0 ? 0u : 1u) | (ok1 ? 0u : 2u) | (ok2 ? 0u : 4u) | (ok3 ? 0u : 8u)) << (4 * b);
         // column q of X_bb: L_bb x = e_q
@@ -568,31 +584,50 @@ __device__ __forceinline__ uint32_t chol16_factor_invert(f64x4& s, f64x4& x, int
     return dead;
 }
 
-// Tile (i, p), i > p, of X = L^-1:  X_ip = -X_ii sum_{k=p}^{i-1} L_ik X_kp, by one wavefront.
-// A holds L in its lower tiles and X_ip transposed in the upper tile (p, i):
-// A[16p + b][16i + a] = X_ip[a][b]; Xd holds the inverses of the diagonal tiles.  The sum S comes
-// out of the MFMA in the accumulator layout, which is the layout of a B operand: register kk is
-// S[4kk + lq][lr], so the product with -X_ii takes it as it stands.
-__device__ __forceinline__ void chol_inverse_tile(double* A, const double* Xd, int LDA, int i, int p, int lr, int lq)
+// Tile (i, j), i > j, of X = L^-1:  X_ij = -X_ii sum_{k=j}^{i-1} L_ik X_kj.
+// A holds L in its lower tiles and X_ij transposed in the upper tile (j, i):
+// A[16j + b][16i + a] = X_ij[a][b]; Xd holds the inverses of the diagonal tiles.
+// chol_inverse_terms adds the terms k0 <= k < k1 of the sum to `acc`, by one wavefront; the k blocks of
+// a tile alternate between two accumulators (a dependent fp64 MFMA waits some 110 cycles for the one
+// before it, an independent one 64).
+__device__ __forceinline__ void chol_inverse_terms(const double* A, const double* Xd, int LDA, int i, int j, int k0,
+                                                   int k1, int lr, int lq, f64x4& acc)
 {
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-    for (int k = p; k < i; ++k) {
+    f64x4 acc2 = {0.0, 0.0, 0.0, 0.0};
+    for (int k = k0; k < k1; ++k) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const double av = A[(16 * i + lr) * LDA + 16 * k + 4 * kk + lq];          // L_ik[a][kk']
-            const double bv = (k == p) ? Xd[(p * 16 + 4 * kk + lq) * 17 + lr]           // X_pp[kk'][b]
-                                       : A[(16 * p + lr) * LDA + 16 * k + 4 * kk + lq]; // X_kp[kk'][b]
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+            const double bv = (k == j) ? Xd[(j * 16 + 4 * kk + lq) * 17 + lr]           // X_jj[kk'][b]
+                                       : A[(16 * j + lr) * LDA + 16 * k + 4 * kk + lq]; // X_kj[kk'][b]
+            if (kk & 1) acc2 = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc2, 0, 0, 0);
+            else acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
         }
     }
-    f64x4 xo = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] += acc2[v];
+}
+// The sum comes out of the MFMA in the accumulator layout, which is the layout of a B operand:
+// register kk is S[4kk + lq][lr], so the product with -X_ii takes it as it stands.  The tile goes to
+// LDS for the rows below and, as tile (j, i) of R^-1 = X^T, to global memory: `out` points at that
+// tile ([k][c] row-major), `keep` has bit v set where entry (k = lr, c = lq + 4v) is neither beyond
+// the rank nor in a removed column.
+__device__ __forceinline__ void chol_inverse_store(double* A, const double* Xd, int LDA, int i, int j, int lr, int lq,
+                                                   const f64x4& acc, double* __restrict__ out, uint32_t keep)
+{
+    f64x4 xo = {0.0, 0.0, 0.0, 0.0}, xo2 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         const double av = -Xd[(i * 16 + lr) * 17 + 4 * kk + lq];                       // X_ii[a][k]
-        xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, acc[kk], xo, 0, 0, 0);
+        if (kk & 1) xo2 = __builtin_amdgcn_mfma_f64_16x16x4f64(av, acc[kk], xo2, 0, 0, 0);
+        else xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, acc[kk], xo, 0, 0, 0);
     }
 #pragma unroll
-    for (int v = 0; v < 4; ++v) A[(16 * p + lr) * LDA + 16 * i + lq + 4 * v] = xo[v];  // transposed
+    for (int v = 0; v < 4; ++v) {
+        xo[v] += xo2[v];
+        A[(16 * j + lr) * LDA + 16 * i + lq + 4 * v] = xo[v];                           // transposed
+        out[lr * 16 + lq + 4 * v] = ((keep >> v) & 1u) ? xo[v] : 0.0;
+    }
 }
 
 __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t T16)
@@ -603,35 +638,40 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
     const uint32_t nb = ta_.nb, r = grp.r;
     extern __shared__ double sm[];
     const int T = static_cast<int>(T16);
-    const int RPAD = 16 * T, LDA = RPAD + 1;
+    const int RPAD = 16 * T, LDA = RPAD + kCholPad;
     double* A = sm;                                   // [RPAD][LDA]: lower tiles L, upper tiles X^T
     double* Xd = A + RPAD * LDA;                      // [T][16][17]: inverses of the diagonal tiles
-    double* dsc = Xd + T * 16 * 17;                   // [RPAD] column scales
-    double* red = dsc + RPAD;                         // [kCholThreads] partial sums (single tile only)
-    uint32_t* deadmask = reinterpret_cast<uint32_t*>(red + kCholThreads);   // [T]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double* wd = Xd + T * 16 * 17;                    // [RPAD] kPivotEps W[c][c]: what the pivot of column c must exceed
+    double* red = wd + RPAD;                          // [kCholThreads] partial sums (single tile only)
+    uint32_t* deadw = reinterpret_cast<uint32_t*>(red + kCholThreads);   // [4]: bit c of the 128 set for a removed column c
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     constexpr int NW = kCholThreads / 64;
     const uint32_t ntile = T16 * (T16 + 1) / 2, ne = ntile * 256;
     const int lr = lane & 15, lq = lane >> 4;         // MFMA fragment coordinates
-
-    // ---- assemble the scaled Gram matrix C = D W D (lower triangle) ----
-    // Every thread's entries are requested at once (registers), the diagonal first for the scales.
+    // ---- the Gram matrix W (lower tiles, diagonal tiles whole) into LDS ----
+    // Every thread's entries are requested at once (registers).
     constexpr int kMaxPerThread = (36 * 256 + kCholThreads - 1) / kCholThreads;
     double wv[kMaxPerThread];
+    f64x4 st = {0.0, 0.0, 0.0, 0.0};                  // wavefront 0: the diagonal tile of the step at hand
+    if (tid < 4) deadw[tid] = 0u;
     if (nb == 1) {
 #pragma unroll
         for (int u = 0; u < kMaxPerThread; ++u) {
             const uint32_t e = tid + u * kCholThreads;
             wv[u] = tiles[e < ne ? e : 0];
         }
+        // wavefront 0 takes the first diagonal tile (tile 0, whole and symmetric) straight into the
+        // registers it factors it from: it does not wait for the other wavefronts' entries
+        if (wave == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) st[v] = tiles[(lq + 4 * v) * 16 + lr];
+        }
         for (int j = tid; j < RPAD; j += kCholThreads) {
             // W[j][j] sits in diagonal tile (t, t), t = j / 16, the tile of index t T - t (t - 1) / 2
             const int t = j >> 4, ti = t * T - t * (t - 1) / 2;
-            const double w = tiles[ti * 256 + (j & 15) * 17];
-            dsc[j] = (w > 0.0) ? rsqrt(w) : 0.0;
+            wd[j] = kPivotEps * tiles[ti * 256 + (j & 15) * 17];
         }
     }
-    for (int e = tid; e < RPAD * LDA; e += kCholThreads) A[e] = 0.0;
     if (nb > 1) {                                     // ne == 256: interleaved groups of blocks per entry
         constexpr uint32_t NG = kCholThreads / 256;
         const uint32_t e = tid & 255, grp = tid >> 8;
@@ -654,48 +694,113 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             red[tid] = t;
         }
         __syncthreads();
-        if (tid < 16) {
-            const double w = red[tid * 17];
-            dsc[tid] = (w > 0.0) ? rsqrt(w) : 0.0;
-        }
+        if (tid < 16) wd[tid] = kPivotEps * red[tid * 17];
         wv[0] = red[tid & 255];
     }
-    __syncthreads();
+    // Entry tid + u * kCholThreads sits in tile (wave / 4) + 4u, the same for a whole wavefront: the
+    // tile's place (ta <= tb) is kept in scalar registers and advanced four tiles at a time.  A tile
+    // holds [i][j] = W[16 tb + i][16 ta + j]: consecutive lanes write consecutive words, one LDS
+    // operation per entry (the block's sixteen wavefronts share one LDS pipeline, which is what the
+    // phases before and after the factorisation wait for).
+    {
+        int ta = 0, tb = wave >> 2;
+        const int i = (tid >> 4) & 15, j = tid & 15;
 #pragma unroll
-    for (int u = 0; u < kMaxPerThread; ++u) {
-        const uint32_t e = tid + u * kCholThreads;
-        if (e < ne && (nb == 1 || u == 0) && (nb == 1 || tid < 256)) {
-            int ta, tb;
-            tri_tile(static_cast<int>(e >> 8), T, ta, tb);
-            const int a = 16 * ta + ((e >> 4) & 15), b = 16 * tb + (e & 15);
-            if (a <= b) A[b * LDA + a] = wv[u] * (dsc[a] * dsc[b]);
+        for (int u = 0; u < kMaxPerThread; ++u) {
+            while (tb >= T && ta < T) { ++ta; tb = tb - T + ta; }   // row ta of the triangle has tiles tb = ta .. T-1
+            if (ta < T && (nb == 1 || u == 0)) A[(16 * tb + i) * LDA + 16 * ta + j] = wv[u];
+            tb += 4;
         }
     }
-    __syncthreads();
-
-    // ---- blocked right-looking Cholesky ----
-    for (int p = 0; p < T; ++p) {
-        const int j0 = 16 * p;
+    if (nb > 1) {
+        // a single tile summed in LDS: wavefront 0 takes it from there (its lower triangle mirrored)
+        __syncthreads();
         if (wave == 0) {
-            // the diagonal tile as a full symmetric tile (its lower triangle is what A holds)
-            f64x4 st, xt;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int a = lq + 4 * v, b = lr;                 // element [a][b]
-                st[v] = A[(j0 + max(a, b)) * LDA + j0 + min(a, b)];
+                st[v] = A[max(a, b) * LDA + min(a, b)];
             }
-            const uint32_t dead = chol16_factor_invert(st, xt, lane, red);
+        }
+    }
+
+    // ---- blocked right-looking Cholesky with the diagonal tile one step ahead ----
+    // The serial part is the chain of diagonal tiles, so wavefront 0 does nothing else: it factors
+    // tile (p, p), solves the one panel tile (p+1, p) below it, applies that tile's update to
+    // (p+1, p+1) in registers and goes on to factor it.  The other wavefronts solve the rest of
+    // panel p, update the rest of the trailing matrix and build X = L^-1 while wavefront 0 is on
+    // the next diagonal tile.  Two block barriers per step: after X_pp and after column p of L.
+    // Column j of X belongs to one wavefront, which carries the sum of a row's tile across steps:
+    // the terms k <= p - 1 of row p + 1 are added during step p (row p + 1 of L is final once
+    // panel p - 1 is), the term k = p and the product with X_(p+1)(p+1) during step p + 1.  The
+    // owners of the long columns sit on different SIMDs (wavefront w runs on SIMD w % 4), none on
+    // wavefront 0's.
+    int xcol = -1;
+    {
+        constexpr int owner[7] = {1, 2, 3, 7, 6, 5, 9};
+#pragma unroll
+        for (int j = 0; j < 7; ++j)
+            if (wave == owner[j]) xcol = j;
+    }
+    int uslot = -1;                                      // this wavefront's place among those that update
+    {
+        constexpr int worker[12] = {15, 14, 13, 11, 10, 9, 5, 6, 7, 3, 2, 1};
+#pragma unroll
+        for (int u = 0; u < 12; ++u)
+            if (wave == worker[u]) uslot = u;
+    }
+    f64x4 xacc = {0.0, 0.0, 0.0, 0.0};
+    if (wave == 0) __builtin_amdgcn_s_setprio(3);
+    for (int p = 0; p < T; ++p) {
+        const int j0 = 16 * p;
+        if (wave == 0) {
+            f64x4 xt;
+            const uint32_t dead = chol16_factor_invert(st, xt, lane, red, wd + j0);
 #pragma unroll
             for (int v = 0; v < 4; ++v) Xd[(p * 16 + lq + 4 * v) * 17 + lr] = xt[v];   // X[row][col]
-            if (lane == 0) deadmask[p] = dead;
-        } else if (p >= 2) {
-            // Beside the diagonal tile's serial factorisation the other wavefronts form row p-1 of
-            // X = L^-1: everything it needs (row p-1 of L, X_(p-1)(p-1), the rows of X above) is final.
-            for (int j = wave - 1; j < p - 1; j += NW - 1) chol_inverse_tile(A, Xd, LDA, p - 1, j, lr, lq);
+            if (lane == 0) deadw[p >> 1] |= dead << (16 * (p & 1));
         }
         __syncthreads();
-        // panel solve: L_ip = C_ip X_pp^T for tiles i > p
-        for (int i = p + 1 + wave; i < T; i += NW) {
+        // panel solve: L_ip = C_ip X_pp^T, tile i = p + 1 + wave (T <= 8: one tile per wavefront at most)
+        f64x4 lt = {0.0, 0.0, 0.0, 0.0};
+        if (wave == 0) {
+            if (p + 1 < T) {
+                // wavefront 0 forms its tile transposed, L^T = X_pp C^T: register v of lane (lr, lq) is
+                // L[lr][lq + 4v], which is the tile's own operand layout (k block v), so the update of
+                // the next diagonal tile takes it from registers
+                const int i0 = j0 + 16;
+                f64x4 lt2 = {0.0, 0.0, 0.0, 0.0};               // two chains: see chol_inverse_terms
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const double av = Xd[(p * 16 + lr) * 17 + 4 * kk + lq];       // X_pp[a = lr][k]
+                    const double bv = A[(i0 + lr) * LDA + j0 + 4 * kk + lq];      // C[b = lr][k]
+                    if (kk & 1) lt2 = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, lt2, 0, 0, 0);
+                    else lt = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, lt, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) lt[v] += lt2[v];
+                // C_(p+1)(p+1) as a full symmetric tile (its lower triangle is what A holds)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int a = lq + 4 * v, b = lr;
+                    st[v] = A[(i0 + max(a, b)) * LDA + i0 + min(a, b)];
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) A[(i0 + lr) * LDA + j0 + lq + 4 * v] = lt[v];
+            }
+        } else if (wave == NW - 1) {
+            // tile (p, p) of R^-1 = X_pp^T above the diagonal: [k][c] = X_pp[c][k] for k <= c
+            const uint32_t wp = deadw[p >> 1] >> (16 * (p & 1));
+            double* __restrict__ out = rinv + (p * T - p * (p - 1) / 2) * 256;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const uint32_t e = lane + 64 * v, kl = e >> 4, cc = e & 15;
+                const bool live = kl <= cc && 16 * p + cc < r && !((wp >> kl) & 1u) && !((wp >> cc) & 1u);
+                const double xv = Xd[(p * 16 + cc) * 17 + kl];
+                out[e] = live ? xv : 0.0;
+            }
+        } else if (p + 1 + wave < T) {
+            const int i = p + 1 + wave;
             f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
@@ -707,44 +812,57 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + j0 + lr] = acc[v];
         }
         __syncthreads();
-        // trailing update: C_ic -= L_ip L_cp^T for p < c <= i
-        const int rem = T - p - 1, npair = rem * (rem + 1) / 2;
-        for (int idx = wave; idx < npair; idx += NW) {
-            int ci, ii;                                  // (c, i) offsets with c <= i, row-major over the triangle
-            tri_tile(idx, rem, ci, ii);
-            const int c = p + 1 + ci, i = p + 1 + ii;
-            f64x4 acc;
+        if (wave == 0) {
+            if (p + 1 < T) {
+                // the next diagonal tile: C_(p+1)(p+1) - L_(p+1)p L_(p+1)p^T, kept in registers
+                f64x4 st2 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc[v] = A[(16 * i + lq + 4 * v) * LDA + 16 * c + lr];
+                for (int kk = 0; kk < 4; ++kk) {
+                    if (kk & 1) st2 = __builtin_amdgcn_mfma_f64_16x16x4f64(-lt[kk], lt[kk], st2, 0, 0, 0);
+                    else st = __builtin_amdgcn_mfma_f64_16x16x4f64(-lt[kk], lt[kk], st, 0, 0, 0);
+                }
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const double av = -A[(16 * i + lr) * LDA + j0 + 4 * kk + lq];
-                const double bv = A[(16 * c + lr) * LDA + j0 + 4 * kk + lq];  // L_cp[b = lr][k]
-                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                for (int v = 0; v < 4; ++v) st[v] += st2[v];
+            }
+        } else {
+            if (xcol >= 0 && xcol < p) {
+                // row p of X: the last term, k = p - 1, and the product with -X_pp
+                chol_inverse_terms(A, Xd, LDA, p, xcol, p - 1, p, lr, lq, xacc);
+                // entry (k, c) of R^-1 = X^T: k = 16 xcol + lr, c = 16 p + lq + 4v
+                const uint32_t wk = deadw[xcol >> 1] >> (16 * (xcol & 1)), wc = deadw[p >> 1] >> (16 * (p & 1));
+                uint32_t keep = 0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t cl = lq + 4 * v;
+                    if (16 * p + cl < r && !((wk >> lr) & 1u) && !((wc >> cl) & 1u)) keep |= 1u << v;
+                }
+                const int t = xcol * T - xcol * (xcol - 1) / 2 + (p - xcol);
+                chol_inverse_store(A, Xd, LDA, p, xcol, lr, lq, xacc, rinv + t * 256, keep);
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + 16 * c + lr] = acc[v];
+            for (int v = 0; v < 4; ++v) xacc[v] = 0.0;
+            if (xcol >= 0 && xcol < p && p + 1 < T)      // row p + 1 of X: the terms k <= p - 1
+                chol_inverse_terms(A, Xd, LDA, p + 1, xcol, xcol, p, lr, lq, xacc);
+            // trailing update: C_ic -= L_ip L_cp^T for p < c <= i, all but wavefront 0's tile (p+1, p+1),
+            // by the twelve wavefronts off wavefront 0's SIMD; those that own no column of X first
+            const int rem = T - p - 1, npair = rem * (rem + 1) / 2;
+            for (int idx = 1 + uslot; idx < npair && uslot >= 0; idx += 12) {
+                int ci, ii;                              // (c, i) offsets with c <= i, row-major over the triangle
+                tri_tile(idx, rem, ci, ii);
+                const int c = p + 1 + ci, i = p + 1 + ii;
+                f64x4 acc;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[v] = A[(16 * i + lq + 4 * v) * LDA + 16 * c + lr];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const double av = -A[(16 * i + lr) * LDA + j0 + 4 * kk + lq];
+                    const double bv = A[(16 * c + lr) * LDA + j0 + 4 * kk + lq];  // L_cp[b = lr][k]
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) A[(16 * i + lq + 4 * v) * LDA + 16 * c + lr] = acc[v];
+            }
         }
-        __syncthreads();
-    }
-
-    // the last row of the inverse, with every wavefront
-    for (int j = wave; j + 1 < T; j += NW) chol_inverse_tile(A, Xd, LDA, T - 1, j, lr, lq);
-    __syncthreads();
-
-    // ---- R^-1[k][c] = d_k X[c][k] for k <= c, zero elsewhere and for removed columns ----
-    const int sh = 31 - __clz(RPAD);                  // RPAD is a power of two
-    for (uint32_t e = tid; e < static_cast<uint32_t>(RPAD * RPAD); e += kCholThreads) {
-        const uint32_t k = e >> sh, c = e & (RPAD - 1);
-        if (k >= r || c >= r) continue;
-        double v = 0.0;
-        const bool dk = (deadmask[k >> 4] >> (k & 15)) & 1u, dc = (deadmask[c >> 4] >> (c & 15)) & 1u;
-        if (k <= c && !dk && !dc) {
-            const double xv = ((k >> 4) == (c >> 4)) ? Xd[((c >> 4) * 16 + (c & 15)) * 17 + (k & 15)]
-                                                     : A[k * LDA + c];
-            v = dsc[k] * xv;
-        }
-        rinv[static_cast<size_t>(k) * r + c] = v;
     }
 }
 
@@ -771,18 +889,11 @@ __global__ __launch_bounds__(64 * WAVES) void k_apply(const Group grp, uint32_t 
     const uint32_t row0 = (blockIdx.x - ta.first) * ROWS;
     // R^-1 goes to LDS once per block (all loads in flight together): the multiply below then
     // runs without a round trip to L2 per k step
-    {
-        const uint32_t e = tid & 255, kl = e >> 4, cc = e & 15;
+    // (k_chol wrote the tiles in this order, zero from rank r on)
 #pragma unroll
-        for (int t0 = 0; t0 < NTILE; t0 += NTH / 256) {
-            const int t = t0 + (tid >> 8);
-            if (t < NTILE) {
-                int tk, tc;
-                tri_tile(t, T16, tk, tc);
-                const uint32_t k = 16 * tk + kl, c = 16 * tc + cc;
-                Rs[t * 256 + e] = (k < r && c < r) ? rinv[static_cast<size_t>(k) * r + c] : 0.0;
-            }
-        }
+    for (int e0 = 0; e0 < NTILE * 256; e0 += NTH) {
+        const int e = e0 + tid;
+        if (e < NTILE * 256) Rs[e] = rinv[e];
     }
 #pragma unroll
     for (int it = 0; it < T16; ++it) {
@@ -2041,7 +2152,7 @@ static constexpr size_t deferred_narrow_lds()
 
 int prepare_compress_kernels(edgc_ctx* ctx)
 {
-    constexpr int chol_max = (128 * 129 + 8 * 16 * 17 + 128 + kCholThreads) * 8 + 64;
+    constexpr int chol_max = (128 * (128 + kCholPad) + 8 * 16 * 17 + 128 + kCholThreads) * 8 + (8 + 36) * 4;
     EDGC_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chol),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, chol_max));
     EDGC_HIP_TRY(ctx, (allow_lds_pass_q<1, 4, 2>()));
@@ -2263,7 +2374,7 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
         bytes += 8.0 * ne * t.nb + 8.0 * r * r;
     }
     const size_t rpad = 16 * t16;
-    const size_t chol_lds = (rpad * (rpad + 1) + t16 * 16 * 17 + rpad + kCholThreads) * sizeof(double) + t16 * sizeof(uint32_t);
+    const size_t chol_lds = (rpad * (rpad + kCholPad) + t16 * 16 * 17 + rpad + kCholThreads) * sizeof(double) + (8 + 36) * sizeof(uint32_t);
     EDGC_LAUNCH(ctx, st, KID_CHOL, bytes, g.count * 2.0 * r * r * r / 3.0,
                 k_chol<<<g.count, kCholThreads, chol_lds, st>>>(g, t16));
     EDGC_HIP_TRY(ctx, hipGetLastError());

@@ -104,7 +104,7 @@ extern "C" int edgc_create(edgc_ctx** out, int hip_device, uint32_t max_bins, ui
     ok = ok && dev_alloc(&s.part, s.part_elems) == hipSuccess;
     ok = ok && dev_alloc(&s.gram_part, s.gram_part_elems) == hipSuccess;
     ok = ok && dev_alloc(&s.gram, static_cast<size_t>(36) * 256) == hipSuccess;
-    ok = ok && dev_alloc(&s.rinv, static_cast<size_t>(max_rank) * max_rank) == hipSuccess;
+    ok = ok && dev_alloc(&s.rinv, rinv_elems(max_rank)) == hipSuccess;
     ok = ok && hipMalloc(&s.pt, s.pt_bytes) == hipSuccess;
     ok = ok && hipMemset(s.done_counter, 0, 4 * sizeof(unsigned int)) == hipSuccess;
     ok = ok && hipMemset(s.wide, 0, 65536 * sizeof(unsigned long long)) == hipSuccess;
@@ -444,7 +444,7 @@ extern "C" int edgc_reserve_batch(edgc_ctx* ctx, const uint32_t* rows, const uin
         ok = ok && dev_alloc(&b.part, b.cap.part_elems) == hipSuccess;
         ok = ok && dev_alloc(&b.gram_part, b.cap.gram_part_elems) == hipSuccess;
         ok = ok && dev_alloc(&b.gram, static_cast<size_t>(36) * 256) == hipSuccess;
-        ok = ok && dev_alloc(&b.rinv, static_cast<size_t>(ctx->max_rank) * ctx->max_rank) == hipSuccess;
+        ok = ok && dev_alloc(&b.rinv, rinv_elems(ctx->max_rank)) == hipSuccess;
         ok = ok && hipMalloc(&b.pt, 2ull * rp * rows_pad * 2ull) == hipSuccess;
     }
     if (!ok) {

@@ -29,12 +29,19 @@ struct Scratch {
     double* gram_part = nullptr;   // [gram_blocks][rank_pad*rank_pad]
     size_t  gram_part_elems = 0;
     double* gram      = nullptr;   // [rank_pad*rank_pad]
-    double* rinv      = nullptr;   // [rank_pad*rank_pad]
+    double* rinv      = nullptr;   // rinv_elems(max_rank): upper-triangle tiles of R^-1
     void*   pt        = nullptr;   // operand copy of P^ transposed: [planes][rank_pad][rows_pad] bf16
     size_t  pt_bytes  = 0;
 };
 
 constexpr int kMaxReduceBlocks = 4096;
+
+// Doubles behind `rinv`: the upper-triangle 16x16 tiles of R^-1 for a rank padded to a multiple of 16
+inline size_t rinv_elems(uint32_t max_rank)
+{
+    const size_t t = (static_cast<size_t>(max_rank) + 15) / 16;
+    return t * (t + 1) / 2 * 256;
+}
 
 // Largest row count, column count or leading dimension of a compressed matrix: the kernels keep
 // lane offsets of up to four rows (4 * leading dimension + column) in 32 bits.
@@ -57,7 +64,7 @@ struct TensorArgs {
     float*  part;           // split partials: [S][rows][rank_pad]
     double* gram_part;      // per-block upper-triangle Gram tiles
     double* gram;           // summed Gram tiles
-    double* rinv;           // r x r inverse factor
+    double* rinv;           // inverse factor R^-1: upper-triangle 16x16 tiles, row-major over (tk <= tc)
     void*   pt;             // transposed bf16 copy of P^: [planes][rank_pad][m_pad]
     const double* tiles;    // what k_chol reads: gram_part (nb sets) or gram (one set)
     uint64_t ldg, ldo;
