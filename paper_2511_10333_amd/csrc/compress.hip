@@ -2380,8 +2380,15 @@ static int run_orthonormalise(edgc_ctx* ctx, Group& g, const TensorScratch* cap,
     EDGC_HIP_TRY(ctx, hipGetLastError());
 
     // P^ = P R^-1 and its transposed bf16 copy.  Above rank 64 the 72 KB of R^-1 tiles leave room for one
-    // block per CU: blocks of 128 rows then keep a group's blocks within one round over the CUs
-    const uint32_t apply_rows = (t16 == 8 && ctx->tune_apply != 4) ? 128u : 64u;
+    // block per CU, and a block's time is its share of fp64 MFMA work (144 per 16 rows, on four SIMDs):
+    // blocks of 64 rows while they fit in one round over the CUs, of 128 rows otherwise
+    uint32_t apply_rows = 64;
+    if (t16 == 8) {
+        uint32_t b64 = 0;
+        for (uint32_t i = 0; i < g.count; ++i) b64 += cdiv(g.t[i].m_pad, 64u);
+        apply_rows = ctx->tune_apply == 4 ? 64u : ctx->tune_apply == 8 ? 128u
+                   : (b64 <= static_cast<uint32_t>(ctx->num_cu) ? 64u : 128u);
+    }
     blocks = 0;
     bytes = flops = 0.0;
     for (uint32_t i = 0; i < g.count; ++i) {

@@ -146,7 +146,7 @@ struct edgc_ctx {
     int tune_pwaves = -1;   // waves per block of that kernel: -1 built-in choice (8 above rank 64), 4 or 8
     int tune_qfull = -1;    // Q-pass of whole-tile groups: -1 built-in choice; 0 the general kernel; 4 / 8 the
                             // pipelined kernel with that many waves per block
-    int tune_apply = -1;    // k_apply above rank 64: 4 keeps four waves (64 rows) per block
+    int tune_apply = -1;    // k_apply above rank 64: 4 = four waves (64 rows) per block, 8 = eight (128 rows)
     int tune_ept = 0;       // items per thread of the histogram of a small sample (the range pass takes twice as many)
     int tune_pattern = 1;   // entropy estimate: 1 one read into 16-bit counters per block where that applies
                             // (bf16 samples, fp32 on more than 16384 bins); 0 the plain kernels only; 3 as 1,
