@@ -156,6 +156,39 @@ def test_rank_deficient_input_compares_reconstruction_only():
     check_step(M, None, _q0(256, 8), 8, "f32", compare_factors=False)
 
 
+@pytest.mark.parametrize("m,n,r,dups", [
+    # (column, the earlier column it repeats): in several blocks of four pivots and several 16-column tiles,
+    # the last column among them
+    (256, 320, 48, [(5, 2), (17, 3), (18, 16), (33, 1), (47, 40)]),
+    (512, 640, 128, [(3, 0), (16, 15), (63, 20), (64, 63 - 1), (100, 99), (126, 7), (127, 125)]),
+    (384, 256, 100, [(31, 30), (32, 31 - 1), (96, 50), (99, 98)]),
+])
+def test_repeated_start_columns_are_removed_and_the_rest_is_the_smaller_problem(m, n, r, dups):
+    # Q0 with columns that repeat earlier ones: P = D Q0 has exactly dependent columns, whose pivots
+    # the orthonormalisation must find zero.  Those columns of P^ and Q are exact zeros, and what is
+    # left is the step at the smaller rank with the repeats taken out, which the oracle computes
+    # (it would normalise the rounding noise a repeat leaves behind, a valid but different factor).
+    G = gen.lowrank_plus_noise(m, n, 3 * r // 2, 0.97, 1e-3, seed=21)
+    Q0 = _q0(n, r, seed=5)
+    for c, o in dups:
+        Q0[:, c] = Q0[:, o]
+    dead = sorted(c for c, _ in dups)
+    live = [c for c in range(r) if c not in dead]
+    Pg, Qg, Dg, _ = gpu_compress(G, None, Q0, r)
+    assert not Pg[:, dead].any() and not Qg[:, dead].any(), "a repeated column leaves a zero column in P^ and Q"
+    Po, Qo, Do = orc.compress(G, None, np.ascontiguousarray(Q0[:, live]), len(live), 1)
+    assert np.array_equal(Dg, Do)
+    tol = TOL["f32"]
+    assert rel_fro(Pg[:, live], Po) <= tol, f"P^ off by {rel_fro(Pg[:, live], Po):.2e}"
+    assert rel_fro(Qg[:, live], Qo) <= tol, f"Q off by {rel_fro(Qg[:, live], Qo):.2e}"
+    gram = Pg[:, live].astype(np.float64).T @ Pg[:, live].astype(np.float64)
+    assert np.abs(gram - np.eye(len(live))).max() < 1e-5
+    out_o, E_o = orc.decompress(Po, Qo, Do, orc.F32)
+    out_g, E_g = gpu_decompress(Pg, Qg, Dg, "f32", r)
+    assert rel_fro(out_g, out_o) <= tol
+    assert np.array_equal(E_g, Dg - out_g)
+
+
 def test_zero_matrix():
     Z = np.zeros((128, 192), dtype=np.float32)
     Pg, Qg, Dg, _ = gpu_compress(Z, None, _q0(192, 4), 4)
