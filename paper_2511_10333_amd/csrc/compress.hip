@@ -731,8 +731,9 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
     // panel p, update the rest of the trailing matrix and build X = L^-1 while wavefront 0 is on
     // the next diagonal tile.  Two block barriers per step: after X_pp and after column p of L.
     // Column j of X belongs to one wavefront, which carries the sum of a row's tile across steps:
-    // the terms k <= p - 1 of row p + 1 are added during step p (row p + 1 of L is final once
-    // panel p - 1 is), the term k = p and the product with X_(p+1)(p+1) during step p + 1.  The
+    // the sum of row p + 1 is formed during step p (row p + 1 of L is final once panel p is, and the
+    // tiles of X it takes are this wavefront's own), the product with X_(p+1)(p+1), which is all that
+    // is left after the last diagonal tile, during step p + 1.  The
     // owners of the long columns sit on different SIMDs (wavefront w runs on SIMD w % 4), none on
     // wavefront 0's.
     int xcol = -1;
@@ -826,8 +827,7 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             }
         } else {
             if (xcol >= 0 && xcol < p) {
-                // row p of X: the last term, k = p - 1, and the product with -X_pp
-                chol_inverse_terms(A, Xd, LDA, p, xcol, p - 1, p, lr, lq, xacc);
+                // row p of X: the sum was formed during step p - 1; the product with -X_pp
                 // entry (k, c) of R^-1 = X^T: k = 16 xcol + lr, c = 16 p + lq + 4v
                 const uint32_t wk = deadw[xcol >> 1] >> (16 * (xcol & 1)), wc = deadw[p >> 1] >> (16 * (p & 1));
                 uint32_t keep = 0;
@@ -841,8 +841,8 @@ __global__ __launch_bounds__(kCholThreads) void k_chol(const Group grp, uint32_t
             }
 #pragma unroll
             for (int v = 0; v < 4; ++v) xacc[v] = 0.0;
-            if (xcol >= 0 && xcol < p && p + 1 < T)      // row p + 1 of X: the terms k <= p - 1
-                chol_inverse_terms(A, Xd, LDA, p + 1, xcol, xcol, p, lr, lq, xacc);
+            if (xcol >= 0 && xcol <= p && p + 1 < T)     // row p + 1 of X: the whole sum, k = xcol .. p
+                chol_inverse_terms(A, Xd, LDA, p + 1, xcol, xcol, p + 1, lr, lq, xacc);
             // trailing update: C_ic -= L_ip L_cp^T for p < c <= i, all but wavefront 0's tile (p+1, p+1),
             // by the twelve wavefronts off wavefront 0's SIMD; those that own no column of X first
             const int rem = T - p - 1, npair = rem * (rem + 1) / 2;
