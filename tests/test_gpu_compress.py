@@ -117,6 +117,16 @@ def test_shapes_tiles_and_ragged_tails(dtype, m, n, r):
     check_step(G, E, _q0(n, r), r, dtype)
 
 
+@pytest.mark.parametrize("r", [15, 17, 31, 33, 63, 65, 97, 127])
+def test_ranks_next_to_the_tile_edges_of_the_factorisation(r):
+    # one column short of, and one past, a whole number of the 16-column tiles the Gram matrix is
+    # factored in (and of the 32-column rank tiles of the passes): the padding columns must stay out
+    G = gen.lowrank_plus_noise(320, 448, 160, 0.97, 1e-3, seed=r)
+    Pg, Qg, out, E = check_step(G, None, _q0(448, r), r, "f32")
+    P64 = Pg.astype(np.float64)
+    assert np.abs(P64.T @ P64 - np.eye(r)).max() < 1e-5
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_strided_gradient_rows(dtype):
     G = gen.lowrank_plus_noise(192, 320, 32, 0.9, 1e-4, seed=5, dtype=dtype)
