@@ -217,8 +217,9 @@ int edgc_init_q(edgc_ctx* ctx, float* Q, uint32_t n, uint32_t ldq, uint32_t col_
  * Errors: EDGC_EINVAL for null pointers, r == 0, r > min(m, n), r > max_rank,
  * m > max_rows, n > max_cols, ld < n, ldp/ldq < r, power_iters == 0, or P/Q
  * not 16-byte aligned with ldp/ldq multiples of 4.
- * A column of P that is numerically dependent on the previous ones (pivot of
- * the scaled Gram matrix below 1e-11) is set to zero. */
+ * A column of P that is numerically dependent on the previous ones (its Cholesky
+ * pivot not above 1e-11 times the column's squared norm, i.e. the pivot of the
+ * Gram matrix scaled to a unit diagonal not above 1e-11) is set to zero. */
 int edgc_compress(edgc_ctx* ctx, const void* grad, edgc_dtype dtype, uint32_t m, uint32_t n,
                   uint64_t ld, float* residual, int residual_is_zero, float* Q, uint32_t ldq,
                   float* P, uint32_t ldp, uint32_t r, uint32_t power_iters, void* hip_stream);
